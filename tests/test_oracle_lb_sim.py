@@ -1,0 +1,229 @@
+"""Pins for the CPU oracle's lower bound and online iteration simulator (no GPU).
+
+Lower bound: paper section "Offline requests scheduling & theoretical lower bound"
+(T^LB = t^p* + t^d*, t^p* = T^p_L floor(sum N^p_i / N^cap_L)).  Simulator: decision rule of
+section "Online requests and iteration scheduling", time model of section "Experiment
+settings and baseline".
+"""
+import os
+import struct
+
+import numpy as np
+import pytest
+
+from paper_2502_15763_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "time_model_examples.txt")
+PAPER_US = dict(cap=200, a_prefill=130, b_decode=210, c_prefill=25000, c_decode=29000, max_prefill_tokens=0)
+
+
+# ------------------------------------------------------------------ lower bound
+def test_lb_closed_forms(oracle):
+    rng = np.random.default_rng(3)
+    # N <= M: LB = OPT = largest cost
+    c = rng.integers(1, 100, size=(5, 4)).astype(np.int64)
+    lb = oracle.lower_bound(c, 6)["lb"]
+    assert lb.tolist() == c.max(axis=1).tolist()
+    for s in range(5):
+        assert oracle.brute_force_opt(c[s], 6, 1) == int(lb[s])
+    # equal costs, M | N: LB = OPT = c*N/M
+    c = np.full((1, 12), 7, np.int64)
+    assert int(oracle.lower_bound(c, 4)["lb"][0]) == 21
+    # N = M+1: OPT = max(c_(1), c_(M)+c_(M+1)) = LB
+    for _ in range(10):
+        c = rng.integers(1, 60, size=(1, 5)).astype(np.int64)
+        s = np.sort(c[0])[::-1]
+        expect = max(int(s[0]), int(s[3] + s[4]))
+        assert int(oracle.lower_bound(c, 4)["lb"][0]) == expect == oracle.brute_force_opt(c[0], 4, 5)
+    # ceil of the average: 3 jobs of 1 on 2 clients, plus a check where L1 dominates
+    assert int(oracle.lower_bound(np.array([[5, 5, 5, 5, 1]], np.int64), 2)["lb"][0]) == 11
+
+
+def test_lb_below_bruteforce_opt(oracle):
+    rng = np.random.default_rng(5)
+    for N, M in [(7, 2), (8, 3), (9, 4), (10, 3)]:
+        for _ in range(8):
+            c = rng.integers(0, 40, size=(1, N)).astype(np.int64)
+            assert int(oracle.lower_bound(c, M)["lb"][0]) <= oracle.brute_force_opt(c[0], M, N)
+
+
+def test_lb_prefill_term(oracle):
+    # worked example of the paper's time model: a prefill bin of 5000 tokens takes 675 ms;
+    # sum N^p = 5000..9999 with N^cap_L = 5000 -> floor = 1 -> t^p* = 675 ms
+    c = np.array([[10, 10]], np.int64)
+    base = int(oracle.lower_bound(c, 2)["lb"][0])
+    for tok, k in [((2500, 2500), 1), ((4999, 5000), 1), ((5000, 5000), 2), ((2499, 2500), 0)]:
+        r = oracle.lower_bound(c, 2, prefill_tokens=np.array([tok], np.int32), ncap_L=5000, tp_L=675000)
+        assert int(r["lb"][0]) == base + 675000 * k
+    # disabled when ncap_L == 0
+    r = oracle.lower_bound(c, 2, prefill_tokens=np.array([[9000, 9000]], np.int32), ncap_L=0, tp_L=675000)
+    assert int(r["lb"][0]) == base
+
+
+def test_lb_bad_cost(oracle):
+    r = oracle.lower_bound(np.array([[1, -1], [2, 2]], np.int64), 2)
+    assert r["status"].tolist() == [3, 0] and r["lb"].tolist() == [0, 2]
+
+
+# ------------------------------------------------------------------ simulator
+def test_time_model_worked_examples(oracle):
+    with open(GOLD) as f:
+        rows = [l.split("|") for l in f if l.strip() and not l.startswith("#")]
+    assert len(rows) == 2
+    for kind, units, expect in rows:
+        fn = oracle.decode_time if kind.strip() == "decode" else oracle.prefill_time
+        assert fn(PAPER_US, int(units)) == int(expect)
+    # and through the simulator itself: 200 requests of 25 input tokens (5000 tokens), 1 output token each
+    arr = np.zeros((1, 200), np.int64)
+    r = oracle.online_iter_sim(arr, np.full((1, 200), 25, np.int32), np.ones((1, 200), np.int32), PAPER_US)
+    assert int(r["total_us"][0]) == 675000 + 71000
+    assert (r["finish_us"][0] == 746000).all()
+
+
+def _params(cap, a=35, b=900, cp=5000, cd=5000, tok=0):
+    return dict(cap=cap, a_prefill=a, b_decode=b, c_prefill=cp, c_decode=cd, max_prefill_tokens=tok)
+
+
+def test_sim_single_request(oracle):
+    p = _params(4)
+    r = oracle.online_iter_sim(np.array([[1234]], np.int64), np.array([[100]], np.int32), np.array([[7]], np.int32), p,
+                               trace_scenarios=1, trace_capacity=8)
+    expect = 1234 + (35 * 100 + 5000) + 7 * (900 + 5000)
+    assert int(r["total_us"][0]) == expect == int(r["finish_us"][0, 0])
+    assert int(r["busy_slot_us"][0]) == expect - 1234
+    assert int(r["n_prefill_iter"][0]) == 1 and int(r["n_decode_iter"][0]) == 7
+    tr = r["trace"][0][: int(r["trace_len"][0])]
+    assert [tuple(x) for x in tr.tolist()] == [(2, 1, 0, 0), (1, 1, 1234, 100), (0, 7, 1234 + 8500, 1)]
+
+
+def test_sim_batch_at_time_zero(oracle):
+    rng = np.random.default_rng(2)
+    n, L = 6, 9
+    in_len = rng.integers(1, 300, size=(1, n)).astype(np.int32)
+    p = _params(8)
+    r = oracle.online_iter_sim(np.zeros((1, n), np.int64), in_len, np.full((1, n), L, np.int32), p)
+    expect = 35 * int(in_len.sum()) + 5000 + L * (900 * n + 5000)
+    assert int(r["total_us"][0]) == expect
+    assert (r["finish_us"][0] == expect).all()
+
+
+def test_sim_cap_one_is_serial_fcfs(oracle):
+    rng = np.random.default_rng(4)
+    N = 40
+    arr = np.cumsum(rng.integers(0, 30000, size=(1, N)), axis=1).astype(np.int64)
+    in_len = rng.integers(1, 200, size=(1, N)).astype(np.int32)
+    out_len = rng.integers(1, 20, size=(1, N)).astype(np.int32)
+    p = _params(1)
+    r = oracle.online_iter_sim(arr, in_len, out_len, p)
+    t = 0
+    for i in range(N):
+        t = max(t, int(arr[0, i])) + 35 * int(in_len[0, i]) + 5000 + int(out_len[0, i]) * (900 + 5000)
+        assert int(r["finish_us"][0, i]) == t
+    assert int(r["total_us"][0]) == t
+
+
+def _fnv(data):
+    h = 0xcbf29ce484222325
+    for b in data:
+        h = ((h ^ b) * 0x100000001b3) & 0xFFFFFFFFFFFFFFFF
+    return h
+
+
+def test_fnv_published_vectors(oracle):
+    assert oracle.fnv1a64(b"") == 0xcbf29ce484222325
+    assert oracle.fnv1a64(b"a") == 0xaf63dc4c8601ec8c
+    assert oracle.fnv1a64(b"foobar") == 0x85944171f73967e8
+
+
+@pytest.mark.parametrize("tok_cap", [0, 600])
+def test_sim_conservation_and_trace(oracle, tok_cap):
+    c5 = W.config5(S=6, N=300)
+    p = dict(c5.params)
+    p["cap"] = 16
+    p["max_prefill_tokens"] = tok_cap
+    r = oracle.online_iter_sim(c5.arrival_us, c5.in_len, c5.out_len, p, trace_scenarios=6, trace_capacity=4000)
+    assert (r["status"] == 0).all()
+    a, b, cp, cd = p["a_prefill"], p["b_decode"], p["c_prefill"], p["c_decode"]
+    for s in range(6):
+        n = int(r["trace_len"][s])
+        assert n <= 4000
+        tr = r["trace"][s][:n]
+        dec = tr[tr["kind"] == 0]
+        pre = tr[tr["kind"] == 1]
+        # conservation: every output token decoded once, every request prefilled once
+        assert int((dec["count"].astype(np.int64) * dec["x"]).sum()) == int(c5.out_len[s].sum())
+        assert int(pre["count"].sum()) == 300
+        assert int(pre["x"].sum()) == int(c5.in_len[s].sum())
+        assert int(dec["x"].max()) <= 16 and int(pre["count"].max()) <= 16
+        assert int(dec["count"].sum()) == int(r["n_decode_iter"][s]) and len(pre) == int(r["n_prefill_iter"][s])
+        if tok_cap:
+            multi = pre[pre["count"] > 1]
+            assert (multi["x"] <= tok_cap).all()
+        # a prefill is always followed by a decode; merged decode runs are maximal
+        kinds = tr["kind"].tolist()
+        for q in range(n - 1):
+            if kinds[q] == 1:
+                assert kinds[q + 1] == 0
+            if kinds[q] == 0 and kinds[q + 1] == 0:
+                assert tr["x"][q] != tr["x"][q + 1]
+        # time is the sum of the iteration times (+ idle gaps), busy slot time likewise
+        t, busy = 0, 0
+        for k, cnt, ts, x in tr.tolist():
+            if k == 2:
+                assert ts == t
+                nxt = c5.arrival_us[s][c5.arrival_us[s] > t].min()
+                t = int(nxt)
+                continue
+            assert ts == t
+            if k == 1:
+                dt = a * x + cp
+                t += dt
+                busy += cnt * dt
+            else:
+                dt = b * x + cd
+                t += cnt * dt
+                busy += cnt * x * dt
+        assert t == int(r["total_us"][s]) == int(r["finish_us"][s].max())
+        assert busy == int(r["busy_slot_us"][s])
+        # no request finishes faster than running alone
+        lo = c5.arrival_us[s] + a * c5.in_len[s] + cp + c5.out_len[s].astype(np.int64) * (b + cd)
+        assert (r["finish_us"][s] >= lo).all()
+        # hash of the canonical records, recomputed independently
+        data = b"".join(struct.pack("<IIqq", *rec) for rec in tr.tolist())
+        assert _fnv(data) == int(r["trace_hash"][s])
+
+
+def test_sim_decision_rule_direction(oracle):
+    """C_p >= C_d keeps decoding (ties included); the first strictly larger C_d triggers the prefill.
+    One long request runs alone (D = 1, C_d grows by b per iteration); a second one waits."""
+    b = 1000
+    for cp_tokens, cfix in [(10, 0), (3, 2000)]:
+        p = _params(2, a=500, b=b, cp=cfix, cd=0)
+        Cp = 500 * cp_tokens + cfix          # 5000 / 3500
+        arr = np.array([[0, 1]], np.int64)
+        r = oracle.online_iter_sim(arr, np.array([[1, cp_tokens]], np.int32), np.array([[50, 1]], np.int32), p,
+                                   trace_scenarios=1, trace_capacity=16)
+        tr = [tuple(x) for x in r["trace"][0][: int(r["trace_len"][0])].tolist()]
+        # decode iterations with D=1 before the second prefill: smallest m with m*b > Cp
+        m = Cp // b + 1
+        assert tr[0] == (1, 1, 0, 1)
+        assert tr[1][0] == 0 and tr[1][1] == m and tr[1][3] == 1
+        assert tr[2][0] == 1 and tr[2][3] == cp_tokens
+
+
+def test_sim_oversized_head_request_still_admitted(oracle):
+    p = _params(4, tok=100)
+    r = oracle.online_iter_sim(np.zeros((1, 3), np.int64), np.array([[500, 60, 60]], np.int32),
+                               np.array([[2, 2, 2]], np.int32), p, trace_scenarios=1, trace_capacity=16)
+    tr = [tuple(x) for x in r["trace"][0][: int(r["trace_len"][0])].tolist()]
+    assert tr[0] == (1, 1, 0, 500)           # alone, although above the token cap
+    assert int(r["status"][0]) == 0
+
+
+def test_sim_bad_input(oracle):
+    arr = np.array([[0, 5, 3], [0, 1, 2], [0, 1, 2], [0, 1, 2]], np.int64)
+    inl = np.array([[1, 1, 1], [1, 0, 1], [1, 1, 1], [1, 1, 1]], np.int32)
+    outl = np.array([[1, 1, 1], [1, 1, 1], [1, 1, 0], [1, 1, 1]], np.int32)
+    r = oracle.online_iter_sim(arr, inl, outl, _params(2))
+    assert r["status"].tolist() == [4, 4, 4, 0]
+    assert (r["finish_us"][:3] == 0).all() and (r["total_us"][:3] == 0).all()
