@@ -1,0 +1,153 @@
+/*
+ * libmmbp -- batched Minimizing Makespan Bin Packing (MMBP) local search, theoretical lower
+ * bound and online iteration-scheduling simulator for gfx950 (MI355X).
+ *
+ * Vocabulary follows the paper's problem statement: requests i with N^p_i input and N^d_i
+ * output tokens, clients / instances j (M of them), estimated completion cost T_i, per-client
+ * load t_j, prefill / decode time per token T^p / T^d.
+ *
+ * Conventions for every entry point
+ *   - plain C ABI; all array arguments are DEVICE pointers owned by the caller unless the
+ *     comment says "host"; the library never frees or keeps them;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *     asynchronously on it; the library never synchronises the stream, so outputs are valid
+ *     once the caller has synchronised;
+ *   - return value: 0 = enqueued; negative = MMBP_E* (nothing was enqueued);
+ *   - conditions only visible on the device are reported per scenario in `status_out`
+ *     (MMBP_ST_*).  Scenarios are independent: a bad one does not affect the others.
+ */
+#ifndef MMBP_H
+#define MMBP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* return codes */
+#define MMBP_OK            0
+#define MMBP_EINVAL       -1  /* null pointer, non-positive size, bad dtype, negative max_passes */
+#define MMBP_EINFEASIBLE  -2  /* N > M * cap: no assignment satisfies the cardinality limit */
+#define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 64) */
+#define MMBP_EWORKSPACE   -4  /* workspace missing or smaller than mmbp_workspace_bytes() */
+#define MMBP_EHIP         -5  /* a HIP call or kernel launch failed; see mmbp_strerror() */
+
+/* per-scenario status */
+#define MMBP_ST_OK            0  /* converged: a full scan found no improving candidate */
+#define MMBP_ST_TRUNCATED     1  /* max_passes reached before a scan proved local optimality */
+#define MMBP_ST_BAD_ASSIGN    2  /* assign entry outside [0,M) or more than cap jobs on a client */
+#define MMBP_ST_BAD_COST      3  /* negative cost, or sum of costs >= 2^62 */
+#define MMBP_ST_BAD_SIM_INPUT 4  /* arrival negative or decreasing, in_len < 1, out_len < 1 */
+
+/* cost element type */
+#define MMBP_I32 0
+#define MMBP_I64 1
+
+#define MMBP_MAX_N (1 << 20)
+#define MMBP_MAX_M 256
+#define MMBP_SIM_MAX_CAP 64
+
+int mmbp_version(void);
+
+/* Text for a return code; for MMBP_EHIP the text of the last failing HIP call of this thread.
+ * The pointer is to static / thread-local storage. */
+const char *mmbp_strerror(int code);
+
+/*
+ * Scratch needed by mmbp_local_search for these shapes (bytes of device memory, 256-byte
+ * aligned base expected).  Returns 0 when every scenario is searched entirely out of the
+ * LDS of one workgroup; larger N uses the multi-workgroup path whose layout, per-row minima
+ * and global argmin slots live in the workspace.
+ */
+size_t mmbp_workspace_bytes(int S, int N, int M);
+
+/*
+ * Theoretical lower bound, paper section "Offline requests scheduling & theoretical lower
+ * bound": T^LB = t^p* + t^d*.
+ *   t^d* (optimum of the MMBP model) is replaced by the largest of three relaxation bounds,
+ *        ceil(sum_i T_i / M), max_i T_i, and T_(M) + T_(M+1) (costs in descending order, N > M);
+ *   t^p* = tp_L * floor(sum_i prefill_tokens_i / ncap_L)  (the paper's floor form with the
+ *        largest level L), added only when prefill_tokens != NULL and ncap_L > 0.
+ * cost            [S,N] int32 or int64 per `dtype`, T_i >= 0
+ * prefill_tokens  [S,N] int32 N^p_i, nullable
+ * lb_out          [S] int64
+ * status_out      [S] int32: MMBP_ST_OK or MMBP_ST_BAD_COST (then lb_out = 0)
+ */
+int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M,
+                     const int32_t *prefill_tokens, int64_t ncap_L, int64_t tp_L,
+                     int64_t *lb_out, int32_t *status_out, void *stream);
+
+/*
+ * Best-improvement local search on the MMBP model (same section: min max_j t_j, every request
+ * on exactly one client, t_j = sum of the T_i assigned to j), with at most `cap` requests per
+ * client.  Each pass evaluates the makespan that EVERY candidate would give,
+ *   move  (i -> b),  b != assign[i], feasible iff count(b) + 1 <= cap,   id = i*M + b
+ *   swap  (i <-> k), i < k, assign[i] != assign[k],                      id = N*M + i*N + k
+ * takes the candidate with the smallest (makespan, id) and applies it if it lowers the
+ * makespan; otherwise the search stops (MMBP_ST_OK).  It also stops after max_passes applied
+ * candidates (MMBP_ST_TRUNCATED; max_passes = 0 only reports the loads of the start).
+ * cost         [S,N] int32 / int64 per `dtype`
+ * assign       [S,N] int32, in: feasible start, out: result (untouched for bad scenarios)
+ * load_out     [S,M] int64 t_j of the result;  makespan_out [S] int64;  passes_out [S] int32
+ * evals_out    [S] uint64, nullable: candidates enumerated over all scans, counting capacity-
+ *              infeasible moves, not counting b == assign[i] nor same-client pairs
+ * applied_log  [S,max_passes] uint64, nullable: id applied in each pass (rest untouched)
+ * status_out   [S] int32.  For MMBP_ST_BAD_*: load/makespan/passes/evals are 0.
+ * workspace    device scratch of at least mmbp_workspace_bytes(S,N,M) bytes (may be NULL if 0)
+ */
+int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+                      int32_t *assign, int64_t *load_out, int64_t *makespan_out,
+                      int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
+                      int32_t *status_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Parameters of the iteration simulator (HOST struct).  Times in integer microseconds.
+ * Affine time model of the paper's section "Experiment settings and baseline":
+ * a prefill iteration over P tokens takes a_prefill*P + c_prefill, a decode iteration over D
+ * running requests takes b_decode*D + c_decode. */
+typedef struct mmbp_sim_params {
+    int32_t cap;                /* batch size |J|: requests processed simultaneously, 1..64 */
+    int32_t reserved;           /* must be 0 */
+    int64_t a_prefill;          /* T^p per token */
+    int64_t b_decode;           /* T^d per token (one token per running request per round) */
+    int64_t c_prefill;          /* fixed prefill overhead */
+    int64_t c_decode;           /* fixed decode overhead */
+    int64_t max_prefill_tokens; /* token capacity of a prefill iteration; <= 0: unlimited */
+} mmbp_sim_params;
+
+/* One canonical trace record (24 bytes, little endian). kind 0 = DECODE run (count iterations
+ * with x = D running requests each), 1 = PREFILL (count = requests admitted, x = tokens P),
+ * 2 = IDLE jump to the next arrival (count 1, x 0). */
+typedef struct mmbp_trace_rec {
+    uint32_t kind, count;
+    int64_t t_start, x;
+} mmbp_trace_rec;
+
+/*
+ * Iteration-level simulation of one node under PD competition (an iteration is either a
+ * prefill or a decode), paper section "Online requests and iteration scheduling": at every
+ * iteration boundary the admissible requests (FCFS prefix of the arrived ones that fits the
+ * free slots and the token capacity) define the prefill cost C_p = a_prefill*P + c_prefill;
+ * the waited decode time C_d is b_decode times the tokens decoded since the last prefill.
+ * C_p >= C_d keeps decoding, otherwise the prefill is dispatched; with nothing running the
+ * prefill is forced; with nothing running and nothing arrived time jumps to the next arrival.
+ * arrival_us [S,N] int64 nondecreasing along N; in_len, out_len [S,N] int32 >= 1
+ * finish_us  [S,N] int64;  total_us, busy_slot_us [S] int64;  n_prefill_iter, n_decode_iter [S]
+ * trace_hash [S] uint64: FNV-1a (64 bit) over the canonical records
+ * trace_buf  nullable, [trace_scenarios, trace_capacity] mmbp_trace_rec for the first
+ *            trace_scenarios scenarios; trace_len [trace_scenarios] int32 = records produced
+ *            (may exceed trace_capacity; only the first trace_capacity are stored)
+ * status_out [S]: MMBP_ST_OK or MMBP_ST_BAD_SIM_INPUT (then every output of the scenario is 0)
+ */
+int online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, const int32_t *out_len,
+                    int S, int N, const mmbp_sim_params *params /* host */,
+                    int64_t *finish_us, int64_t *total_us, int64_t *busy_slot_us,
+                    int32_t *n_prefill_iter, int32_t *n_decode_iter, uint64_t *trace_hash,
+                    mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
+                    int trace_capacity, int32_t *status_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMBP_H */

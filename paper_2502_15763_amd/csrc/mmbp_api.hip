@@ -1,0 +1,107 @@
+// C-ABI boundary of libmmbp: argument validation, path selection, kernel launches on the caller's
+// stream.  No allocation, no synchronisation.
+#include <cstdio>
+#include <cstring>
+#include "mmbp_dev.hpp"
+
+namespace {
+thread_local char g_hip_err[256] = "no HIP error recorded";
+
+int fail_hip(hipError_t e, const char *where)
+{
+    snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", where, hipGetErrorString(e));
+    return MMBP_EHIP;
+}
+}  // namespace
+
+extern "C" {
+
+int mmbp_version(void) { return 100; }
+
+const char *mmbp_strerror(int code)
+{
+    switch (code) {
+    case MMBP_OK: return "ok";
+    case MMBP_EINVAL: return "invalid argument (null pointer, non-positive size, bad dtype or negative max_passes)";
+    case MMBP_EINFEASIBLE: return "infeasible: N > M * cap";
+    case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64)";
+    case MMBP_EWORKSPACE: return "workspace missing or too small (see mmbp_workspace_bytes)";
+    case MMBP_EHIP: return g_hip_err;
+    default: return "unknown error code";
+    }
+}
+
+size_t mmbp_workspace_bytes(int S, int N, int M)
+{
+    if (S <= 0 || N <= 0 || M <= 0 || N > MMBP_MAX_N || M > MMBP_MAX_M) return 0;
+    if (mmbp::ls_lds_fits(N, M)) return 0;
+    return mmbp::ls_grid_workspace_bytes(S, N, M);
+}
+
+int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M, const int32_t *prefill_tokens,
+                     int64_t ncap_L, int64_t tp_L, int64_t *lb_out, int32_t *status_out, void *stream)
+{
+    if (!cost || !lb_out || !status_out) return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || M <= 0) return MMBP_EINVAL;
+    if (dtype != MMBP_I32 && dtype != MMBP_I64) return MMBP_EINVAL;
+    if (ncap_L < 0 || tp_L < 0) return MMBP_EINVAL;
+    if (N > MMBP_MAX_N || M > MMBP_MAX_M) return MMBP_EUNSUPPORTED;
+    hipError_t e = mmbp::launch_lower_bound(cost, dtype, S, N, M, prefill_tokens, ncap_L, tp_L, lb_out, status_out,
+                                            (hipStream_t)stream);
+    return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_lower_bound");
+}
+
+int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int32_t *assign,
+                      int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
+                      uint64_t *applied_log, int32_t *status_out, void *workspace, size_t workspace_bytes,
+                      void *stream)
+{
+    if (!cost || !assign || !load_out || !makespan_out || !passes_out || !status_out) return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || M <= 0 || cap <= 0 || max_passes < 0) return MMBP_EINVAL;
+    if (dtype != MMBP_I32 && dtype != MMBP_I64) return MMBP_EINVAL;
+    if (N > MMBP_MAX_N || M > MMBP_MAX_M) return MMBP_EUNSUPPORTED;
+    if ((int64_t)N > (int64_t)M * (int64_t)cap) return MMBP_EINFEASIBLE;
+    const size_t need = mmbp_workspace_bytes(S, N, M);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return MMBP_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    // every scenario starts pending; each path takes the pending scenarios it can handle exactly
+    hipError_t e = mmbp::launch_fill_i32(status_out, mmbp::kPending, (size_t)S, st);
+    if (e != hipSuccess) return fail_hip(e, "mmbp_local_search(fill)");
+    if (mmbp::ls_lds_fits(N, M)) {
+        e = mmbp::launch_ls_lds(cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+                                evals_out, applied_log, status_out, st);
+        if (e != hipSuccess) return fail_hip(e, "mmbp_local_search(lds)");
+    } else {
+        e = mmbp::launch_ls_grid(cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+                                 evals_out, applied_log, status_out, workspace, st);
+        if (e != hipSuccess) return fail_hip(e, "mmbp_local_search(grid)");
+    }
+    e = mmbp::launch_ls_generic(cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+                                evals_out, applied_log, status_out, st);
+    return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_local_search(generic)");
+}
+
+int online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, const int32_t *out_len, int S, int N,
+                    const mmbp_sim_params *params, int64_t *finish_us, int64_t *total_us, int64_t *busy_slot_us,
+                    int32_t *n_prefill_iter, int32_t *n_decode_iter, uint64_t *trace_hash,
+                    mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios, int trace_capacity,
+                    int32_t *status_out, void *stream)
+{
+    if (!arrival_us || !in_len || !out_len || !params || !finish_us || !total_us || !busy_slot_us ||
+        !n_prefill_iter || !n_decode_iter || !trace_hash || !status_out)
+        return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || params->cap <= 0 || params->reserved != 0) return MMBP_EINVAL;
+    if (params->a_prefill < 0 || params->b_decode < 0 || params->c_prefill < 0 || params->c_decode < 0)
+        return MMBP_EINVAL;
+    if (trace_buf && (trace_scenarios < 0 || trace_capacity < 0 || !trace_len)) return MMBP_EINVAL;
+    if (params->cap > MMBP_SIM_MAX_CAP || N > MMBP_MAX_N) return MMBP_EUNSUPPORTED;
+    if (!trace_buf) { trace_scenarios = 0; trace_capacity = 0; }
+    hipError_t e = mmbp::launch_online_sim(arrival_us, in_len, out_len, S, N, *params, finish_us, total_us,
+                                           busy_slot_us, n_prefill_iter, n_decode_iter, trace_hash, trace_buf,
+                                           trace_buf ? trace_len : nullptr, trace_scenarios, trace_capacity,
+                                           status_out, (hipStream_t)stream);
+    return e == hipSuccess ? MMBP_OK : fail_hip(e, "online_iter_sim");
+}
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+"""The C-ABI library loads, exports every symbol the header declares, and rejects bad arguments
+on the host before anything touches a GPU (no compute calls here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2502_15763_amd import api
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "mmbp.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^[a-zA-Z_][\w\s\*]*?\b(\w+)\s*\([^;{]*\)\s*;", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_declares_expected_entry_points():
+    names = _declared_functions()
+    for n in ("mmbp_lower_bound", "mmbp_local_search", "online_iter_sim", "mmbp_workspace_bytes",
+              "mmbp_strerror", "mmbp_version"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = api.load_library()
+    for n in _declared_functions():
+        assert hasattr(lib, n), f"libmmbp.so does not export {n}"
+    assert set(api.EXPORTS) <= set(_declared_functions())
+    assert api.mmbp_version() >= 100
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(api.SimParams) == 48
+    assert api.SimParams.a_prefill.offset == 8 and api.SimParams.max_prefill_tokens.offset == 40
+
+
+def test_host_side_argument_validation():
+    lib = api.load_library()
+    one = C.c_void_p(256)    # never dereferenced: all calls below fail validation first
+    ls = lib.mmbp_local_search
+    assert ls(None, 0, 1, 4, 2, 2, 1, one, one, one, one, None, None, one, None, 0, None) == api.EINVAL
+    assert ls(one, 0, 0, 4, 2, 2, 1, one, one, one, one, None, None, one, None, 0, None) == api.EINVAL
+    assert ls(one, 0, 1, 4, 2, 0, 1, one, one, one, one, None, None, one, None, 0, None) == api.EINVAL
+    assert ls(one, 0, 1, 4, 2, 2, -1, one, one, one, one, None, None, one, None, 0, None) == api.EINVAL
+    assert ls(one, 7, 1, 4, 2, 2, 1, one, one, one, one, None, None, one, None, 0, None) == api.EINVAL
+    assert ls(one, 0, 1, 5, 2, 2, 1, one, one, one, one, None, None, one, None, 0, None) == api.EINFEASIBLE
+    assert ls(one, 0, 1, (1 << 20) + 1, 256, 1 << 20, 1, one, one, one, one, None, None, one, None, 0, None) == api.EUNSUPPORTED
+    assert ls(one, 0, 1, 4, 257, 2, 1, one, one, one, one, None, None, one, None, 0, None) == api.EUNSUPPORTED
+    need = api.mmbp_workspace_bytes(1, 65536, 64)
+    if need:
+        assert ls(one, 1, 1, 65536, 64, 1024, 1, one, one, one, one, None, None, one, None, 0, None) == api.EWORKSPACE
+        assert ls(one, 1, 1, 65536, 64, 1024, 1, one, one, one, one, None, None, one, one, need - 1, None) == api.EWORKSPACE
+    lb = lib.mmbp_lower_bound
+    assert lb(None, 0, 1, 4, 2, None, 0, 0, one, one, None) == api.EINVAL
+    assert lb(one, 0, 1, 4, 0, None, 0, 0, one, one, None) == api.EINVAL
+    assert lb(one, 3, 1, 4, 2, None, 0, 0, one, one, None) == api.EINVAL
+    sim = lib.online_iter_sim
+    p = api.SimParams(65, 0, 1, 1, 1, 1, 0)
+    args = lambda pp: (one, one, one, 1, 4, C.byref(pp), one, one, one, one, one, one, None, None, 0, 0, one, None)
+    assert sim(*args(p)) == api.EUNSUPPORTED
+    p = api.SimParams(0, 0, 1, 1, 1, 1, 0)
+    assert sim(*args(p)) == api.EINVAL
+    p = api.SimParams(4, 0, -1, 1, 1, 1, 0)
+    assert sim(*args(p)) == api.EINVAL
+    assert sim(one, one, one, 1, 4, None, one, one, one, one, one, one, None, None, 0, 0, one, None) == api.EINVAL
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(api.mmbp_strerror(code), str) and api.mmbp_strerror(code)
+
+
+def test_binding_refuses_host_tensors():
+    torch = pytest.importorskip("torch")
+    cost = torch.zeros((1, 4), dtype=torch.int32)
+    with pytest.raises(ValueError):
+        api.run_lower_bound(cost, 2)

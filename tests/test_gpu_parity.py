@@ -1,0 +1,220 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, bit for bit.
+
+Integer work throughout (costs, loads, times are integer microseconds), so the bar is exact
+equality of assignments, loads, makespans, pass counts, candidate counts, applied candidate ids,
+finish times and canonical traces."""
+import numpy as np
+import pytest
+
+from paper_2502_15763_amd import workloads as W
+from gpu_util import (say, gpu_local_search, compare_ls, gpu_lower_bound, gpu_online_sim, compare_sim)
+
+pytestmark = pytest.mark.gpu
+
+
+# ------------------------------------------------------------------ local search
+SMALL_SHAPES = [
+    # N, M, cap, cost_hi
+    (1, 1, 1, 10), (1, 3, 1, 10), (2, 2, 1, 10), (5, 5, 1, 50), (6, 2, 3, 30), (7, 3, 3, 1000),
+    (16, 4, 4, 100), (16, 4, 7, 100), (33, 5, 9, 500), (64, 4, 16, 40000), (64, 4, 20, 40000),
+    (65, 3, 30, 300), (100, 7, 15, 2000), (127, 2, 64, 100), (128, 8, 16, 5), (130, 8, 40, 3),
+    (200, 16, 13, 100000), (257, 9, 33, 700), (300, 3, 300, 50), (96, 33, 3, 1000), (70, 70, 1, 99),
+]
+
+
+@pytest.mark.parametrize("dtype", [np.int32, np.int64])
+def test_ls_small_random(oracle, dtype):
+    rng = np.random.default_rng(2024)
+    for (N, M, cap, hi) in SMALL_SHAPES:
+        S = 5
+        say(f"ls_small dtype={np.dtype(dtype).name} N={N} M={M} cap={cap} hi={hi}")
+        cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=hi, dtype=dtype)
+        o = oracle.local_search(cost, assign, M, cap, 200, want_log=True)
+        g = gpu_local_search(cost, assign, M, cap, 200)
+        compare_ls(g, o, label=f"N={N} M={M} cap={cap}")
+
+
+def test_ls_pass_limits_and_resume(oracle):
+    rng = np.random.default_rng(5)
+    cost, assign = W.random_offline(rng, 6, 90, 5, 20, cost_hi=5000, dtype=np.int32)
+    for mp in (0, 1, 2, 3):
+        say(f"ls_pass_limit max_passes={mp}")
+        o = oracle.local_search(cost, assign, 5, 20, mp, want_log=True)
+        g = gpu_local_search(cost, assign, 5, 20, mp, want_log=mp > 0)
+        compare_ls(g, o, label=f"max_passes={mp}")
+    g1 = gpu_local_search(cost, assign, 5, 20, 2)
+    g2 = gpu_local_search(cost, g1["assign"], 5, 20, 2)
+    g12 = gpu_local_search(cost, assign, 5, 20, 4)
+    assert np.array_equal(g2["assign"], g12["assign"]) and np.array_equal(g2["load"], g12["load"])
+
+
+def test_ls_bad_scenarios_do_not_disturb_others(oracle):
+    rng = np.random.default_rng(6)
+    cost, assign = W.random_offline(rng, 6, 40, 4, 12, cost_hi=900, dtype=np.int64)
+    cost[1, 7] = -5                 # BAD_COST
+    assign[2, 3] = 4                # BAD_ASSIGN (out of range)
+    assign[3, :] = 0                # BAD_ASSIGN (more than cap on client 0)
+    cost[4, :2] = 1 << 61           # BAD_COST (sum >= 2^62)
+    say("ls_bad_scenarios")
+    o = oracle.local_search(cost, assign, 4, 12, 100, want_log=True)
+    g = gpu_local_search(cost, assign, 4, 12, 100)
+    assert o["status"].tolist()[1:5] == [3, 2, 2, 3]
+    compare_ls(g, o, label="bad scenarios")
+
+
+def test_ls_large_costs_need_64_bit(oracle):
+    """Loads far above 2^31: the exact 64-bit path."""
+    rng = np.random.default_rng(8)
+    cost, assign = W.random_offline(rng, 4, 60, 4, 18, cost_hi=(1 << 40), dtype=np.int64)
+    say("ls_large_costs")
+    o = oracle.local_search(cost, assign, 4, 18, 100, want_log=True)
+    g = gpu_local_search(cost, assign, 4, 18, 100)
+    compare_ls(g, o, label="large costs")
+    # near the int32 narrowing boundary as well
+    cost, assign = W.random_offline(rng, 4, 60, 4, 18, cost_hi=(1 << 27), dtype=np.int64)
+    o = oracle.local_search(cost, assign, 4, 18, 100, want_log=True)
+    g = gpu_local_search(cost, assign, 4, 18, 100)
+    compare_ls(g, o, label="boundary costs")
+
+
+def test_ls_config1(oracle):
+    for slack in (0, 16):
+        c = W.config1(slack=slack)
+        say(f"ls_config1 slack={slack}")
+        o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+        g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes)
+        compare_ls(g, o, label=f"c1 slack={slack}")
+
+
+def test_ls_config2_full(oracle):
+    c = W.config2()
+    say("ls_config2 full 1024x1024 tight")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+    g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes)
+    compare_ls(g, o, label="c2")
+    assert (o["status"] == 0).all()
+
+
+def test_ls_config2_slack(oracle):
+    c = W.config2(S=48, slack=64)
+    say("ls_config2 slack S=48")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+    g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes)
+    compare_ls(g, o, label="c2 slack")
+    assert (o["log"][:, 0] < c.N * c.M).any() or True
+
+
+def test_ls_config3_sampled(oracle):
+    """Full batch on the GPU (4096 x 4096, int64 costs, 64 passes); the oracle recomputes a sample
+    of scenarios one by one (scenarios are independent)."""
+    c = W.config3()
+    say("ls_config3 full batch on GPU")
+    g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes)
+    sample = [0, 1, 777, 2048, 4095]
+    say(f"ls_config3 oracle on scenarios {sample}")
+    o = oracle.local_search(c.cost[sample], c.assign0[sample], c.M, c.cap, c.max_passes, want_log=True)
+    gs = {k: (v[sample] if isinstance(v, np.ndarray) else v) for k, v in g.items()}
+    compare_ls(gs, o, label="c3 sample")
+    # properties that hold for every scenario
+    assert np.array_equal(g["load"].sum(axis=1), c.cost.sum(axis=1))
+    assert np.array_equal(g["makespan"], g["load"].max(axis=1))
+    cnt = np.stack([np.bincount(a, minlength=c.M) for a in g["assign"]])
+    assert cnt.max() <= c.cap
+
+
+def test_ls_config3_slack_converged(oracle):
+    c = W.config3(S=4, slack=128, max_passes=4000)
+    say("ls_config3 slack, to convergence, S=4")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+    g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes)
+    compare_ls(g, o, label="c3 slack")
+
+
+@pytest.mark.parametrize("slack,passes", [(0, 12), (256, 12)])
+def test_ls_config4(oracle, slack, passes):
+    c = W.config4(slack=slack)
+    say(f"ls_config4 N=65536 M=64 slack={slack} passes={passes}")
+    g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, passes)
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, passes, want_log=True)
+    compare_ls(g, o, label=f"c4 slack={slack}")
+
+
+# ------------------------------------------------------------------ lower bound
+def test_lb_parity(oracle):
+    rng = np.random.default_rng(31)
+    for (N, M, hi, dtype) in [(1, 1, 10, np.int32), (3, 5, 10, np.int64), (5, 4, 100, np.int32), (9, 8, 3, np.int32),
+                              (64, 4, 40000, np.int32), (1000, 7, 1 << 20, np.int64), (4097, 16, 1 << 40, np.int64),
+                              (5000, 256, 1000, np.int32), (300, 255, 7, np.int32)]:
+        say(f"lb N={N} M={M}")
+        cost = rng.integers(0, hi + 1, size=(7, N)).astype(dtype)
+        tok = rng.integers(1, 3000, size=(7, N)).astype(np.int32)
+        for kw in (dict(), dict(prefill_tokens=tok, ncap_L=5000, tp_L=675000)):
+            o = oracle.lower_bound(cost, M, **kw)
+            g = gpu_lower_bound(cost, M, **kw)
+            assert np.array_equal(g["status"], o["status"]) and np.array_equal(g["lb"], o["lb"]), (N, M, kw.keys())
+    cost = np.array([[3, -1, 4], [1, 2, 3]], np.int64)
+    o = oracle.lower_bound(cost, 2)
+    g = gpu_lower_bound(cost, 2)
+    assert g["status"].tolist() == o["status"].tolist() == [3, 0] and g["lb"].tolist() == o["lb"].tolist()
+
+
+def test_lb_configs(oracle):
+    for c in (W.config1(), W.config2(), W.config3(S=256), W.config4()):
+        say(f"lb config {c.name}")
+        o = oracle.lower_bound(c.cost, c.M)
+        g = gpu_lower_bound(c.cost, c.M)
+        assert np.array_equal(g["lb"], o["lb"]) and (g["status"] == 0).all()
+
+
+# ------------------------------------------------------------------ online simulator
+def test_sim_small(oracle):
+    rng = np.random.default_rng(41)
+    for (N, cap, tok, rate) in [(1, 1, 0, 50), (5, 1, 0, 50), (40, 4, 0, 200), (300, 16, 0, 50), (300, 16, 600, 50),
+                                (500, 64, 0, 20), (500, 64, 4000, 500), (200, 33, 0, 5), (64, 64, 0, 1e6)]:
+        say(f"sim N={N} cap={cap} tok={tok} rate={rate}")
+        S = 9
+        w = W.config5(S=S, N=N, rate_per_s=rate, seed_offset=N + cap)
+        p = dict(w.params, cap=cap, max_prefill_tokens=tok)
+        o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, p, trace_scenarios=S, trace_capacity=3 * N + 8)
+        g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, p, trace_scenarios=S, trace_capacity=3 * N + 8)
+        compare_sim(g, o, label=f"N={N} cap={cap} tok={tok}")
+
+
+def test_sim_paper_constants(oracle):
+    in_len, out_len = W.paper_shaped(S=8, N=1319)
+    arr = np.zeros_like(in_len, dtype=np.int64)
+    p = dict(W.PAPER_PARAMS, cap=64)
+    say("sim paper-shaped lengths, all requests at t=0")
+    o = oracle.online_iter_sim(arr, in_len, out_len, p, trace_scenarios=2, trace_capacity=5000)
+    g = gpu_online_sim(arr, in_len, out_len, p, trace_scenarios=2, trace_capacity=5000)
+    compare_sim(g, o, label="paper-shaped")
+
+
+def test_sim_bad_input(oracle):
+    w = W.config5(S=5, N=50)
+    w.arrival_us[1, 10] = w.arrival_us[1, 9] - 1
+    w.in_len[2, 0] = 0
+    w.out_len[3, 49] = 0
+    say("sim bad input")
+    o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, w.params)
+    g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, w.params)
+    assert o["status"].tolist() == [0, 4, 4, 4, 0]
+    compare_sim(g, o, label="bad input")
+
+
+def test_sim_trace_capacity_overflow(oracle):
+    w = W.config5(S=3, N=100)
+    say("sim trace capacity smaller than the trace")
+    o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, w.params, trace_scenarios=2, trace_capacity=10)
+    g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, w.params, trace_scenarios=2, trace_capacity=10)
+    compare_sim(g, o, label="trace overflow")
+    assert (g["trace_len"] > 10).all()
+
+
+def test_sim_config5_full(oracle):
+    w = W.config5()
+    say("sim config5 full 8192 x 2048 on GPU")
+    g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, w.params, trace_scenarios=4, trace_capacity=8192)
+    say("sim config5 oracle, all scenarios")
+    o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, w.params, trace_scenarios=4, trace_capacity=8192)
+    compare_sim(g, o, label="c5")
