@@ -65,9 +65,9 @@ int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap,
     if (need > 0 && (!workspace || workspace_bytes < need)) return MMBP_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
 
-    // every scenario starts pending; each path takes the pending scenarios it can handle exactly
-    hipError_t e = mmbp::launch_fill_i32(status_out, mmbp::kPending, (size_t)S, st);
-    if (e != hipSuccess) return fail_hip(e, "mmbp_local_search(fill)");
+    // The first path writes a status for every scenario: final where it can search the scenario
+    // exactly, pending otherwise; the 64-bit kernel then takes the pending ones.
+    hipError_t e;
     if (mmbp::ls_lds_fits(N, M)) {
         e = mmbp::launch_ls_lds(cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
                                 evals_out, applied_log, status_out, st);
