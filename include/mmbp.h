@@ -40,6 +40,8 @@ extern "C" {
 #define MMBP_ST_BAD_ASSIGN    2  /* assign entry outside [0,M) or more than cap jobs on a client */
 #define MMBP_ST_BAD_COST      3  /* negative cost, or sum of costs >= 2^62 */
 #define MMBP_ST_BAD_SIM_INPUT 4  /* arrival negative or decreasing, in_len < 1, out_len < 1 */
+#define MMBP_ST_INTERNAL      5  /* a consistency check inside a kernel failed (a bug): the scenario's
+                                    outputs are not valid */
 
 /* cost element type */
 #define MMBP_I32 0

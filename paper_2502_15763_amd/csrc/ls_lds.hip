@@ -11,24 +11,31 @@
 //     2 * max(l_a - d, l_b + d) = (l_a + l_b) + |(2 T_k + 2^30) - (2 T_i + 2^30 - (l_a - l_b))| .
 // Inside a tile (64*R rows of client a) x (columns of client b), l_a, l_b and the largest
 // untouched load are uniform, so the candidate with the smallest makespan is the one with the
-// smallest absolute difference: one v_sad_u32 per candidate and one v_min3_u32 per two
-// candidates.  Each unordered client pair is evaluated once; the client with the largest load
+// smallest absolute difference |y - x|, y = cu of the column, x = cu of the row - (l_a - l_b).
+// With d = y - x taken modulo 2^32, the smallest d is the distance to the nearest column at or
+// above x and the negated largest d the distance to the nearest column below x, so a candidate
+// costs one v_sub_u32 plus half a v_min3_u32 and half a v_max3_u32, all full-rate VALU
+// (v_sad_u32 would fuse them but issues at quarter rate).  Each unordered client pair is evaluated once; the client with the largest load
 // ("critical") is always the column side, so the per-row minima against it are known for every
 // other job.  They resolve the lowest-id tie-break exactly: an improving swap must involve the
 // critical client, the jobs that take part in a best swap are read off the row minima, and only
 // the few pairs that can carry the lowest id are re-examined.
 //
-// Exactness: all loads stay below the initial makespan T0; with T0 + 2*max T_i < 2^30 every
-// quantity above fits 32 bits without wrap.  Scenarios that do not satisfy this stay pending for
-// the 64-bit kernel.
+// Exactness: all loads stay at or below the initial makespan T0; with T0 + 2*max T_i < 2^29 every
+// quantity above is exact in 32 bits: x lies in (2^29, 3*2^29), a real |y - x| is below 2^29, a
+// wrapped difference is above 7*2^29, and an empty column (cu = 6*2^29) gives d in (3*2^29, 5*2^29),
+// which can win neither the minimum nor (negated) the maximum against a real column.  Scenarios
+// that do not satisfy the bound stay pending for the 64-bit kernel.
 #include "mmbp_dev.hpp"
 
 namespace mmbp {
 namespace {
 
 constexpr uint32_t kBias = 1u << 30;
-constexpr uint32_t kPad = 0xFFFFFFFFu;
-constexpr uint32_t kKeyLimit = 1u << 30;      // every real key is below this
+constexpr uint32_t kNarrowLimit = 1u << 29;   // narrowing needs T0 + 2 * max cost below this
+constexpr uint32_t kPad = 0xC0000000u;        // cu of an empty position
+constexpr uint32_t kKeyLimit = 1u << 29;      // |y - x| of a real candidate is below this; keys that come
+                                              // from empty columns or from the absent side are >= 3 * 2^29
 constexpr uint32_t kInf = 0xFFFFFFFFu;
 constexpr uint16_t kNoJob = 0xFFFFu;
 constexpr int kRMax = 4;                       // row segments (of 64 positions) per tile
@@ -43,15 +50,16 @@ struct Ctrl {
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
-    uint32_t vswap, vmove, partner;
+    uint32_t vswap, vmove;
     int nE, nF, nfeas, P;
-    int passes, status, stop;
+    uint32_t top_v[3];            // three largest loads and their clients, published by wave 0
+    int top_j[3];
+    int passes, status, stop, iters;
     int bad_cost, bad_assign;
-    int pos_i, pos_k;
 };
 
 struct Lds {
-    uint32_t *cu, *rowkey;
+    uint32_t *cu, *rowkey;   // rowkey[p]: best swap makespan of the job at p against the critical client
     uint16_t *job, *list;
     long long *load;
     int *cnt, *gstart, *fillc, *feas;
@@ -99,18 +107,22 @@ __device__ inline Lds carve(unsigned char *base, int N, int M)
     return l;
 }
 
-__device__ __forceinline__ uint32_t sad_u32(uint32_t a, uint32_t b)
+__device__ __forceinline__ uint32_t absdiff_u32(uint32_t a, uint32_t b) { return max(a, b) - min(a, b); }
+
+// Running nearest-above / nearest-below search of one row against four columns.
+struct RowAcc {
+    uint32_t up;   // min over columns of (y - x) mod 2^32
+    uint32_t mx;   // max over columns of (y - x) mod 2^32
+};
+__device__ __forceinline__ void nearest_x4(RowAcc &a, uint32_t x, const uint4 &c)
 {
-    uint32_t d;
-    asm("v_sad_u32 %0, %1, %2, 0" : "=v"(d) : "v"(a), "v"(b));
-    return d;
+    const uint32_t d0 = c.x - x, d1 = c.y - x, d2 = c.z - x, d3 = c.w - x;
+    a.up = min(min(a.up, d0), d1);
+    a.mx = max(max(a.mx, d0), d1);
+    a.up = min(min(a.up, d2), d3);
+    a.mx = max(max(a.mx, d2), d3);
 }
-__device__ __forceinline__ uint32_t min3_u32(uint32_t a, uint32_t b, uint32_t c)
-{
-    uint32_t d;
-    asm("v_min3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-    return d;
-}
+__device__ __forceinline__ uint32_t nearest_key(const RowAcc &a) { return min(a.up, 0u - a.mx); }
 
 __device__ __forceinline__ unsigned long long sat_add62(unsigned long long a, unsigned long long b)
 {
@@ -155,37 +167,143 @@ __device__ __forceinline__ uint32_t others_max(const Top3 &t, int a, int b)
     return t.v[2];
 }
 
-// makespan of a swap candidate from its key (absolute difference), the two loads and the largest
-// untouched load
+// makespan of a swap candidate from its key |y - x|: twice the larger changed load is
+// l_a + l_b + key; the other loads contribute the largest untouched one
 __device__ __forceinline__ uint32_t swap_value(uint32_t key, uint32_t lsum, uint32_t others)
 {
     return key < kKeyLimit ? max(others, (lsum + key) >> 1) : kInf;
 }
 
-// Tile: R row segments starting at rowbase against the columns [c0, c1) ((c1 - c0) % 8 == 0).
-// acc[r] = min over the columns of |cu[col] - (cu[row] - delta)|.
+// Tile: R rows per lane (x[r], already shifted by l_a - l_b) against the columns [c0, c1)
+// ((c1 - c0) % 8 == 0, > 0).  key[r] = min over the columns of |cu[col] - x[r]|.  Two register
+// sets in ping-pong: the LDS loads of one are in flight while the other is evaluated.
 template <int R>
-__device__ __forceinline__ void swap_tile(const uint32_t *cu, int rowbase, int lane, uint32_t delta, int c0, int c1,
-                                          uint32_t (&acc)[kRMax], uint32_t (&rowx)[kRMax])
+__device__ __forceinline__ void tile_columns(const uint32_t *cu, const uint32_t (&x)[R], int c0, int c1,
+                                             uint32_t (&key)[R])
 {
-    uint32_t g[R];
+    RowAcc acc[R];
 #pragma unroll
-    for (int r = 0; r < R; r++) {
-        rowx[r] = cu[rowbase + 64 * r + lane];
-        g[r] = rowx[r] - delta;
-        acc[r] = kInf;
-    }
+    for (int r = 0; r < R; r++) { acc[r].up = kInf; acc[r].mx = 0u; }
     const uint4 *col = reinterpret_cast<const uint4 *>(cu + c0);
-    const int n4 = (c1 - c0) >> 2;
-    for (int k = 0; k < n4; k += 2) {
-        const uint4 u = col[k];
-        const uint4 w = col[k + 1];
+    const int n8 = (c1 - c0) >> 3;
+    uint4 a0 = col[0], a1 = col[1], b0, b1;
+    int k = 1;
+    for (; k + 1 < n8; k += 2) {
+        b0 = col[2 * k]; b1 = col[2 * k + 1];
+#pragma unroll
+        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], a0); nearest_x4(acc[r], x[r], a1); }
+        a0 = col[2 * k + 2]; a1 = col[2 * k + 3];
+#pragma unroll
+        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], b0); nearest_x4(acc[r], x[r], b1); }
+    }
+    if (k < n8) {
+        b0 = col[2 * k]; b1 = col[2 * k + 1];
+#pragma unroll
+        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], a0); nearest_x4(acc[r], x[r], a1); }
+#pragma unroll
+        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], b0); nearest_x4(acc[r], x[r], b1); }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], a0); nearest_x4(acc[r], x[r], a1); }
+    }
+#pragma unroll
+    for (int r = 0; r < R; r++) key[r] = nearest_key(acc[r]);
+}
+
+// Per-client counts, layout starts and loads as seen by one wave.  With M <= 64 they sit one per
+// lane and are fetched with v_readlane (no LDS round trip in the task loop); otherwise they are
+// read from LDS.
+template <bool SMALLM>
+struct Clients {
+    const Lds *l;
+    int maxn, maxp;               // clamps: a count never exceeds N, a start never exceeds the padded size
+    uint32_t vcnt, vstart, vload;
+    __device__ __forceinline__ void refresh(int M, int lane)
+    {
+        if (SMALLM) {
+            vcnt = lane < M ? (uint32_t)l->cnt[lane] : 0u;
+            vstart = lane < M ? (uint32_t)l->gstart[lane] : 0u;
+            vload = lane < M ? (uint32_t)l->load[lane] : 0u;
+        }
+    }
+    __device__ __forceinline__ int cnt(int g) const
+    {
+        const int v = SMALLM ? __builtin_amdgcn_readlane((int)vcnt, g) : __builtin_amdgcn_readfirstlane(l->cnt[g]);
+        return min(max(v, 0), maxn);
+    }
+    __device__ __forceinline__ int start(int g) const
+    {
+        const int v = SMALLM ? __builtin_amdgcn_readlane((int)vstart, g) : __builtin_amdgcn_readfirstlane(l->gstart[g]);
+        return min(max(v, 0), maxp) & ~63;
+    }
+    __device__ __forceinline__ uint32_t load(int g) const
+    {
+        return (uint32_t)(SMALLM ? __builtin_amdgcn_readlane((int)vload, g)
+                                 : __builtin_amdgcn_readfirstlane((int)(uint32_t)l->load[g]));
+    }
+};
+
+// three largest loads with their clients for M <= 64 (one load per lane): every lane ranks its
+// load against all others (ties: lower client first), the lanes of rank 0, 1, 2 are read back
+__device__ __forceinline__ Top3 wave_top3_small(uint32_t vload, int M, int lane)
+{
+    int rank = 0;
+    for (int i = 0; i < M; i++) {
+        const uint32_t li = (uint32_t)__builtin_amdgcn_readlane((int)vload, i);
+        rank += (li > vload || (li == vload && i < lane)) ? 1 : 0;
+    }
+    Top3 t;
+#pragma unroll
+    for (int r = 0; r < 3; r++) {
+        const unsigned long long m = __ballot(lane < M && rank == r);
+        if (m) {
+            const int j = __builtin_ctzll(m);
+            t.j[r] = j;
+            t.v[r] = (uint32_t)__builtin_amdgcn_readlane((int)vload, j);
+        } else {
+            t.j[r] = -1;
+            t.v[r] = 0u;
+        }
+    }
+    return t;
+}
+
+// One row unit (R row segments of client g starting at rowbase) against the column clients whose
+// flattened task index falls in [lo, hi); `first` is the task index of the unit's first column
+// client.  Column clients of g: the non-empty clients after g except the critical one, then the
+// critical one.
+template <int R, bool SMALLM>
+__device__ __forceinline__ void row_unit(const Lds &l, const Clients<SMALLM> &cl, const Top3 &top, int M, int astar,
+                                         int g, uint32_t la, int rowbase, int lane, int first, int lo, int hi,
+                                         uint32_t &sbest)
+{
+    uint32_t rowx[R];
+#pragma unroll
+    for (int r = 0; r < R; r++) rowx[r] = l.cu[rowbase + 64 * r + lane];
+    int idx = first;
+    for (int bb = g + 1; bb <= M; bb++) {
+        const int b = (bb == M) ? astar : bb;
+        if (bb < M && b == astar) continue;
+        const int nb = cl.cnt(b);
+        if (nb == 0) continue;
+        const int my = idx++;
+        if (my < lo) continue;
+        if (my >= hi) break;
+        const uint32_t lb = cl.load(b);
+        const int c0 = cl.start(b);
+        const int c1 = min(c0 + ((nb + 7) & ~7), cl.maxp);
+        if (c1 <= c0) continue;
+        uint32_t x[R], key[R];
+#pragma unroll
+        for (int r = 0; r < R; r++) x[r] = rowx[r] - (la - lb);
+        tile_columns<R>(l.cu, x, c0, c1, key);
+        const uint32_t oth = others_max(top, g, b);
+        const uint32_t lsum = la + lb;
 #pragma unroll
         for (int r = 0; r < R; r++) {
-            acc[r] = min3_u32(acc[r], sad_u32(u.x, g[r]), sad_u32(u.y, g[r]));
-            acc[r] = min3_u32(acc[r], sad_u32(u.z, g[r]), sad_u32(u.w, g[r]));
-            acc[r] = min3_u32(acc[r], sad_u32(w.x, g[r]), sad_u32(w.y, g[r]));
-            acc[r] = min3_u32(acc[r], sad_u32(w.z, g[r]), sad_u32(w.w, g[r]));
+            const uint32_t v = rowx[r] != kPad ? swap_value(key[r], lsum, oth) : kInf;
+            sbest = min(sbest, v);
+            if (b == astar) l.rowkey[rowbase + 64 * r + lane] = v;
         }
     }
 }
@@ -200,7 +318,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
         for (int g = 0; g < M; g++) {
             l.gstart[g] = pos;
             const int n = l.cnt[g];
-            const int ns = (n + 63) >> 6;
+            const int ns = min((n + 63) >> 6, (N + 64 * M - pos) >> 6);
             for (int q = 0; q < ns; q++) l.seg_grp[(pos >> 6) + q] = (uint8_t)g;
             pos += ns * 64;
             if (n < cap) l.feas[nf++] = g;
@@ -225,7 +343,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
     __syncthreads();
 }
 
-template <typename CostT, int BLOCK>
+template <typename CostT, int BLOCK, bool SMALLM>
 __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
     const CostT *__restrict__ cost_all, int N, int M, int cap, int max_passes, int32_t *assign_all,
     int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
@@ -292,34 +410,59 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
             }
             return;
         }
-        // exact 32-bit narrowing needs T0 + 2*max cost < 2^30
-        if ((unsigned long long)ctrl->T0 + 2ull * cmax >= (unsigned long long)kKeyLimit) {
+        // exact 32-bit narrowing needs T0 + 2*max cost < 2^29
+        if ((unsigned long long)ctrl->T0 + 2ull * cmax >= (unsigned long long)kNarrowLimit) {
             if (tid == 0) status_out[s] = kPending;
             return;
         }
     }
     build_layout<CostT, BLOCK>(l, c, asg, N, M, cap);
 
-    const uint32_t *load32 = reinterpret_cast<const uint32_t *>(l.load);   // low words (loads < 2^30)
+    // loads stay below 2^29 on this path: their low words are used
+    auto load32 = [&](int g) -> uint32_t { return (uint32_t)l.load[g]; };
+    Clients<SMALLM> cl;
+    cl.l = &l;
+    cl.maxn = N;
+    cl.maxp = N + 64 * M;
+    if (tid == 0) ctrl->iters = 0;
 
     // ---------------- pass loop ----------------
     for (;;) {
+        // serial section of wave 0: pass accounting, then the three largest loads for everybody.
+        // Every loop of a pass is bounded by N, M and the padded size, every barrier is reached under
+        // conditions read from LDS after a barrier, and the pass loop itself is capped.
         if (tid == 0) {
-            if (ctrl->passes == max_passes) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
+            ctrl->iters += 1;
+            if ((long long)ctrl->iters > (long long)max_passes + 1) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
+            else if (ctrl->passes == max_passes) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
             else ctrl->evals += (unsigned long long)N * (unsigned long long)(M - 1) + ctrl->pairs_per_scan;
-            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->partner = kInf;
+            ctrl->vswap = kInf; ctrl->vmove = kInf;
             ctrl->k0 = ~0ull; ctrl->pair = ~0ull; ctrl->mv = ~0ull;
             ctrl->nE = 0; ctrl->nF = 0;
+        }
+        if (wave == 0) {
+            // the lanes of wave 0 run in lockstep with thread 0, so its load updates above are complete
+            __builtin_amdgcn_wave_barrier();
+            const Top3 t = SMALLM ? wave_top3_small(lane < M ? (uint32_t)l.load[lane] : 0u, M, lane)
+                                  : wave_top3(l.load, M, lane);
+            if (lane == 0) {
+                for (int r = 0; r < 3; r++) { ctrl->top_v[r] = t.v[r]; ctrl->top_j[r] = t.j[r]; }
+            }
         }
         __syncthreads();
         if (ctrl->stop) break;
 
-        const int P = ctrl->P;
+        const int P = min(ctrl->P, N + 64 * M) & ~63;
         const int nseg = P >> 6;
-        const int nfeas = ctrl->nfeas;
-        const Top3 top = wave_top3(l.load, M, lane);
+        const int nfeas = min(ctrl->nfeas, M);
+        cl.refresh(M, lane);
+        Top3 top;
+        for (int r = 0; r < 3; r++) {
+            top.v[r] = uniu(ctrl->top_v[r]);
+            top.j[r] = uni(ctrl->top_j[r]);
+        }
         const uint32_t T = top.v[0];
-        const int astar = top.j[0];
+        const int astar = min(max(top.j[0], 0), M - 1);
 
         // ---- moves: value only ----
         uint32_t mbest = kInf;
@@ -328,53 +471,50 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
                 const int g = l.seg_grp[seg];
                 const uint32_t x = l.cu[seg * 64 + lane];
                 const uint32_t ci = (x - kBias) >> 1;
-                const uint32_t la = load32[2 * g];
+                const uint32_t la = load32(g);
                 uint32_t m = kInf;
                 for (int q = 0; q < nfeas; q++) {
                     const int b = l.feas[q];
                     if (b == g) continue;
-                    const uint32_t v = max(max(la - ci, load32[2 * b] + ci), others_max(top, g, b));
+                    const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
                     m = min(m, v);
                 }
                 if (x != kPad) mbest = min(mbest, m);
             }
         }
 
-        // ---- swaps: value only, every unordered client pair once, critical client as columns ----
+        // ---- swaps: value only.  Every unordered client pair once, the critical client always as
+        // columns.  Tasks (row unit, column client) are numbered in row-major order and each wave
+        // takes a contiguous range, so consecutive tasks of a wave reuse the rows in registers. ----
         uint32_t sbest = kInf;
         {
-            int tcount = 0;
-            for (int g = 0; g < M; g++) {
-                const int ng = l.cnt[g];
-                if (g == astar || ng == 0) continue;
-                const int gseg = (ng + 63) >> 6;
-                const int gbase = l.gstart[g];
-                const uint32_t la = load32[2 * g];
-                for (int blk = 0; blk < gseg; blk += kRMax) {
-                    const int R = min(kRMax, gseg - blk);
+            const bool star_ok = cl.cnt(astar) > 0;
+            int ntask = 0, nonempty = 0;
+            for (int g = M - 1; g >= 0; g--) {
+                const int ng = cl.cnt(g);
+                if (ng == 0 || g == astar) continue;
+                ntask += ((((ng + 63) >> 6) + kRMax - 1) / kRMax) * (nonempty + (star_ok ? 1 : 0));
+                nonempty++;
+            }
+            const int lo = (int)(((long long)ntask * wave) / kWaves);
+            const int hi = (int)(((long long)ntask * (wave + 1)) / kWaves);
+            int base = 0, after = nonempty;
+            for (int g = 0; g < M && base < hi; g++) {
+                const int ng = cl.cnt(g);
+                if (ng == 0 || g == astar) continue;
+                after--;                                   // non-empty, non-critical clients after g
+                const int ncol = after + (star_ok ? 1 : 0);
+                const int gbase = cl.start(g);
+                const int gseg = min((ng + 63) >> 6, (cl.maxp - gbase) >> 6);
+                const uint32_t la = cl.load(g);
+                for (int blk = 0; blk < gseg; blk += kRMax, base += ncol) {
+                    if (base + ncol <= lo || base >= hi) continue;
                     const int rowbase = gbase + blk * 64;
-                    for (int bb = g + 1; bb <= M; bb++) {
-                        const int b = (bb == M) ? astar : bb;
-                        if (bb < M && b == astar) continue;
-                        const int nb = l.cnt[b];
-                        if (nb == 0) continue;
-                        if ((tcount++ % kWaves) != wave) continue;
-                        const uint32_t lb = load32[2 * b];
-                        const int c0 = l.gstart[b];
-                        const int c1 = c0 + ((nb + 7) & ~7);
-                        uint32_t acc[kRMax], rowx[kRMax];
-                        switch (R) {
-                        case 1: swap_tile<1>(l.cu, rowbase, lane, la - lb, c0, c1, acc, rowx); break;
-                        case 2: swap_tile<2>(l.cu, rowbase, lane, la - lb, c0, c1, acc, rowx); break;
-                        case 3: swap_tile<3>(l.cu, rowbase, lane, la - lb, c0, c1, acc, rowx); break;
-                        default: swap_tile<4>(l.cu, rowbase, lane, la - lb, c0, c1, acc, rowx); break;
-                        }
-                        const uint32_t oth = others_max(top, g, b);
-                        const uint32_t lsum = la + lb;
-                        for (int r = 0; r < R; r++) {
-                            if (rowx[r] != kPad) sbest = min(sbest, swap_value(acc[r], lsum, oth));
-                            if (b == astar) l.rowkey[rowbase + 64 * r + lane] = acc[r];
-                        }
+                    switch (min(kRMax, gseg - blk)) {
+                    case 1: row_unit<1, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
+                    case 2: row_unit<2, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
+                    case 3: row_unit<3, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
+                    default: row_unit<4, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
                     }
                 }
             }
@@ -400,12 +540,12 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
                 const uint32_t x = l.cu[p];
                 if (x == kPad) continue;
                 const uint32_t ci = (x - kBias) >> 1;
-                const uint32_t la = load32[2 * g];
+                const uint32_t la = load32(g);
                 const uint32_t jb = l.job[p];
                 for (int q = 0; q < nfeas; q++) {
                     const int b = l.feas[q];
                     if (b == g) continue;
-                    const uint32_t v = max(max(la - ci, load32[2 * b] + ci), others_max(top, g, b));
+                    const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
                     if (v == V) {
                         const unsigned long long id = (unsigned long long)jb * (unsigned long long)M + (unsigned long long)b;
                         best = min(best, (id << 32) | (unsigned long long)p);
@@ -420,30 +560,37 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
                 const uint32_t id = (uint32_t)(mvv >> 32);
                 const int p = (int)(uint32_t)mvv;
                 const int i = (int)(id / (uint32_t)M), b = (int)(id % (uint32_t)M);
-                const int a = l.seg_grp[p >> 6];
-                const long long ci = (long long)((l.cu[p] - kBias) >> 1);
-                l.load[a] -= ci; l.load[b] += ci;
-                l.cnt[a] -= 1; l.cnt[b] += 1;
-                asg[i] = b;
-                if (applied_log) applied_log[(size_t)s * max_passes + ctrl->passes] = (uint64_t)id;
-                ctrl->passes += 1;
+                if (mvv == ~0ull || i >= N || p >= P) {
+                    ctrl->status = MMBP_ST_INTERNAL;     // cannot happen: the best move was found above
+                    ctrl->stop = 1;
+                } else {
+                    const int a = l.seg_grp[p >> 6];
+                    const long long ci = (long long)((l.cu[p] - kBias) >> 1);
+                    l.load[a] -= ci; l.load[b] += ci;
+                    l.cnt[a] -= 1; l.cnt[b] += 1;
+                    asg[i] = b;
+                    if (applied_log) applied_log[(size_t)s * max_passes + ctrl->passes] = (uint64_t)id;
+                    ctrl->passes += 1;
+                }
             }
             __syncthreads();
             build_layout<CostT, BLOCK>(l, c, asg, N, M, cap);
             continue;
         }
 
-        // ---- a swap wins: lowest (min(i,k), max(i,k)) among swaps of value V ----
-        const uint32_t lstar = load32[2 * astar];
-        // A: non-critical jobs that take part in a best swap (from the row minima against the critical client)
+        // ---- a swap wins: lowest (min(i,k), max(i,k)) among swaps of value V.  An improving swap
+        // involves the critical client, so every best swap pairs a critical job with a job whose
+        // row minimum against the critical client equals V. ----
+        const uint32_t lstar = load32(astar);
+        const int sbase = min(max(l.gstart[astar], 0), P), scnt = min(max(l.cnt[astar], 0), P - sbase);
+        const int send = sbase + scnt, sslots = sbase + ((scnt + 63) & ~63);
+        // A: flagged jobs (non-critical side of a best swap); k0 = the lowest of them
         {
             unsigned long long k0 = ~0ull;
             for (int p = tid; p < P; p += BLOCK) {
-                const int g = l.seg_grp[p >> 6];
-                const uint32_t jb = l.job[p];
-                if (g == astar || jb == kNoJob) continue;
-                const uint32_t v = swap_value(l.rowkey[p], load32[2 * g] + lstar, others_max(top, g, astar));
-                if (v == V) {
+                if (p >= sbase && p < sslots) continue;
+                if (l.rowkey[p] == V) {
+                    const uint32_t jb = l.job[p];
                     const int idx = atomicAdd(&ctrl->nF, 1);
                     l.list[idx] = (uint16_t)p;
                     k0 = min(k0, ((unsigned long long)jb << 32) | (unsigned long long)p);
@@ -453,10 +600,13 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
             if (lane == 0 && k0 != ~0ull) atomicMin(&ctrl->k0, k0);
         }
         __syncthreads();
+        if (ctrl->k0 == ~0ull) {                         // cannot happen: a best swap has a flagged job
+            if (tid == 0) ctrl->status = MMBP_ST_INTERNAL;
+            break;
+        }
         const uint32_t k0job = (uint32_t)(ctrl->k0 >> 32);
-        const int k0pos = (int)(uint32_t)ctrl->k0;
-        const int sbase = l.gstart[astar], send = sbase + l.cnt[astar];
-        // B: critical-client jobs with a lower index than k0 (only they can give a lower id)
+        const int k0pos = min((int)(uint32_t)ctrl->k0, P - 1);
+        // B: critical jobs with a lower index than k0 (only they can give a lower id than k0's swaps)
         for (int p = sbase + tid; p < send; p += BLOCK) {
             if ((uint32_t)l.job[p] < k0job) {
                 const int idx = atomicAdd(&ctrl->nE, 1);
@@ -464,54 +614,47 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
             }
         }
         __syncthreads();
-        const int nE = ctrl->nE, nF = ctrl->nF;
-        if (nE > 0) {
-            // C: pairs (early critical job, flagged job): waves over the former, lanes over the latter
+        {
+            // C: pairs (early critical job e, flagged job f), id (job_e, job_f);
+            // D: pairs (k0, later critical job),              id (k0, job).
+            // Candidates are packed (i:16 | k:16 | pos_i:16 | pos_k:16); the smallest wins.
+            const int nE = min(ctrl->nE, scnt), nF = min(ctrl->nF, P);
             unsigned long long best = ~0ull;
-            for (int e = wave; e < nE; e += kWaves) {
-                const int pe = l.list[P - 1 - e];
-                const uint32_t xe = l.cu[pe];
-                const unsigned long long je = (unsigned long long)l.job[pe] << 32;
-                for (int f = lane; f < nF; f += kWave) {
-                    const int pf = l.list[f];
-                    const int g = l.seg_grp[pf >> 6];
-                    const uint32_t lg = load32[2 * g];
-                    const uint32_t key = sad_u32(xe, l.cu[pf] - (lg - lstar));
-                    if (swap_value(key, lg + lstar, others_max(top, g, astar)) == V)
-                        best = min(best, je | (unsigned long long)l.job[pf]);
+            const int npair = nE * nF;
+            for (int q = tid; q < npair; q += BLOCK) {
+                const int e = q / nF, f = q - e * nF;
+                const int pe = l.list[P - 1 - e], pf = l.list[f];
+                const int g = l.seg_grp[pf >> 6];
+                const uint32_t lg = load32(g);
+                const uint32_t key = absdiff_u32(l.cu[pe], l.cu[pf] - (lg - lstar));
+                if (swap_value(key, lg + lstar, others_max(top, g, astar)) == V)
+                    best = min(best, ((unsigned long long)l.job[pe] << 48) | ((unsigned long long)l.job[pf] << 32) |
+                                         ((unsigned long long)pe << 16) | (unsigned long long)pf);
+            }
+            {
+                const int g = l.seg_grp[k0pos >> 6];
+                const uint32_t lg = load32(g);
+                const uint32_t xk = l.cu[k0pos] - (lg - lstar);
+                const uint32_t oth = others_max(top, g, astar);
+                for (int p = sbase + tid; p < send; p += BLOCK) {
+                    const uint32_t jb = l.job[p];
+                    if (jb > k0job && swap_value(absdiff_u32(l.cu[p], xk), lg + lstar, oth) == V)
+                        best = min(best, ((unsigned long long)k0job << 48) | ((unsigned long long)jb << 32) |
+                                             ((unsigned long long)k0pos << 16) | (unsigned long long)p);
                 }
             }
             best = wave_min_u64(best);
             if (lane == 0 && best != ~0ull) atomicMin(&ctrl->pair, best);
-            __syncthreads();
-        }
-        unsigned long long pr = (nE > 0) ? ctrl->pair : ~0ull;
-        if (pr == ~0ull) {
-            // D: k0 is the lower index of the best swap; its partner is the lowest critical job paired with it
-            const int g = l.seg_grp[k0pos >> 6];
-            const uint32_t lg = load32[2 * g];
-            const uint32_t gk = l.cu[k0pos] - (lg - lstar);
-            const uint32_t oth = others_max(top, g, astar);
-            uint32_t pj = kInf;
-            for (int p = sbase + tid; p < send; p += BLOCK) {
-                const uint32_t key = sad_u32(l.cu[p], gk);
-                if (swap_value(key, lg + lstar, oth) == V) pj = min(pj, (uint32_t)l.job[p]);
-            }
-            pj = wave_min_u32(pj);
-            if (lane == 0 && pj != kInf) atomicMin(&ctrl->partner, pj);
-            __syncthreads();
-            pr = ((unsigned long long)k0job << 32) | (unsigned long long)ctrl->partner;
-        }
-        const uint32_t ji = (uint32_t)(pr >> 32), jk = (uint32_t)pr;     // ji < jk
-        // positions of the two jobs
-        for (int p = tid; p < P; p += BLOCK) {
-            const uint32_t jb = l.job[p];
-            if (jb == ji) ctrl->pos_i = p;
-            if (jb == jk) ctrl->pos_k = p;
         }
         __syncthreads();
         if (tid == 0) {
-            const int pi = ctrl->pos_i, pk = ctrl->pos_k;
+            const unsigned long long pr = ctrl->pair;
+            const uint32_t ji = (uint32_t)(pr >> 48), jk = (uint32_t)(pr >> 32) & 0xFFFFu;     // ji < jk
+            const int pi = (int)((pr >> 16) & 0xFFFFu), pk = (int)(pr & 0xFFFFu);
+            if (pr == ~0ull || ji >= (uint32_t)N || jk >= (uint32_t)N || pi >= P || pk >= P) {
+                ctrl->status = MMBP_ST_INTERNAL;         // cannot happen: the best swap was found above
+                ctrl->stop = 1;
+            } else {
             const int ga = l.seg_grp[pi >> 6], gb = l.seg_grp[pk >> 6];
             const uint32_t xi = l.cu[pi], xk = l.cu[pk];
             const long long d = (long long)((xi - kBias) >> 1) - (long long)((xk - kBias) >> 1);
@@ -523,6 +666,7 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
                 applied_log[(size_t)s * max_passes + ctrl->passes] =
                     (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
             ctrl->passes += 1;
+            }
         }
         // the barrier at the top of the next pass orders the update before its readers
     }
@@ -540,13 +684,13 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
     }
 }
 
-template <typename CostT, int BLOCK>
+template <typename CostT, int BLOCK, bool SMALLM>
 hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_passes, int32_t *assign,
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
     const size_t bytes = lds_bytes(N, M);
-    ls_lds_kernel<CostT, BLOCK><<<dim3(S), dim3(BLOCK), bytes, st>>>(
+    ls_lds_kernel<CostT, BLOCK, SMALLM><<<dim3(S), dim3(BLOCK), bytes, st>>>(
         (const CostT *)cost, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out,
         applied_log, status_out);
     return hipGetLastError();
@@ -560,12 +704,20 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                          uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
+#ifdef MMBP_LDS_FORCE_BLOCK
+    const bool big = (MMBP_LDS_FORCE_BLOCK) > 256;
+#else
     const bool big = (N + 64 * M) > 2048;
-#define MMBP_LDS_LAUNCH(T, B) \
-    launch_one<T, B>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
-                     applied_log, status_out, st)
-    if (dtype == MMBP_I32) return big ? MMBP_LDS_LAUNCH(int32_t, 512) : MMBP_LDS_LAUNCH(int32_t, 256);
-    return big ? MMBP_LDS_LAUNCH(int64_t, 512) : MMBP_LDS_LAUNCH(int64_t, 256);
+#endif
+#define MMBP_LDS_LAUNCH(T, B, SM) \
+    launch_one<T, B, SM>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
+                         applied_log, status_out, st)
+#define MMBP_LDS_PICK(T) \
+    (big ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 512, true) : MMBP_LDS_LAUNCH(T, 512, false)) \
+         : (M <= 64 ? MMBP_LDS_LAUNCH(T, 256, true) : MMBP_LDS_LAUNCH(T, 256, false)))
+    if (dtype == MMBP_I32) return MMBP_LDS_PICK(int32_t);
+    return MMBP_LDS_PICK(int64_t);
+#undef MMBP_LDS_PICK
 #undef MMBP_LDS_LAUNCH
 }
 
