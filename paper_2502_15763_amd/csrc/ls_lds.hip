@@ -39,19 +39,23 @@ constexpr uint32_t kKeyLimit = 1u << 29;      // |y - x| of a real candidate is 
 constexpr uint32_t kInf = 0xFFFFFFFFu;
 constexpr uint16_t kNoJob = 0xFFFFu;
 constexpr int kRMax = 4;                       // row segments (of 64 positions) per tile
+#ifndef MMBP_LDS_CHUNK
+#define MMBP_LDS_CHUNK 128
+#endif
+#ifndef MMBP_LDS_WPE
+#define MMBP_LDS_WPE 4
+#endif
+constexpr int kChunk = MMBP_LDS_CHUNK;         // columns per task
 constexpr size_t kLdsLimit = 64 * 1024;
 
 struct Ctrl {
-    unsigned long long k0;        // min (job << 32 | pos) over flagged non-critical jobs
-    unsigned long long pair;      // min (job_e << 32 | job_f) over re-examined pairs
-    unsigned long long mv;        // min (move id << 32 | pos)
     unsigned long long evals;
-    unsigned long long pairs_per_scan;
+    unsigned long long pairs_per_scan, pairs_before;
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
     uint32_t vswap, vmove;
-    int nE, nF, nfeas, P;
+    int nfeas, P, rebuild;
     uint32_t top_v[3];            // three largest loads and their clients, published by wave 0
     int top_j[3];
     int passes, status, stop, iters;
@@ -268,10 +272,11 @@ __device__ __forceinline__ Top3 wave_top3_small(uint32_t vload, int M, int lane)
     return t;
 }
 
-// One row unit (R row segments of client g starting at rowbase) against the column clients whose
-// flattened task index falls in [lo, hi); `first` is the task index of the unit's first column
-// client.  Column clients of g: the non-empty clients after g except the critical one, then the
-// critical one.
+// One row unit (R row segments of client g starting at rowbase) against the column chunks whose
+// flattened task index falls in [lo, hi); `first` is the task index of the unit's first chunk.
+// Column clients of g: the non-empty clients after g except the critical one, then the critical
+// one; each is cut into chunks of kChunk columns.  The best makespan of a row against the
+// critical client is min-combined into rowkey (its chunks may run on different waves).
 template <int R, bool SMALLM>
 __device__ __forceinline__ void row_unit(const Lds &l, const Clients<SMALLM> &cl, const Top3 &top, int M, int astar,
                                          int g, uint32_t la, int rowbase, int lane, int first, int lo, int hi,
@@ -286,24 +291,31 @@ __device__ __forceinline__ void row_unit(const Lds &l, const Clients<SMALLM> &cl
         if (bb < M && b == astar) continue;
         const int nb = cl.cnt(b);
         if (nb == 0) continue;
-        const int my = idx++;
-        if (my < lo) continue;
-        if (my >= hi) break;
+        const int nch = (nb + kChunk - 1) / kChunk;
+        if (idx + nch <= lo) { idx += nch; continue; }
+        if (idx >= hi) break;
         const uint32_t lb = cl.load(b);
-        const int c0 = cl.start(b);
-        const int c1 = min(c0 + ((nb + 7) & ~7), cl.maxp);
-        if (c1 <= c0) continue;
-        uint32_t x[R], key[R];
-#pragma unroll
-        for (int r = 0; r < R; r++) x[r] = rowx[r] - (la - lb);
-        tile_columns<R>(l.cu, x, c0, c1, key);
+        const int cbase = cl.start(b);
+        const int cend = min(cbase + ((nb + 7) & ~7), cl.maxp);
         const uint32_t oth = others_max(top, g, b);
         const uint32_t lsum = la + lb;
+        uint32_t x[R];
 #pragma unroll
-        for (int r = 0; r < R; r++) {
-            const uint32_t v = rowx[r] != kPad ? swap_value(key[r], lsum, oth) : kInf;
-            sbest = min(sbest, v);
-            if (b == astar) l.rowkey[rowbase + 64 * r + lane] = v;
+        for (int r = 0; r < R; r++) x[r] = rowx[r] - (la - lb);
+        for (int ch = 0; ch < nch; ch++, idx++) {
+            if (idx < lo) continue;
+            if (idx >= hi) break;
+            const int c0 = cbase + ch * kChunk;
+            const int c1 = min(c0 + kChunk, cend);
+            if (c1 <= c0) continue;
+            uint32_t key[R];
+            tile_columns<R>(l.cu, x, c0, c1, key);
+#pragma unroll
+            for (int r = 0; r < R; r++) {
+                const uint32_t v = rowx[r] != kPad ? swap_value(key[r], lsum, oth) : kInf;
+                sbest = min(sbest, v);
+                if (b == astar && v != kInf) atomicMin(&l.rowkey[rowbase + 64 * r + lane], v);
+            }
         }
     }
 }
@@ -332,7 +344,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
     for (int j = tid; j < M; j += BLOCK) l.fillc[j] = 0;
     __syncthreads();
     const int P = l.ctrl->P;
-    for (int p = tid; p < P; p += BLOCK) { l.cu[p] = kPad; l.job[p] = kNoJob; }
+    for (int p = tid; p < P; p += BLOCK) { l.cu[p] = kPad; l.job[p] = kNoJob; l.rowkey[p] = kInf; }
     __syncthreads();
     for (int i = tid; i < N; i += BLOCK) {
         const int a = asg[i];
@@ -344,7 +356,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
 }
 
 template <typename CostT, int BLOCK, bool SMALLM>
-__global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
+__global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     const CostT *__restrict__ cost_all, int N, int M, int cap, int max_passes, int32_t *assign_all,
     int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
     uint64_t *applied_log, int32_t *status_out)
@@ -362,7 +374,7 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
     for (int j = tid; j < M; j += BLOCK) { l.load[j] = 0; l.cnt[j] = 0; }
     if (tid == 0) {
         ctrl->bad_cost = 0; ctrl->bad_assign = 0; ctrl->passes = 0; ctrl->status = MMBP_ST_OK;
-        ctrl->stop = 0; ctrl->evals = 0;
+        ctrl->stop = 0; ctrl->evals = 0; ctrl->rebuild = 0; ctrl->pairs_before = 0;
     }
     __syncthreads();
     {
@@ -424,35 +436,45 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
     cl.l = &l;
     cl.maxn = N;
     cl.maxp = N + 64 * M;
-    if (tid == 0) ctrl->iters = 0;
+    const int Pmax = N + 64 * M;
 
-    // ---------------- pass loop ----------------
-    for (;;) {
-        // serial section of wave 0: pass accounting, then the three largest loads for everybody.
-        // Every loop of a pass is bounded by N, M and the padded size, every barrier is reached under
-        // conditions read from LDS after a barrier, and the pass loop itself is capped.
-        if (tid == 0) {
+    // Opens a pass (wave 0 only, all 64 lanes): pass accounting and the three largest loads for
+    // everybody.  Termination by construction: every loop of a pass is bounded by N, M and the
+    // padded size, every barrier is reached under conditions read from LDS after a barrier, and
+    // the pass loop itself is capped.
+    auto open_pass = [&]() {
+        __builtin_amdgcn_wave_barrier();   // lanes of a wave run in lockstep: lane 0's updates are complete
+        if (lane == 0) {
             ctrl->iters += 1;
             if ((long long)ctrl->iters > (long long)max_passes + 1) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
+            else if (ctrl->stop) { }
             else if (ctrl->passes == max_passes) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
             else ctrl->evals += (unsigned long long)N * (unsigned long long)(M - 1) + ctrl->pairs_per_scan;
             ctrl->vswap = kInf; ctrl->vmove = kInf;
-            ctrl->k0 = ~0ull; ctrl->pair = ~0ull; ctrl->mv = ~0ull;
-            ctrl->nE = 0; ctrl->nF = 0;
         }
-        if (wave == 0) {
-            // the lanes of wave 0 run in lockstep with thread 0, so its load updates above are complete
-            __builtin_amdgcn_wave_barrier();
-            const Top3 t = SMALLM ? wave_top3_small(lane < M ? (uint32_t)l.load[lane] : 0u, M, lane)
-                                  : wave_top3(l.load, M, lane);
-            if (lane == 0) {
-                for (int r = 0; r < 3; r++) { ctrl->top_v[r] = t.v[r]; ctrl->top_j[r] = t.j[r]; }
+        const Top3 t = SMALLM ? wave_top3_small(lane < M ? (uint32_t)l.load[lane] : 0u, M, lane)
+                              : wave_top3(l.load, M, lane);
+        if (lane == 0) {
+            for (int r = 0; r < 3; r++) { ctrl->top_v[r] = t.v[r]; ctrl->top_j[r] = t.j[r]; }
+        }
+    };
+    if (tid == 0) ctrl->iters = 0;
+    if (wave == 0) open_pass();        // pairs_per_scan was set by build_layout (barrier inside)
+
+    // ---------------- pass loop ----------------
+    for (;;) {
+        __syncthreads();                                 // B0: layout, loads, top-3 and flags are published
+        if (ctrl->stop) break;
+        if (ctrl->rebuild) {                             // a move was applied: regroup the jobs
+            build_layout<CostT, BLOCK>(l, c, asg, N, M, cap);
+            if (tid == 0) {                              // (after the last barrier of build_layout: nobody
+                ctrl->rebuild = 0;                       //  reads the flag before the next B0)
+                ctrl->evals -= ctrl->pairs_before;       // the pair count of the scan that starts now
+                ctrl->evals += ctrl->pairs_per_scan;
             }
         }
-        __syncthreads();
-        if (ctrl->stop) break;
 
-        const int P = min(ctrl->P, N + 64 * M) & ~63;
+        const int P = min(ctrl->P, Pmax) & ~63;
         const int nseg = P >> 6;
         const int nfeas = min(ctrl->nfeas, M);
         cl.refresh(M, lane);
@@ -484,26 +506,27 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
         }
 
         // ---- swaps: value only.  Every unordered client pair once, the critical client always as
-        // columns.  Tasks (row unit, column client) are numbered in row-major order and each wave
+        // columns.  Tasks (row unit, column chunk) are numbered in row-major order and each wave
         // takes a contiguous range, so consecutive tasks of a wave reuse the rows in registers. ----
         uint32_t sbest = kInf;
         {
-            const bool star_ok = cl.cnt(astar) > 0;
-            int ntask = 0, nonempty = 0;
+            const int nstar = cl.cnt(astar);
+            const int chstar = (nstar + kChunk - 1) / kChunk;
+            int ntask = 0, chafter = 0;                    // chunks of the non-empty, non-critical clients after g
             for (int g = M - 1; g >= 0; g--) {
                 const int ng = cl.cnt(g);
                 if (ng == 0 || g == astar) continue;
-                ntask += ((((ng + 63) >> 6) + kRMax - 1) / kRMax) * (nonempty + (star_ok ? 1 : 0));
-                nonempty++;
+                ntask += ((((ng + 63) >> 6) + kRMax - 1) / kRMax) * (chafter + chstar);
+                chafter += (ng + kChunk - 1) / kChunk;
             }
             const int lo = (int)(((long long)ntask * wave) / kWaves);
             const int hi = (int)(((long long)ntask * (wave + 1)) / kWaves);
-            int base = 0, after = nonempty;
+            int base = 0;
             for (int g = 0; g < M && base < hi; g++) {
                 const int ng = cl.cnt(g);
                 if (ng == 0 || g == astar) continue;
-                after--;                                   // non-empty, non-critical clients after g
-                const int ncol = after + (star_ok ? 1 : 0);
+                chafter -= (ng + kChunk - 1) / kChunk;
+                const int ncol = chafter + chstar;
                 const int gbase = cl.start(g);
                 const int gseg = min((ng + 63) >> 6, (cl.maxp - gbase) >> 6);
                 const uint32_t la = cl.load(g);
@@ -525,20 +548,22 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
             if (mbest != kInf) atomicMin(&ctrl->vmove, mbest);
             if (sbest != kInf) atomicMin(&ctrl->vswap, sbest);
         }
-        __syncthreads();
+        __syncthreads();                                 // B1: all candidate values are in
+        if (wave != 0) continue;                         // selection, apply and the next pass opening: wave 0
 
         const uint32_t Vm = ctrl->vmove, Vs = ctrl->vswap;
         const uint32_t V = min(Vm, Vs);
-        if (V >= T) break;                               // local optimum (status stays OK)
-
+        if (V >= T) {                                    // local optimum (status stays OK)
+            if (lane == 0) ctrl->stop = 1;
+            continue;
+        }
         if (Vm <= Vs) {
             // ---- a move wins (move ids are below swap ids): lowest id among moves of value V ----
             unsigned long long best = ~0ull;
-            for (int seg = wave; seg < nseg; seg += kWaves) {
+            for (int seg = 0; seg < nseg; seg++) {
                 const int g = l.seg_grp[seg];
                 const int p = seg * 64 + lane;
                 const uint32_t x = l.cu[p];
-                if (x == kPad) continue;
                 const uint32_t ci = (x - kBias) >> 1;
                 const uint32_t la = load32(g);
                 const uint32_t jb = l.job[p];
@@ -546,21 +571,18 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
                     const int b = l.feas[q];
                     if (b == g) continue;
                     const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
-                    if (v == V) {
+                    if (x != kPad && v == V) {
                         const unsigned long long id = (unsigned long long)jb * (unsigned long long)M + (unsigned long long)b;
                         best = min(best, (id << 32) | (unsigned long long)p);
                     }
                 }
             }
             best = wave_min_u64(best);
-            if (lane == 0 && best != ~0ull) atomicMin(&ctrl->mv, best);
-            __syncthreads();
-            if (tid == 0) {
-                const unsigned long long mvv = ctrl->mv;
-                const uint32_t id = (uint32_t)(mvv >> 32);
-                const int p = (int)(uint32_t)mvv;
+            if (lane == 0) {
+                const uint32_t id = (uint32_t)(best >> 32);
+                const int p = (int)(uint32_t)best;
                 const int i = (int)(id / (uint32_t)M), b = (int)(id % (uint32_t)M);
-                if (mvv == ~0ull || i >= N || p >= P) {
+                if (best == ~0ull || i >= N || p >= P) {
                     ctrl->status = MMBP_ST_INTERNAL;     // cannot happen: the best move was found above
                     ctrl->stop = 1;
                 } else {
@@ -571,10 +593,11 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
                     asg[i] = b;
                     if (applied_log) applied_log[(size_t)s * max_passes + ctrl->passes] = (uint64_t)id;
                     ctrl->passes += 1;
+                    ctrl->rebuild = 1;
+                    ctrl->pairs_before = ctrl->pairs_per_scan;
                 }
             }
-            __syncthreads();
-            build_layout<CostT, BLOCK>(l, c, asg, N, M, cap);
+            open_pass();
             continue;
         }
 
@@ -583,45 +606,47 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
         // row minimum against the critical client equals V. ----
         const uint32_t lstar = load32(astar);
         const int sbase = min(max(l.gstart[astar], 0), P), scnt = min(max(l.cnt[astar], 0), P - sbase);
-        const int send = sbase + scnt, sslots = sbase + ((scnt + 63) & ~63);
-        // A: flagged jobs (non-critical side of a best swap); k0 = the lowest of them
-        {
-            unsigned long long k0 = ~0ull;
-            for (int p = tid; p < P; p += BLOCK) {
-                if (p >= sbase && p < sslots) continue;
-                if (l.rowkey[p] == V) {
-                    const uint32_t jb = l.job[p];
-                    const int idx = atomicAdd(&ctrl->nF, 1);
-                    l.list[idx] = (uint16_t)p;
-                    k0 = min(k0, ((unsigned long long)jb << 32) | (unsigned long long)p);
-                }
+        const int send = sbase + scnt;
+        // A: flagged jobs (non-critical side of a best swap), k0 = the lowest of them.  rowkey goes
+        // back to "none" for the next pass while it is read.
+        int nF = 0;
+        unsigned long long k0 = ~0ull;
+        for (int p0 = 0; p0 < P; p0 += kWave) {
+            const int p = p0 + lane;
+            const uint32_t v = l.rowkey[p];
+            l.rowkey[p] = kInf;
+            const bool flag = v == V;
+            const unsigned long long m = __ballot(flag);
+            if (flag) {
+                l.list[nF + __popcll(m & ((1ull << lane) - 1ull))] = (uint16_t)p;
+                k0 = min(k0, ((unsigned long long)l.job[p] << 32) | (unsigned long long)p);
             }
-            k0 = wave_min_u64(k0);
-            if (lane == 0 && k0 != ~0ull) atomicMin(&ctrl->k0, k0);
+            nF += __popcll(m);
         }
-        __syncthreads();
-        if (ctrl->k0 == ~0ull) {                         // cannot happen: a best swap has a flagged job
-            if (tid == 0) ctrl->status = MMBP_ST_INTERNAL;
-            break;
+        k0 = wave_min_u64(k0);
+        if (k0 == ~0ull) {                               // cannot happen: a best swap has a flagged job
+            if (lane == 0) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
+            continue;
         }
-        const uint32_t k0job = (uint32_t)(ctrl->k0 >> 32);
-        const int k0pos = min((int)(uint32_t)ctrl->k0, P - 1);
+        const uint32_t k0job = (uint32_t)(k0 >> 32);
+        const int k0pos = min((int)(uint32_t)k0, P - 1);
         // B: critical jobs with a lower index than k0 (only they can give a lower id than k0's swaps)
-        for (int p = sbase + tid; p < send; p += BLOCK) {
-            if ((uint32_t)l.job[p] < k0job) {
-                const int idx = atomicAdd(&ctrl->nE, 1);
-                l.list[P - 1 - idx] = (uint16_t)p;
-            }
+        int nE = 0;
+        for (int p0 = sbase; p0 < send; p0 += kWave) {
+            const int p = p0 + lane;
+            const bool early = p < send && (uint32_t)l.job[p] < k0job;
+            const unsigned long long m = __ballot(early);
+            if (early) l.list[P - 1 - (nE + __popcll(m & ((1ull << lane) - 1ull)))] = (uint16_t)p;
+            nE += __popcll(m);
         }
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();                 // the lists are read by other lanes of this wave
+        // C: pairs (early critical job e, flagged job f), id (job_e, job_f);
+        // D: pairs (k0, later critical job),              id (k0, job).
+        // Candidates are packed (i:16 | k:16 | pos_i:16 | pos_k:16); the smallest wins.
+        unsigned long long best = ~0ull;
         {
-            // C: pairs (early critical job e, flagged job f), id (job_e, job_f);
-            // D: pairs (k0, later critical job),              id (k0, job).
-            // Candidates are packed (i:16 | k:16 | pos_i:16 | pos_k:16); the smallest wins.
-            const int nE = min(ctrl->nE, scnt), nF = min(ctrl->nF, P);
-            unsigned long long best = ~0ull;
             const int npair = nE * nF;
-            for (int q = tid; q < npair; q += BLOCK) {
+            for (int q = lane; q < npair; q += kWave) {
                 const int e = q / nF, f = q - e * nF;
                 const int pe = l.list[P - 1 - e], pf = l.list[f];
                 const int g = l.seg_grp[pf >> 6];
@@ -631,44 +656,40 @@ __global__ __launch_bounds__(BLOCK) void ls_lds_kernel(
                     best = min(best, ((unsigned long long)l.job[pe] << 48) | ((unsigned long long)l.job[pf] << 32) |
                                          ((unsigned long long)pe << 16) | (unsigned long long)pf);
             }
-            {
-                const int g = l.seg_grp[k0pos >> 6];
-                const uint32_t lg = load32(g);
-                const uint32_t xk = l.cu[k0pos] - (lg - lstar);
-                const uint32_t oth = others_max(top, g, astar);
-                for (int p = sbase + tid; p < send; p += BLOCK) {
-                    const uint32_t jb = l.job[p];
-                    if (jb > k0job && swap_value(absdiff_u32(l.cu[p], xk), lg + lstar, oth) == V)
-                        best = min(best, ((unsigned long long)k0job << 48) | ((unsigned long long)jb << 32) |
-                                             ((unsigned long long)k0pos << 16) | (unsigned long long)p);
-                }
+            const int g = l.seg_grp[k0pos >> 6];
+            const uint32_t lg = load32(g);
+            const uint32_t xk = l.cu[k0pos] - (lg - lstar);
+            const uint32_t oth = others_max(top, g, astar);
+            for (int p = sbase + lane; p < send; p += kWave) {
+                const uint32_t jb = l.job[p];
+                if (jb > k0job && swap_value(absdiff_u32(l.cu[p], xk), lg + lstar, oth) == V)
+                    best = min(best, ((unsigned long long)k0job << 48) | ((unsigned long long)jb << 32) |
+                                         ((unsigned long long)k0pos << 16) | (unsigned long long)p);
             }
-            best = wave_min_u64(best);
-            if (lane == 0 && best != ~0ull) atomicMin(&ctrl->pair, best);
         }
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned long long pr = ctrl->pair;
+        best = wave_min_u64(best);
+        if (lane == 0) {
+            const unsigned long long pr = best;
             const uint32_t ji = (uint32_t)(pr >> 48), jk = (uint32_t)(pr >> 32) & 0xFFFFu;     // ji < jk
             const int pi = (int)((pr >> 16) & 0xFFFFu), pk = (int)(pr & 0xFFFFu);
             if (pr == ~0ull || ji >= (uint32_t)N || jk >= (uint32_t)N || pi >= P || pk >= P) {
                 ctrl->status = MMBP_ST_INTERNAL;         // cannot happen: the best swap was found above
                 ctrl->stop = 1;
             } else {
-            const int ga = l.seg_grp[pi >> 6], gb = l.seg_grp[pk >> 6];
-            const uint32_t xi = l.cu[pi], xk = l.cu[pk];
-            const long long d = (long long)((xi - kBias) >> 1) - (long long)((xk - kBias) >> 1);
-            l.load[ga] -= d; l.load[gb] += d;
-            l.cu[pi] = xk; l.cu[pk] = xi;
-            l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
-            asg[ji] = gb; asg[jk] = ga;
-            if (applied_log)
-                applied_log[(size_t)s * max_passes + ctrl->passes] =
-                    (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
-            ctrl->passes += 1;
+                const int ga = l.seg_grp[pi >> 6], gb = l.seg_grp[pk >> 6];
+                const uint32_t xi = l.cu[pi], xk = l.cu[pk];
+                const long long d = (long long)((xi - kBias) >> 1) - (long long)((xk - kBias) >> 1);
+                l.load[ga] -= d; l.load[gb] += d;
+                l.cu[pi] = xk; l.cu[pk] = xi;
+                l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
+                asg[ji] = gb; asg[jk] = ga;
+                if (applied_log)
+                    applied_log[(size_t)s * max_passes + ctrl->passes] =
+                        (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
+                ctrl->passes += 1;
             }
         }
-        // the barrier at the top of the next pass orders the update before its readers
+        open_pass();
     }
 
     // ---------------- write back ----------------
@@ -689,7 +710,10 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
-    const size_t bytes = lds_bytes(N, M);
+    size_t bytes = lds_bytes(N, M);
+#ifdef MMBP_LDS_MINBYTES
+    if (bytes < (size_t)(MMBP_LDS_MINBYTES)) bytes = (size_t)(MMBP_LDS_MINBYTES);
+#endif
     ls_lds_kernel<CostT, BLOCK, SMALLM><<<dim3(S), dim3(BLOCK), bytes, st>>>(
         (const CostT *)cost, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out,
         applied_log, status_out);
@@ -704,17 +728,21 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                          uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
+    // workgroup size by padded problem size: more waves shorten a pass when the workgroup is alone
+    // on its CU at the tail of a batch
 #ifdef MMBP_LDS_FORCE_BLOCK
-    const bool big = (MMBP_LDS_FORCE_BLOCK) > 256;
+    const int block = (MMBP_LDS_FORCE_BLOCK);
 #else
-    const bool big = (N + 64 * M) > 2048;
+    const int pmax = N + 64 * M;
+    const int block = pmax <= 2048 ? 256 : 512;
 #endif
 #define MMBP_LDS_LAUNCH(T, B, SM) \
     launch_one<T, B, SM>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
                          applied_log, status_out, st)
 #define MMBP_LDS_PICK(T) \
-    (big ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 512, true) : MMBP_LDS_LAUNCH(T, 512, false)) \
-         : (M <= 64 ? MMBP_LDS_LAUNCH(T, 256, true) : MMBP_LDS_LAUNCH(T, 256, false)))
+    (block == 256 ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 256, true) : MMBP_LDS_LAUNCH(T, 256, false)) \
+     : block == 512 ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 512, true) : MMBP_LDS_LAUNCH(T, 512, false)) \
+                    : (M <= 64 ? MMBP_LDS_LAUNCH(T, 1024, true) : MMBP_LDS_LAUNCH(T, 1024, false)))
     if (dtype == MMBP_I32) return MMBP_LDS_PICK(int32_t);
     return MMBP_LDS_PICK(int64_t);
 #undef MMBP_LDS_PICK
