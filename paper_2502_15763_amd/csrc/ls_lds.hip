@@ -27,18 +27,11 @@
 // which can win neither the minimum nor (negated) the maximum against a real column.  Scenarios
 // that do not satisfy the bound stay pending for the 64-bit kernel.
 #include "mmbp_dev.hpp"
+#include "ls_tile.hpp"
 
 namespace mmbp {
 namespace {
 
-constexpr uint32_t kBias = 1u << 30;
-constexpr uint32_t kNarrowLimit = 1u << 29;   // narrowing needs T0 + 2 * max cost below this
-constexpr uint32_t kPad = 0xC0000000u;        // cu of an empty position
-constexpr uint32_t kKeyLimit = 1u << 29;      // |y - x| of a real candidate is below this; keys that come
-                                              // from empty columns or from the absent side are >= 3 * 2^29
-constexpr uint32_t kInf = 0xFFFFFFFFu;
-constexpr uint16_t kNoJob = 0xFFFFu;
-constexpr int kRMax = 4;                       // row segments (of 64 positions) per tile
 #ifndef MMBP_LDS_CHUNK
 #define MMBP_LDS_CHUNK 128
 #endif
@@ -109,109 +102,6 @@ __device__ inline Lds carve(unsigned char *base, int N, int M)
     o = align_up(o, 16);
     l.ctrl = (Ctrl *)(base + o);
     return l;
-}
-
-__device__ __forceinline__ uint32_t absdiff_u32(uint32_t a, uint32_t b) { return max(a, b) - min(a, b); }
-
-// Running nearest-above / nearest-below search of one row against four columns.
-struct RowAcc {
-    uint32_t up;   // min over columns of (y - x) mod 2^32
-    uint32_t mx;   // max over columns of (y - x) mod 2^32
-};
-__device__ __forceinline__ void nearest_x4(RowAcc &a, uint32_t x, const uint4 &c)
-{
-    const uint32_t d0 = c.x - x, d1 = c.y - x, d2 = c.z - x, d3 = c.w - x;
-    a.up = min(min(a.up, d0), d1);
-    a.mx = max(max(a.mx, d0), d1);
-    a.up = min(min(a.up, d2), d3);
-    a.mx = max(max(a.mx, d2), d3);
-}
-__device__ __forceinline__ uint32_t nearest_key(const RowAcc &a) { return min(a.up, 0u - a.mx); }
-
-__device__ __forceinline__ unsigned long long sat_add62(unsigned long long a, unsigned long long b)
-{
-    unsigned long long r = a + b;
-    return r >= (unsigned long long)kCostSumLimit ? (unsigned long long)kCostSumLimit : r;
-}
-
-__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
-__device__ __forceinline__ uint32_t uniu(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
-
-// three largest loads with their clients (lowest client index first among equal loads)
-struct Top3 {
-    uint32_t v[3];
-    int j[3];
-};
-
-__device__ __forceinline__ Top3 wave_top3(const long long *load, int M, int lane)
-{
-    Top3 t;
-    int ex0 = -1, ex1 = -1;
-#pragma unroll
-    for (int r = 0; r < 3; r++) {
-        uint32_t bv = 0, bj = kInf;
-        for (int j = lane; j < M; j += kWave) {
-            if (j == ex0 || j == ex1) continue;
-            uint32_t l = (uint32_t)load[j];
-            if (bj == kInf || l > bv) { bv = l; bj = (uint32_t)j; }
-        }
-        uint32_t mv = wave_max_u32(bv);
-        uint32_t mj = wave_min_u32((bv == mv) ? bj : kInf);
-        t.v[r] = (mj == kInf) ? 0u : mv;
-        t.j[r] = (int)mj;                       // -1 when fewer than r+1 clients
-        if (r == 0) ex0 = (int)mj; else ex1 = (int)mj;
-    }
-    return t;
-}
-
-__device__ __forceinline__ uint32_t others_max(const Top3 &t, int a, int b)
-{
-    if (t.j[0] != a && t.j[0] != b) return t.v[0];
-    if (t.j[1] != a && t.j[1] != b) return t.v[1];
-    return t.v[2];
-}
-
-// makespan of a swap candidate from its key |y - x|: twice the larger changed load is
-// l_a + l_b + key; the other loads contribute the largest untouched one
-__device__ __forceinline__ uint32_t swap_value(uint32_t key, uint32_t lsum, uint32_t others)
-{
-    return key < kKeyLimit ? max(others, (lsum + key) >> 1) : kInf;
-}
-
-// Tile: R rows per lane (x[r], already shifted by l_a - l_b) against the columns [c0, c1)
-// ((c1 - c0) % 8 == 0, > 0).  key[r] = min over the columns of |cu[col] - x[r]|.  Two register
-// sets in ping-pong: the LDS loads of one are in flight while the other is evaluated.
-template <int R>
-__device__ __forceinline__ void tile_columns(const uint32_t *cu, const uint32_t (&x)[R], int c0, int c1,
-                                             uint32_t (&key)[R])
-{
-    RowAcc acc[R];
-#pragma unroll
-    for (int r = 0; r < R; r++) { acc[r].up = kInf; acc[r].mx = 0u; }
-    const uint4 *col = reinterpret_cast<const uint4 *>(cu + c0);
-    const int n8 = (c1 - c0) >> 3;
-    uint4 a0 = col[0], a1 = col[1], b0, b1;
-    int k = 1;
-    for (; k + 1 < n8; k += 2) {
-        b0 = col[2 * k]; b1 = col[2 * k + 1];
-#pragma unroll
-        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], a0); nearest_x4(acc[r], x[r], a1); }
-        a0 = col[2 * k + 2]; a1 = col[2 * k + 3];
-#pragma unroll
-        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], b0); nearest_x4(acc[r], x[r], b1); }
-    }
-    if (k < n8) {
-        b0 = col[2 * k]; b1 = col[2 * k + 1];
-#pragma unroll
-        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], a0); nearest_x4(acc[r], x[r], a1); }
-#pragma unroll
-        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], b0); nearest_x4(acc[r], x[r], b1); }
-    } else {
-#pragma unroll
-        for (int r = 0; r < R; r++) { nearest_x4(acc[r], x[r], a0); nearest_x4(acc[r], x[r], a1); }
-    }
-#pragma unroll
-    for (int r = 0; r < R; r++) key[r] = nearest_key(acc[r]);
 }
 
 // Per-client counts, layout starts and loads as seen by one wave.  With M <= 64 they sit one per

@@ -139,6 +139,20 @@ def test_ls_config4(oracle, slack, passes):
     compare_ls(g, o, label=f"c4 slack={slack}")
 
 
+def test_ls_multi_workgroup_path_batch(oracle):
+    """Shapes too large for one workgroup's LDS, several scenarios per call, slack capacity so that
+    moves and swaps are both applied; one scenario needs the 64-bit path."""
+    rng = np.random.default_rng(77)
+    S, N, M, cap = 3, 6000, 6, 1100
+    cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=30000, dtype=np.int32, start="rr")
+    cost = cost.astype(np.int64)
+    cost[2] *= 1 << 16                      # loads above the 32-bit narrowing bound
+    say(f"ls multi-workgroup batch S={S} N={N} M={M}")
+    o = oracle.local_search(cost, assign, M, cap, 6, want_log=True)
+    g = gpu_local_search(cost, assign, M, cap, 6)
+    compare_ls(g, o, label="multi-workgroup batch")
+
+
 # ------------------------------------------------------------------ lower bound
 def test_lb_parity(oracle):
     rng = np.random.default_rng(31)
