@@ -15,17 +15,32 @@
 // With d = y - x taken modulo 2^32, the smallest d is the distance to the nearest column at or
 // above x and the negated largest d the distance to the nearest column below x, so a candidate
 // costs one v_sub_u32 plus half a v_min3_u32 and half a v_max3_u32, all full-rate VALU
-// (v_sad_u32 would fuse them but issues at quarter rate).  Each unordered client pair is evaluated once; the client with the largest load
-// ("critical") is always the column side, so the per-row minima against it are known for every
-// other job.  They resolve the lowest-id tie-break exactly: an improving swap must involve the
-// critical client, the jobs that take part in a best swap are read off the row minima, and only
-// the few pairs that can carry the lowest id are re-examined.
+// (v_sad_u32 would fuse them but issues at quarter rate).
+//
+// Tasks.  Every unordered client pair is evaluated once.  A table built with the layout lists the
+// tasks (row unit of client g: up to 4 segments of 64 rows) x (chunk of up to kChunk columns of a
+// client b > g); each wave takes a contiguous range of it, so a pass costs a wave two readlanes and
+// one LDS record per task.  The client with the largest load ("critical") must be the column
+// side (the per-row minima against it resolve the tie-break, below): a task whose row client is
+// critical is run transposed (the chunk's positions become the rows, the unit's the columns).
+//
+// Exact lowest-id tie-break without a second full scan.  An improving swap involves the critical
+// client.  Phase 1 min-combines, per non-critical job, its best makespan against the critical
+// client (rowkey) and tracks the smallest (makespan, job) of those.  After the barrier wave 0 knows
+// the best value V and k0 = the lowest-index non-critical job of a best swap; only critical jobs
+// with a lower index than k0 can carry a lower id: if there are any, they are paired with the
+// flagged jobs (rowkey == V); k0's own partners are scanned; the packed minimum (i, k, pos_i,
+// pos_k) is applied.  Moves are value-only in phase 1 and rescanned for the id when a move wins.
 //
 // Exactness: all loads stay at or below the initial makespan T0; with T0 + 2*max T_i < 2^29 every
 // quantity above is exact in 32 bits: x lies in (2^29, 3*2^29), a real |y - x| is below 2^29, a
 // wrapped difference is above 7*2^29, and an empty column (cu = 6*2^29) gives d in (3*2^29, 5*2^29),
 // which can win neither the minimum nor (negated) the maximum against a real column.  Scenarios
 // that do not satisfy the bound stay pending for the 64-bit kernel.
+//
+// Termination by construction: every loop of a pass is bounded by N, M and the padded size, every
+// barrier is reached under conditions read from LDS after a barrier, the pass loop is capped, and
+// states that cannot occur stop the scenario with MMBP_ST_INTERNAL instead of being acted on.
 #include "mmbp_dev.hpp"
 #include "ls_tile.hpp"
 
@@ -38,17 +53,20 @@ namespace {
 #ifndef MMBP_LDS_WPE
 #define MMBP_LDS_WPE 4
 #endif
-constexpr int kChunk = MMBP_LDS_CHUNK;         // columns per task
-constexpr size_t kLdsLimit = 64 * 1024;
+constexpr int kChunk = MMBP_LDS_CHUNK;         // columns per task (multiple of 64, at most 256)
+constexpr size_t kLdsLimit = 78 * 1024;        // two workgroups per CU (160 KB); above 64 KB the launch raises the
+                                               // kernel's dynamic-LDS attribute first
+static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnable as the row side of a tile");
 
 struct Ctrl {
     unsigned long long evals;
     unsigned long long pairs_per_scan, pairs_before;
+    unsigned long long k0key;     // min over the rows against the critical client of (makespan << 32 | job << 16 | pos)
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
     uint32_t vswap, vmove;
-    int nfeas, P, rebuild;
+    int nfeas, P, rebuild, ntask, nchunk;
     uint32_t top_v[3];            // three largest loads and their clients, published by wave 0
     int top_j[3];
     int passes, status, stop, iters;
@@ -56,28 +74,46 @@ struct Ctrl {
 };
 
 struct Lds {
-    uint32_t *cu, *rowkey;   // rowkey[p]: best swap makespan of the job at p against the critical client
+    uint32_t *cu, *rowkey;        // rowkey[p]: best swap makespan of the job at p against the critical client
     uint16_t *job, *list;
+    unsigned long long *tasks;    // (rowbase/64 | R << 10 | g << 13) | chunk record << 32
+    uint32_t *chunks;             // c0/64 | ncols << 10 | b << 19
     long long *load;
-    int *cnt, *gstart, *fillc, *feas;
+    int *cnt, *gstart, *fillc, *feas, *chpre, *upre;
     uint8_t *seg_grp;
     Ctrl *ctrl;
 };
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+struct LdsDims {
+    size_t P, U, C, T;            // padded positions, row units, column chunks, tasks (upper bounds)
+};
+__host__ __device__ inline LdsDims lds_dims(int N, int M)
+{
+    LdsDims d;
+    d.P = ((size_t)N + 63u) / 64u * 64u + 64u * (size_t)M;   // multiple of 64: keeps every array 16-byte aligned
+    d.U = d.P / (64u * kRMax) + (size_t)M;
+    d.C = (size_t)N / kChunk + (size_t)M;
+    d.T = d.U * d.C;
+    return d;
+}
+
 __host__ __device__ inline size_t lds_bytes(int N, int M)
 {
-    const size_t P = (size_t)N + 64u * (size_t)M;
+    const LdsDims d = lds_dims(N, M);
     size_t b = 0;
-    b += 4 * P;                       // cu
-    b += 4 * P;                       // rowkey
-    b += 2 * P;                       // job
-    b += 2 * P;                       // list
+    b += 4 * d.P;                     // cu
+    b += 4 * d.P;                     // rowkey
+    b += 2 * d.P;                     // job
+    b += 2 * d.P;                     // list
+    b = align_up(b, 16);
+    b += 8 * d.T;                     // tasks
+    b += 4 * d.C;                     // chunks
     b = align_up(b, 16);
     b += 8 * (size_t)M;               // load
-    b += 4 * (size_t)(M + 1) * 4;     // cnt, gstart, fillc, feas
-    b += align_up(P / 64 + 1, 16);    // seg_grp
+    b += 4 * (size_t)(M + 1) * 6;     // cnt, gstart, fillc, feas, chpre, upre
+    b += align_up(d.P / 64 + 1, 16);  // seg_grp
     b = align_up(b, 16);
     b += sizeof(Ctrl);
     return b;
@@ -85,57 +121,29 @@ __host__ __device__ inline size_t lds_bytes(int N, int M)
 
 __device__ inline Lds carve(unsigned char *base, int N, int M)
 {
-    const size_t P = (size_t)N + 64u * (size_t)M;
+    const LdsDims d = lds_dims(N, M);
     Lds l;
     size_t o = 0;
-    l.cu = (uint32_t *)(base + o); o += 4 * P;
-    l.rowkey = (uint32_t *)(base + o); o += 4 * P;
-    l.job = (uint16_t *)(base + o); o += 2 * P;
-    l.list = (uint16_t *)(base + o); o += 2 * P;
+    l.cu = (uint32_t *)(base + o); o += 4 * d.P;
+    l.rowkey = (uint32_t *)(base + o); o += 4 * d.P;
+    l.job = (uint16_t *)(base + o); o += 2 * d.P;
+    l.list = (uint16_t *)(base + o); o += 2 * d.P;
+    o = align_up(o, 16);
+    l.tasks = (unsigned long long *)(base + o); o += 8 * d.T;
+    l.chunks = (uint32_t *)(base + o); o += 4 * d.C;
     o = align_up(o, 16);
     l.load = (long long *)(base + o); o += 8 * (size_t)M;
     l.cnt = (int *)(base + o); o += 4 * (size_t)(M + 1);
     l.gstart = (int *)(base + o); o += 4 * (size_t)(M + 1);
     l.fillc = (int *)(base + o); o += 4 * (size_t)(M + 1);
     l.feas = (int *)(base + o); o += 4 * (size_t)(M + 1);
-    l.seg_grp = (uint8_t *)(base + o); o += align_up(P / 64 + 1, 16);
+    l.chpre = (int *)(base + o); o += 4 * (size_t)(M + 1);
+    l.upre = (int *)(base + o); o += 4 * (size_t)(M + 1);
+    l.seg_grp = (uint8_t *)(base + o); o += align_up(d.P / 64 + 1, 16);
     o = align_up(o, 16);
     l.ctrl = (Ctrl *)(base + o);
     return l;
 }
-
-// Per-client counts, layout starts and loads as seen by one wave.  With M <= 64 they sit one per
-// lane and are fetched with v_readlane (no LDS round trip in the task loop); otherwise they are
-// read from LDS.
-template <bool SMALLM>
-struct Clients {
-    const Lds *l;
-    int maxn, maxp;               // clamps: a count never exceeds N, a start never exceeds the padded size
-    uint32_t vcnt, vstart, vload;
-    __device__ __forceinline__ void refresh(int M, int lane)
-    {
-        if (SMALLM) {
-            vcnt = lane < M ? (uint32_t)l->cnt[lane] : 0u;
-            vstart = lane < M ? (uint32_t)l->gstart[lane] : 0u;
-            vload = lane < M ? (uint32_t)l->load[lane] : 0u;
-        }
-    }
-    __device__ __forceinline__ int cnt(int g) const
-    {
-        const int v = SMALLM ? __builtin_amdgcn_readlane((int)vcnt, g) : __builtin_amdgcn_readfirstlane(l->cnt[g]);
-        return min(max(v, 0), maxn);
-    }
-    __device__ __forceinline__ int start(int g) const
-    {
-        const int v = SMALLM ? __builtin_amdgcn_readlane((int)vstart, g) : __builtin_amdgcn_readfirstlane(l->gstart[g]);
-        return min(max(v, 0), maxp) & ~63;
-    }
-    __device__ __forceinline__ uint32_t load(int g) const
-    {
-        return (uint32_t)(SMALLM ? __builtin_amdgcn_readlane((int)vload, g)
-                                 : __builtin_amdgcn_readfirstlane((int)(uint32_t)l->load[g]));
-    }
-};
 
 // three largest loads with their clients for M <= 64 (one load per lane): every lane ranks its
 // load against all others (ties: lower client first), the lanes of rank 0, 1, 2 are read back
@@ -162,85 +170,94 @@ __device__ __forceinline__ Top3 wave_top3_small(uint32_t vload, int M, int lane)
     return t;
 }
 
-// One row unit (R row segments of client g starting at rowbase) against the column chunks whose
-// flattened task index falls in [lo, hi); `first` is the task index of the unit's first chunk.
-// Column clients of g: the non-empty clients after g except the critical one, then the critical
-// one; each is cut into chunks of kChunk columns.  The best makespan of a row against the
-// critical client is min-combined into rowkey (its chunks may run on different waves).
-template <int R, bool SMALLM>
-__device__ __forceinline__ void row_unit(const Lds &l, const Clients<SMALLM> &cl, const Top3 &top, int M, int astar,
-                                         int g, uint32_t la, int rowbase, int lane, int first, int lo, int hi,
-                                         uint32_t &sbest)
+// One tile: rows = R segments at rowbase (client X, load lx), columns [c0, c1) (client Y, load ly).
+// star: Y is the critical client -> the rows' best makespans go to rowkey and to the (makespan,
+// job, pos) minimum kbest.
+template <int R>
+__device__ __forceinline__ void run_tile(const Lds &l, int rowbase, int c0, int c1, uint32_t lx, uint32_t ly,
+                                         uint32_t oth, bool star, int lane, uint32_t &sbest, unsigned long long &kbest)
 {
-    uint32_t rowx[R];
+    uint32_t rowx[R], x[R], key[R];
 #pragma unroll
-    for (int r = 0; r < R; r++) rowx[r] = l.cu[rowbase + 64 * r + lane];
-    int idx = first;
-    for (int bb = g + 1; bb <= M; bb++) {
-        const int b = (bb == M) ? astar : bb;
-        if (bb < M && b == astar) continue;
-        const int nb = cl.cnt(b);
-        if (nb == 0) continue;
-        const int nch = (nb + kChunk - 1) / kChunk;
-        if (idx + nch <= lo) { idx += nch; continue; }
-        if (idx >= hi) break;
-        const uint32_t lb = cl.load(b);
-        const int cbase = cl.start(b);
-        const int cend = min(cbase + ((nb + 7) & ~7), cl.maxp);
-        const uint32_t oth = others_max(top, g, b);
-        const uint32_t lsum = la + lb;
-        uint32_t x[R];
+    for (int r = 0; r < R; r++) {
+        rowx[r] = l.cu[rowbase + 64 * r + lane];
+        x[r] = rowx[r] - (lx - ly);
+    }
+    tile_columns<R>(l.cu, x, c0, c1, key);
 #pragma unroll
-        for (int r = 0; r < R; r++) x[r] = rowx[r] - (la - lb);
-        for (int ch = 0; ch < nch; ch++, idx++) {
-            if (idx < lo) continue;
-            if (idx >= hi) break;
-            const int c0 = cbase + ch * kChunk;
-            const int c1 = min(c0 + kChunk, cend);
-            if (c1 <= c0) continue;
-            uint32_t key[R];
-            tile_columns<R>(l.cu, x, c0, c1, key);
-#pragma unroll
-            for (int r = 0; r < R; r++) {
-                const uint32_t v = rowx[r] != kPad ? swap_value(key[r], lsum, oth) : kInf;
-                sbest = min(sbest, v);
-                if (b == astar && v != kInf) atomicMin(&l.rowkey[rowbase + 64 * r + lane], v);
-            }
+    for (int r = 0; r < R; r++) {
+        const uint32_t v = rowx[r] != kPad ? swap_value(key[r], lx + ly, oth) : kInf;
+        sbest = min(sbest, v);
+        if (star && v != kInf) {
+            const int p = rowbase + 64 * r + lane;
+            atomicMin(&l.rowkey[p], v);
+            kbest = min(kbest, ((unsigned long long)v << 32) | ((unsigned long long)l.job[p] << 16) | (unsigned long long)p);
         }
     }
 }
 
+// Groups the jobs by client and builds the chunk and task tables (all threads; barriers inside).
 template <typename CostT, int BLOCK>
 __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const int32_t *asg, int N, int M, int cap)
 {
     const int tid = threadIdx.x;
+    const LdsDims d = lds_dims(N, M);
     if (tid == 0) {
-        int pos = 0, nf = 0;
+        int pos = 0, nf = 0, nch = 0, nu = 0;
         unsigned long long sq = 0;
         for (int g = 0; g < M; g++) {
             l.gstart[g] = pos;
+            l.chpre[g] = min(nch, (int)d.C);
+            l.upre[g] = min(nu, (int)d.U);
             const int n = l.cnt[g];
-            const int ns = min((n + 63) >> 6, (N + 64 * M - pos) >> 6);
+            const int ns = min((n + 63) >> 6, (int)((d.P - pos) >> 6));
             for (int q = 0; q < ns; q++) l.seg_grp[(pos >> 6) + q] = (uint8_t)g;
             pos += ns * 64;
+            nch += (n + kChunk - 1) / kChunk;
+            nu += (ns + kRMax - 1) / kRMax;
             if (n < cap) l.feas[nf++] = g;
             sq += (unsigned long long)n * (unsigned long long)n;
         }
         l.gstart[M] = pos;
+        l.chpre[M] = min(nch, (int)d.C);
+        l.upre[M] = min(nu, (int)d.U);
         l.ctrl->P = pos;
         l.ctrl->nfeas = nf;
+        l.ctrl->nchunk = min(nch, (int)d.C);
+        l.ctrl->ntask = 0;
         l.ctrl->pairs_per_scan = ((unsigned long long)N * (unsigned long long)N - sq) / 2ull;
     }
     for (int j = tid; j < M; j += BLOCK) l.fillc[j] = 0;
     __syncthreads();
     const int P = l.ctrl->P;
     for (int p = tid; p < P; p += BLOCK) { l.cu[p] = kPad; l.job[p] = kNoJob; l.rowkey[p] = kInf; }
+    // chunk records: one thread per client
+    for (int g = tid; g < M; g += BLOCK) {
+        const int n = l.cnt[g], ncols = (n + 7) & ~7;
+        for (int k = l.chpre[g], q = 0; k < l.chpre[g + 1]; k++, q++)
+            l.chunks[k] = (uint32_t)((l.gstart[g] + q * kChunk) >> 6) | ((uint32_t)min(kChunk, ncols - q * kChunk) << 10) |
+                          ((uint32_t)g << 19);
+    }
     __syncthreads();
     for (int i = tid; i < N; i += BLOCK) {
         const int a = asg[i];
         const int p = l.gstart[a] + atomicAdd(&l.fillc[a], 1);
         l.cu[p] = 2u * (uint32_t)c[i] + kBias;
         l.job[p] = (uint16_t)i;
+    }
+    // task records: one thread per row unit; its tasks (all chunks of later clients) are contiguous
+    const int nU = l.upre[M], nCh = l.ctrl->nchunk;
+    for (int u = tid; u < nU; u += BLOCK) {
+        int g = 0;
+        while (g + 1 < M && l.upre[g + 1] <= u) g++;
+        const int blk = (u - l.upre[g]) * kRMax;
+        const int gseg = (l.gstart[g + 1] - l.gstart[g]) >> 6;
+        const uint32_t w0 = (uint32_t)((l.gstart[g] >> 6) + blk) | ((uint32_t)min(kRMax, gseg - blk) << 10) | ((uint32_t)g << 13);
+        const int k0 = l.chpre[g + 1], n = nCh - k0;
+        if (n <= 0) continue;
+        const int base = atomicAdd(&l.ctrl->ntask, n);
+        if (base + n > (int)d.T) continue;               // cannot happen: T bounds the table
+        for (int q = 0; q < n; q++) l.tasks[base + q] = (unsigned long long)w0 | ((unsigned long long)l.chunks[k0 + q] << 32);
     }
     __syncthreads();
 }
@@ -264,7 +281,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     for (int j = tid; j < M; j += BLOCK) { l.load[j] = 0; l.cnt[j] = 0; }
     if (tid == 0) {
         ctrl->bad_cost = 0; ctrl->bad_assign = 0; ctrl->passes = 0; ctrl->status = MMBP_ST_OK;
-        ctrl->stop = 0; ctrl->evals = 0; ctrl->rebuild = 0; ctrl->pairs_before = 0;
+        ctrl->stop = 0; ctrl->evals = 0; ctrl->rebuild = 0; ctrl->pairs_before = 0; ctrl->iters = 0;
     }
     __syncthreads();
     {
@@ -322,16 +339,11 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
 
     // loads stay below 2^29 on this path: their low words are used
     auto load32 = [&](int g) -> uint32_t { return (uint32_t)l.load[g]; };
-    Clients<SMALLM> cl;
-    cl.l = &l;
-    cl.maxn = N;
-    cl.maxp = N + 64 * M;
     const int Pmax = N + 64 * M;
+    const int Tmax = (int)lds_dims(N, M).T;
 
     // Opens a pass (wave 0 only, all 64 lanes): pass accounting and the three largest loads for
-    // everybody.  Termination by construction: every loop of a pass is bounded by N, M and the
-    // padded size, every barrier is reached under conditions read from LDS after a barrier, and
-    // the pass loop itself is capped.
+    // everybody; also puts the row minima back to "none" (they are min-combined during a pass).
     auto open_pass = [&]() {
         __builtin_amdgcn_wave_barrier();   // lanes of a wave run in lockstep: lane 0's updates are complete
         if (lane == 0) {
@@ -340,16 +352,18 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             else if (ctrl->stop) { }
             else if (ctrl->passes == max_passes) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
             else ctrl->evals += (unsigned long long)N * (unsigned long long)(M - 1) + ctrl->pairs_per_scan;
-            ctrl->vswap = kInf; ctrl->vmove = kInf;
+            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->k0key = ~0ull;
         }
         const Top3 t = SMALLM ? wave_top3_small(lane < M ? (uint32_t)l.load[lane] : 0u, M, lane)
                               : wave_top3(l.load, M, lane);
         if (lane == 0) {
             for (int r = 0; r < 3; r++) { ctrl->top_v[r] = t.v[r]; ctrl->top_j[r] = t.j[r]; }
         }
+        const int P = min(ctrl->P, Pmax) & ~63;
+        uint4 *rk = reinterpret_cast<uint4 *>(l.rowkey);
+        for (int q = lane; q < (P >> 2); q += kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
     };
-    if (tid == 0) ctrl->iters = 0;
-    if (wave == 0) open_pass();        // pairs_per_scan was set by build_layout (barrier inside)
+    if (wave == 0) open_pass();        // (build_layout ended with a barrier)
 
     // ---------------- pass loop ----------------
     for (;;) {
@@ -367,7 +381,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         const int P = min(ctrl->P, Pmax) & ~63;
         const int nseg = P >> 6;
         const int nfeas = min(ctrl->nfeas, M);
-        cl.refresh(M, lane);
+        const int ntask = min(ctrl->ntask, Tmax);
         Top3 top;
         for (int r = 0; r < 3; r++) {
             top.v[r] = uniu(ctrl->top_v[r]);
@@ -375,6 +389,10 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         }
         const uint32_t T = top.v[0];
         const int astar = min(max(top.j[0], 0), M - 1);
+        const uint32_t vload = SMALLM ? (lane < M ? (uint32_t)l.load[lane] : 0u) : 0u;   // one load per lane
+        auto wload = [&](int g) -> uint32_t {
+            return SMALLM ? (uint32_t)__builtin_amdgcn_readlane((int)vload, g) : uniu((uint32_t)l.load[g]);
+        };
 
         // ---- moves: value only ----
         uint32_t mbest = kInf;
@@ -395,48 +413,44 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             }
         }
 
-        // ---- swaps: value only.  Every unordered client pair once, the critical client always as
-        // columns.  Tasks (row unit, column chunk) are numbered in row-major order and each wave
-        // takes a contiguous range, so consecutive tasks of a wave reuse the rows in registers. ----
+        // ---- swaps: value only; this wave's contiguous range of the task table ----
         uint32_t sbest = kInf;
+        unsigned long long kbest = ~0ull;
         {
-            const int nstar = cl.cnt(astar);
-            const int chstar = (nstar + kChunk - 1) / kChunk;
-            int ntask = 0, chafter = 0;                    // chunks of the non-empty, non-critical clients after g
-            for (int g = M - 1; g >= 0; g--) {
-                const int ng = cl.cnt(g);
-                if (ng == 0 || g == astar) continue;
-                ntask += ((((ng + 63) >> 6) + kRMax - 1) / kRMax) * (chafter + chstar);
-                chafter += (ng + kChunk - 1) / kChunk;
-            }
             const int lo = (int)(((long long)ntask * wave) / kWaves);
             const int hi = (int)(((long long)ntask * (wave + 1)) / kWaves);
-            int base = 0;
-            for (int g = 0; g < M && base < hi; g++) {
-                const int ng = cl.cnt(g);
-                if (ng == 0 || g == astar) continue;
-                chafter -= (ng + kChunk - 1) / kChunk;
-                const int ncol = chafter + chstar;
-                const int gbase = cl.start(g);
-                const int gseg = min((ng + 63) >> 6, (cl.maxp - gbase) >> 6);
-                const uint32_t la = cl.load(g);
-                for (int blk = 0; blk < gseg; blk += kRMax, base += ncol) {
-                    if (base + ncol <= lo || base >= hi) continue;
-                    const int rowbase = gbase + blk * 64;
-                    switch (min(kRMax, gseg - blk)) {
-                    case 1: row_unit<1, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
-                    case 2: row_unit<2, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
-                    case 3: row_unit<3, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
-                    default: row_unit<4, SMALLM>(l, cl, top, M, astar, g, la, rowbase, lane, base, lo, hi, sbest); break;
-                    }
+            unsigned long long rec = lo < hi ? l.tasks[lo] : 0ull;
+            for (int t = lo; t < hi; t++) {
+                const uint32_t w0 = uniu((uint32_t)rec), w1 = uniu((uint32_t)(rec >> 32));
+                if (t + 1 < hi) rec = l.tasks[t + 1];                      // next record while this tile runs
+                int rowbase = (int)(w0 & 0x3FFu) << 6, R = (int)((w0 >> 10) & 7u), X = (int)((w0 >> 13) & 0xFFu);
+                int c0 = (int)(w1 & 0x3FFu) << 6, Y = (int)((w1 >> 19) & 0xFFu);
+                int c1 = c0 + (int)((w1 >> 10) & 0x1FFu);
+                if (X == astar) {                                            // the critical client must be the column side
+                    const int rb = c0, rr = (c1 - c0 + 63) >> 6;
+                    c0 = rowbase; c1 = rowbase + 64 * R;
+                    rowbase = rb; R = rr;
+                    const int q = X; X = Y; Y = q;
+                }
+                if (R < 1 || R > kRMax || c1 <= c0 || c1 > Pmax || rowbase + 64 * R > Pmax) continue;   // cannot happen
+                const uint32_t lx = wload(X), ly = wload(Y);
+                const uint32_t oth = others_max(top, X, Y);
+                const bool star = Y == astar;
+                switch (R) {
+                case 1: run_tile<1>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
+                case 2: run_tile<2>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
+                case 3: run_tile<3>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
+                default: run_tile<4>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
                 }
             }
         }
         mbest = wave_min_u32(mbest);
         sbest = wave_min_u32(sbest);
+        kbest = wave_min_u64(kbest);
         if (lane == 0) {
             if (mbest != kInf) atomicMin(&ctrl->vmove, mbest);
             if (sbest != kInf) atomicMin(&ctrl->vswap, sbest);
+            if (kbest != ~0ull) atomicMin(&ctrl->k0key, kbest);
         }
         __syncthreads();                                 // B1: all candidate values are in
         if (wave != 0) continue;                         // selection, apply and the next pass opening: wave 0
@@ -492,35 +506,18 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         }
 
         // ---- a swap wins: lowest (min(i,k), max(i,k)) among swaps of value V.  An improving swap
-        // involves the critical client, so every best swap pairs a critical job with a job whose
-        // row minimum against the critical client equals V. ----
-        const uint32_t lstar = load32(astar);
-        const int sbase = min(max(l.gstart[astar], 0), P), scnt = min(max(l.cnt[astar], 0), P - sbase);
-        const int send = sbase + scnt;
-        // A: flagged jobs (non-critical side of a best swap), k0 = the lowest of them.  rowkey goes
-        // back to "none" for the next pass while it is read.
-        int nF = 0;
-        unsigned long long k0 = ~0ull;
-        for (int p0 = 0; p0 < P; p0 += kWave) {
-            const int p = p0 + lane;
-            const uint32_t v = l.rowkey[p];
-            l.rowkey[p] = kInf;
-            const bool flag = v == V;
-            const unsigned long long m = __ballot(flag);
-            if (flag) {
-                l.list[nF + __popcll(m & ((1ull << lane) - 1ull))] = (uint16_t)p;
-                k0 = min(k0, ((unsigned long long)l.job[p] << 32) | (unsigned long long)p);
-            }
-            nF += __popcll(m);
-        }
-        k0 = wave_min_u64(k0);
-        if (k0 == ~0ull) {                               // cannot happen: a best swap has a flagged job
+        // involves the critical client; k0 = the lowest-index non-critical job of a best swap. ----
+        const unsigned long long k0key = ctrl->k0key;
+        if ((uint32_t)(k0key >> 32) != V) {              // cannot happen: the best swap is in a critical tile
             if (lane == 0) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
             continue;
         }
-        const uint32_t k0job = (uint32_t)(k0 >> 32);
-        const int k0pos = min((int)(uint32_t)k0, P - 1);
-        // B: critical jobs with a lower index than k0 (only they can give a lower id than k0's swaps)
+        const uint32_t k0job = (uint32_t)(k0key >> 16) & 0xFFFFu;
+        const int k0pos = min((int)(k0key & 0xFFFFu), P - 1);
+        const uint32_t lstar = load32(astar);
+        const int sbase = min(max(l.gstart[astar], 0), P), scnt = min(max(l.cnt[astar], 0), P - sbase);
+        const int send = sbase + scnt;
+        // E: critical jobs with a lower index than k0 (only they can give a lower id than k0's swaps)
         int nE = 0;
         for (int p0 = sbase; p0 < send; p0 += kWave) {
             const int p = p0 + lane;
@@ -529,12 +526,18 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             if (early) l.list[P - 1 - (nE + __popcll(m & ((1ull << lane) - 1ull)))] = (uint16_t)p;
             nE += __popcll(m);
         }
-        __builtin_amdgcn_wave_barrier();                 // the lists are read by other lanes of this wave
-        // C: pairs (early critical job e, flagged job f), id (job_e, job_f);
-        // D: pairs (k0, later critical job),              id (k0, job).
-        // Candidates are packed (i:16 | k:16 | pos_i:16 | pos_k:16); the smallest wins.
         unsigned long long best = ~0ull;
-        {
+        if (nE > 0) {
+            // F: flagged jobs (rowkey == V), then the pairs (early critical job e, flagged job f)
+            int nF = 0;
+            for (int p0 = 0; p0 < P; p0 += kWave) {
+                const int p = p0 + lane;
+                const bool flag = l.rowkey[p] == V;
+                const unsigned long long m = __ballot(flag);
+                if (flag) l.list[nF + __popcll(m & ((1ull << lane) - 1ull))] = (uint16_t)p;
+                nF += __popcll(m);
+            }
+            __builtin_amdgcn_wave_barrier();             // the lists are read by other lanes of this wave
             const int npair = nE * nF;
             for (int q = lane; q < npair; q += kWave) {
                 const int e = q / nF, f = q - e * nF;
@@ -546,6 +549,9 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                     best = min(best, ((unsigned long long)l.job[pe] << 48) | ((unsigned long long)l.job[pf] << 32) |
                                          ((unsigned long long)pe << 16) | (unsigned long long)pf);
             }
+        }
+        {
+            // k0's partners among the later critical jobs: id (k0, job)
             const int g = l.seg_grp[k0pos >> 6];
             const uint32_t lg = load32(g);
             const uint32_t xk = l.cu[k0pos] - (lg - lstar);
@@ -604,6 +610,15 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
 #ifdef MMBP_LDS_MINBYTES
     if (bytes < (size_t)(MMBP_LDS_MINBYTES)) bytes = (size_t)(MMBP_LDS_MINBYTES);
 #endif
+    if (bytes > 64 * 1024) {
+        static bool raised = false;                      // per instantiation; setting it twice is harmless
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ls_lds_kernel<CostT, BLOCK, SMALLM>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
     ls_lds_kernel<CostT, BLOCK, SMALLM><<<dim3(S), dim3(BLOCK), bytes, st>>>(
         (const CostT *)cost, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out,
         applied_log, status_out);
@@ -612,7 +627,7 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
 
 }  // namespace
 
-bool ls_lds_fits(int N, int M) { return N < 65535 && lds_bytes(N, M) <= kLdsLimit; }
+bool ls_lds_fits(int N, int M) { return N < 65535 && N + 64 * M <= 65536 && lds_bytes(N, M) <= kLdsLimit; }
 
 hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
@@ -624,7 +639,7 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
     const int block = (MMBP_LDS_FORCE_BLOCK);
 #else
     const int pmax = N + 64 * M;
-    const int block = pmax <= 2048 ? 256 : 512;
+    const int block = pmax <= 512 ? 256 : 512;
 #endif
 #define MMBP_LDS_LAUNCH(T, B, SM) \
     launch_one<T, B, SM>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
