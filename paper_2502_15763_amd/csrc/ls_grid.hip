@@ -32,8 +32,7 @@ constexpr uint32_t kNoJob32 = 0xFFFFFFFFu;
 struct GCtrl {
     unsigned long long evals, pairs_per_scan, k0, pair, mv;
     uint32_t vswap, vmove;
-    uint32_t top_v[3];
-    int top_j[3];
+    Top3 top;
     int P, nfeas, ntask, passes, status, stop, iters;
 };
 
@@ -181,15 +180,14 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
             *s_ntask = 0;
         }
         const Top3 t = wave_top3(w.load, M, lane);
-        if (lane == 0)
-            for (int r = 0; r < 3; r++) { ctrl->top_v[r] = t.v[r]; ctrl->top_j[r] = t.j[r]; }
+        if (lane == 0) ctrl->top = t;
     }
     __syncthreads();
     if (ctrl->stop) { g_finish(w, o, s, M); return false; }
     const int P = min(ctrl->P, w.pmax);
     for (int p = tid; p < P; p += kSelBlock) w.rowkey[p] = kInf;
     // task table: every unordered pair of non-empty clients once, the critical client as columns
-    const int astar = min(max(ctrl->top_j[0], 0), M - 1);
+    const int astar = min(max(ctrl->top.j0, 0), M - 1);
     for (int q = tid; q < M * M; q += kSelBlock) {
         const int g = q / M, b = q - g * M;
         if (g >= b) continue;
@@ -324,8 +322,9 @@ __global__ __launch_bounds__(kEvalBlock) void grid_eval_kernel(int N, int M, voi
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __shared__ __align__(16) uint32_t cols[kColChunk];
     Top3 top;
-    for (int r = 0; r < 3; r++) { top.v[r] = uniu(ctrl->top_v[r]); top.j[r] = uni(ctrl->top_j[r]); }
-    const int astar = min(max(top.j[0], 0), M - 1);
+    top.v0 = uniu(ctrl->top.v0); top.v1 = uniu(ctrl->top.v1); top.v2 = uniu(ctrl->top.v2);
+    top.j0 = uni(ctrl->top.j0); top.j1 = uni(ctrl->top.j1); top.j2 = uni(ctrl->top.j2);
+    const int astar = min(max(top.j0, 0), M - 1);
     const int ntask = min(ctrl->ntask, w.tmax);
     const int P = min(ctrl->P, w.pmax);
     uint32_t sbest = kInf, mbest = kInf;
@@ -397,9 +396,10 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
     __shared__ unsigned long long s_k0, s_best;
 
     Top3 top;
-    for (int r = 0; r < 3; r++) { top.v[r] = uniu(ctrl->top_v[r]); top.j[r] = uni(ctrl->top_j[r]); }
-    const uint32_t T = top.v[0];
-    const int astar = min(max(top.j[0], 0), M - 1);
+    top.v0 = uniu(ctrl->top.v0); top.v1 = uniu(ctrl->top.v1); top.v2 = uniu(ctrl->top.v2);
+    top.j0 = uni(ctrl->top.j0); top.j1 = uni(ctrl->top.j1); top.j2 = uni(ctrl->top.j2);
+    const uint32_t T = top.v0;
+    const int astar = min(max(top.j0, 0), M - 1);
     const int P = min(ctrl->P, w.pmax);
     const int nfeas = min(ctrl->nfeas, M);
     const uint32_t Vm = ctrl->vmove, Vs = ctrl->vswap;

@@ -59,27 +59,26 @@ constexpr size_t kLdsLimit = 78 * 1024;        // two workgroups per CU (160 KB)
 static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnable as the row side of a tile");
 
 struct Ctrl {
-    unsigned long long evals;
-    unsigned long long pairs_per_scan, pairs_before;
+    unsigned long long pairs_per_scan;
     unsigned long long k0key;     // min over the rows against the critical client of (makespan << 32 | job << 16 | pos)
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
     uint32_t vswap, vmove;
     int nfeas, P, rebuild, ntask, nchunk;
-    uint32_t top_v[3];            // three largest loads and their clients, published by wave 0
-    int top_j[3];
-    int passes, status, stop, iters;
+    Top3 top;                     // three largest loads and their clients, published by wave 0
+    int stop;
     int bad_cost, bad_assign;
 };
 
 struct Lds {
     uint32_t *cu, *rowkey;        // rowkey[p]: best swap makespan of the job at p against the critical client
-    uint16_t *job, *list;
+    uint16_t *job;
     unsigned long long *tasks;    // (rowbase/64 | R << 10 | g << 13) | chunk record << 32
     uint32_t *chunks;             // c0/64 | ncols << 10 | b << 19
     long long *load;
     int *cnt, *gstart, *fillc, *feas, *chpre, *upre;
+    uint32_t *tdl, *tr1;          // per client, for the selection: l_g - l_critical and the key bound of a best swap
     uint8_t *seg_grp;
     Ctrl *ctrl;
 };
@@ -106,13 +105,12 @@ __host__ __device__ inline size_t lds_bytes(int N, int M)
     b += 4 * d.P;                     // cu
     b += 4 * d.P;                     // rowkey
     b += 2 * d.P;                     // job
-    b += 2 * d.P;                     // list
     b = align_up(b, 16);
     b += 8 * d.T;                     // tasks
     b += 4 * d.C;                     // chunks
     b = align_up(b, 16);
     b += 8 * (size_t)M;               // load
-    b += 4 * (size_t)(M + 1) * 6;     // cnt, gstart, fillc, feas, chpre, upre
+    b += 4 * (size_t)(M + 1) * 8;     // cnt, gstart, fillc, feas, chpre, upre, tdl, tr1
     b += align_up(d.P / 64 + 1, 16);  // seg_grp
     b = align_up(b, 16);
     b += sizeof(Ctrl);
@@ -127,7 +125,6 @@ __device__ inline Lds carve(unsigned char *base, int N, int M)
     l.cu = (uint32_t *)(base + o); o += 4 * d.P;
     l.rowkey = (uint32_t *)(base + o); o += 4 * d.P;
     l.job = (uint16_t *)(base + o); o += 2 * d.P;
-    l.list = (uint16_t *)(base + o); o += 2 * d.P;
     o = align_up(o, 16);
     l.tasks = (unsigned long long *)(base + o); o += 8 * d.T;
     l.chunks = (uint32_t *)(base + o); o += 4 * d.C;
@@ -139,6 +136,8 @@ __device__ inline Lds carve(unsigned char *base, int N, int M)
     l.feas = (int *)(base + o); o += 4 * (size_t)(M + 1);
     l.chpre = (int *)(base + o); o += 4 * (size_t)(M + 1);
     l.upre = (int *)(base + o); o += 4 * (size_t)(M + 1);
+    l.tdl = (uint32_t *)(base + o); o += 4 * (size_t)(M + 1);
+    l.tr1 = (uint32_t *)(base + o); o += 4 * (size_t)(M + 1);
     l.seg_grp = (uint8_t *)(base + o); o += align_up(d.P / 64 + 1, 16);
     o = align_up(o, 16);
     l.ctrl = (Ctrl *)(base + o);
@@ -154,19 +153,15 @@ __device__ __forceinline__ Top3 wave_top3_small(uint32_t vload, int M, int lane)
         const uint32_t li = (uint32_t)__builtin_amdgcn_readlane((int)vload, i);
         rank += (li > vload || (li == vload && i < lane)) ? 1 : 0;
     }
-    Top3 t;
-#pragma unroll
-    for (int r = 0; r < 3; r++) {
+    auto ranked = [&](int r, uint32_t &v, int &jout) {
         const unsigned long long m = __ballot(lane < M && rank == r);
-        if (m) {
-            const int j = __builtin_ctzll(m);
-            t.j[r] = j;
-            t.v[r] = (uint32_t)__builtin_amdgcn_readlane((int)vload, j);
-        } else {
-            t.j[r] = -1;
-            t.v[r] = 0u;
-        }
-    }
+        jout = m ? (int)__builtin_ctzll(m) : -1;
+        v = m ? (uint32_t)__builtin_amdgcn_readlane((int)vload, jout & 63) : 0u;
+    };
+    Top3 t;
+    ranked(0, t.v0, t.j0);
+    ranked(1, t.v1, t.j1);
+    ranked(2, t.v2, t.j2);
     return t;
 }
 
@@ -280,8 +275,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     // ---------------- stage: validation, counts, loads ----------------
     for (int j = tid; j < M; j += BLOCK) { l.load[j] = 0; l.cnt[j] = 0; }
     if (tid == 0) {
-        ctrl->bad_cost = 0; ctrl->bad_assign = 0; ctrl->passes = 0; ctrl->status = MMBP_ST_OK;
-        ctrl->stop = 0; ctrl->evals = 0; ctrl->rebuild = 0; ctrl->pairs_before = 0; ctrl->iters = 0;
+        ctrl->bad_cost = 0; ctrl->bad_assign = 0; ctrl->stop = 0; ctrl->rebuild = 0;
     }
     __syncthreads();
     {
@@ -341,29 +335,37 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     auto load32 = [&](int g) -> uint32_t { return (uint32_t)l.load[g]; };
     const int Pmax = N + 64 * M;
     const int Tmax = (int)lds_dims(N, M).T;
+    // A workgroup's waves go round the four SIMDs of its CU; the two halves of a SIMD's waves get
+    // neighbouring ranges of the task table, so the SIMDs carry equal shares when waves outnumber them.
+    const int twave = kWaves >= 8 ? (wave & 3) * (kWaves / 4) + (wave >> 2) : wave;
 
-    // Opens a pass (wave 0 only, all 64 lanes): pass accounting and the three largest loads for
-    // everybody; also puts the row minima back to "none" (they are min-combined during a pass).
-    auto open_pass = [&]() {
-        __builtin_amdgcn_wave_barrier();   // lanes of a wave run in lockstep: lane 0's updates are complete
+    // Pass accounting lives in wave 0's registers (uniform); LDS only carries what the other
+    // waves read: the stop and rebuild flags, the three largest loads, the per-pass minima.
+    int w_passes = 0, w_iters = 0, w_status = MMBP_ST_OK;
+    bool w_stop = false;
+    unsigned long long w_evals = 0, w_pairs = ctrl->pairs_per_scan;
+
+    // Opens a pass (wave 0 only, all 64 lanes): accounting, the three largest loads for everybody,
+    // the per-pass minima and the row minima back to "none".  vnew: lane j holds the load of
+    // client j (SMALLM only; otherwise the loads are read back from LDS).
+    auto open_pass = [&](uint32_t vnew) {
+        w_iters += 1;
+        if ((long long)w_iters > (long long)max_passes + 1) { w_status = MMBP_ST_INTERNAL; w_stop = true; }
+        else if (w_stop) { }
+        else if (w_passes == max_passes) { w_status = MMBP_ST_TRUNCATED; w_stop = true; }
+        else w_evals += (unsigned long long)N * (unsigned long long)(M - 1) + w_pairs;
+        __builtin_amdgcn_wave_barrier();   // lanes of a wave run in lockstep: earlier LDS updates are complete
+        const Top3 t = SMALLM ? wave_top3_small(vnew, M, lane) : wave_top3(l.load, M, lane);
         if (lane == 0) {
-            ctrl->iters += 1;
-            if ((long long)ctrl->iters > (long long)max_passes + 1) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
-            else if (ctrl->stop) { }
-            else if (ctrl->passes == max_passes) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
-            else ctrl->evals += (unsigned long long)N * (unsigned long long)(M - 1) + ctrl->pairs_per_scan;
+            ctrl->top = t;
             ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->k0key = ~0ull;
-        }
-        const Top3 t = SMALLM ? wave_top3_small(lane < M ? (uint32_t)l.load[lane] : 0u, M, lane)
-                              : wave_top3(l.load, M, lane);
-        if (lane == 0) {
-            for (int r = 0; r < 3; r++) { ctrl->top_v[r] = t.v[r]; ctrl->top_j[r] = t.j[r]; }
+            if (w_stop) ctrl->stop = 1;
         }
         const int P = min(ctrl->P, Pmax) & ~63;
         uint4 *rk = reinterpret_cast<uint4 *>(l.rowkey);
         for (int q = lane; q < (P >> 2); q += kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
     };
-    if (wave == 0) open_pass();        // (build_layout ended with a barrier)
+    if (wave == 0) open_pass(SMALLM ? (lane < M ? load32(lane) : 0u) : 0u);   // (build_layout ended with a barrier)
 
     // ---------------- pass loop ----------------
     for (;;) {
@@ -371,11 +373,11 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         if (ctrl->stop) break;
         if (ctrl->rebuild) {                             // a move was applied: regroup the jobs
             build_layout<CostT, BLOCK>(l, c, asg, N, M, cap);
-            if (tid == 0) {                              // (after the last barrier of build_layout: nobody
-                ctrl->rebuild = 0;                       //  reads the flag before the next B0)
-                ctrl->evals -= ctrl->pairs_before;       // the pair count of the scan that starts now
-                ctrl->evals += ctrl->pairs_per_scan;
-            }
+            if (tid == 0) ctrl->rebuild = 0;             // (after the last barrier of build_layout: nobody
+                                                         //  reads the flag before the next B0)
+            const unsigned long long np = ctrl->pairs_per_scan;
+            w_evals = w_evals - w_pairs + np;            // the pair count of the scan that starts now
+            w_pairs = np;
         }
 
         const int P = min(ctrl->P, Pmax) & ~63;
@@ -383,15 +385,13 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         const int nfeas = min(ctrl->nfeas, M);
         const int ntask = min(ctrl->ntask, Tmax);
         Top3 top;
-        for (int r = 0; r < 3; r++) {
-            top.v[r] = uniu(ctrl->top_v[r]);
-            top.j[r] = uni(ctrl->top_j[r]);
-        }
-        const uint32_t T = top.v[0];
-        const int astar = min(max(top.j[0], 0), M - 1);
-        const uint32_t vload = SMALLM ? (lane < M ? (uint32_t)l.load[lane] : 0u) : 0u;   // one load per lane
+        top.v0 = uniu(ctrl->top.v0); top.v1 = uniu(ctrl->top.v1); top.v2 = uniu(ctrl->top.v2);
+        top.j0 = uni(ctrl->top.j0); top.j1 = uni(ctrl->top.j1); top.j2 = uni(ctrl->top.j2);
+        const uint32_t T = top.v0;
+        const int astar = min(max(top.j0, 0), M - 1);
+        const uint32_t vload = SMALLM ? (lane < M ? load32(lane) : 0u) : 0u;   // one load per lane
         auto wload = [&](int g) -> uint32_t {
-            return SMALLM ? (uint32_t)__builtin_amdgcn_readlane((int)vload, g) : uniu((uint32_t)l.load[g]);
+            return SMALLM ? (uint32_t)__builtin_amdgcn_readlane((int)vload, g) : uniu(load32(g));
         };
 
         // ---- moves: value only ----
@@ -417,8 +417,8 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         uint32_t sbest = kInf;
         unsigned long long kbest = ~0ull;
         {
-            const int lo = (int)(((long long)ntask * wave) / kWaves);
-            const int hi = (int)(((long long)ntask * (wave + 1)) / kWaves);
+            const int lo = (int)(((long long)ntask * twave) / kWaves);
+            const int hi = (int)(((long long)ntask * (twave + 1)) / kWaves);
             unsigned long long rec = lo < hi ? l.tasks[lo] : 0ull;
             for (int t = lo; t < hi; t++) {
                 const uint32_t w0 = uniu((uint32_t)rec), w1 = uniu((uint32_t)(rec >> 32));
@@ -436,15 +436,15 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 const uint32_t lx = wload(X), ly = wload(Y);
                 const uint32_t oth = others_max(top, X, Y);
                 const bool star = Y == astar;
-                switch (R) {
-                case 1: run_tile<1>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
-                case 2: run_tile<2>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
-                case 3: run_tile<3>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
-                default: run_tile<4>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest); break;
+                if (R == 1) run_tile<1>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
+                else if (R == 2) run_tile<2>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
+                else if constexpr (kRMax >= 3) {
+                    if (R == 3) run_tile<3>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
+                    else run_tile<kRMax>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
                 }
             }
         }
-        mbest = wave_min_u32(mbest);
+        if (nfeas > 0) mbest = wave_min_u32(mbest);
         sbest = wave_min_u32(sbest);
         kbest = wave_min_u64(kbest);
         if (lane == 0) {
@@ -455,7 +455,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         __syncthreads();                                 // B1: all candidate values are in
         if (wave != 0) continue;                         // selection, apply and the next pass opening: wave 0
 
-        const uint32_t Vm = ctrl->vmove, Vs = ctrl->vswap;
+        const uint32_t Vm = uniu(ctrl->vmove), Vs = uniu(ctrl->vswap);
         const uint32_t V = min(Vm, Vs);
         if (V >= T) {                                    // local optimum (status stays OK)
             if (lane == 0) ctrl->stop = 1;
@@ -482,110 +482,197 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 }
             }
             best = wave_min_u64(best);
-            if (lane == 0) {
-                const uint32_t id = (uint32_t)(best >> 32);
-                const int p = (int)(uint32_t)best;
-                const int i = (int)(id / (uint32_t)M), b = (int)(id % (uint32_t)M);
-                if (best == ~0ull || i >= N || p >= P) {
-                    ctrl->status = MMBP_ST_INTERNAL;     // cannot happen: the best move was found above
-                    ctrl->stop = 1;
-                } else {
-                    const int a = l.seg_grp[p >> 6];
-                    const long long ci = (long long)((l.cu[p] - kBias) >> 1);
-                    l.load[a] -= ci; l.load[b] += ci;
+            const uint32_t id = (uint32_t)(best >> 32);
+            const int p = (int)(uint32_t)best;
+            const int i = (int)(id / (uint32_t)M), b = (int)(id % (uint32_t)M);
+            uint32_t vnew = vload;
+            if (best == ~0ull || i >= N || p >= P) {
+                w_status = MMBP_ST_INTERNAL;             // cannot happen: the best move was found above
+                w_stop = true;
+            } else {
+                const int a = uni(l.seg_grp[p >> 6]);
+                const uint32_t ci = (uniu(l.cu[p]) - kBias) >> 1;
+                if (SMALLM) {
+                    vnew = vload - (lane == a ? ci : 0u) + (lane == b ? ci : 0u);
+                    if (lane == a || lane == b) l.load[lane] = (long long)vnew;
+                }
+                if (lane == 0) {
+                    if (!SMALLM) { l.load[a] -= (long long)ci; l.load[b] += (long long)ci; }
                     l.cnt[a] -= 1; l.cnt[b] += 1;
                     asg[i] = b;
-                    if (applied_log) applied_log[(size_t)s * max_passes + ctrl->passes] = (uint64_t)id;
-                    ctrl->passes += 1;
+                    if (applied_log) applied_log[(size_t)s * max_passes + w_passes] = (uint64_t)id;
                     ctrl->rebuild = 1;
-                    ctrl->pairs_before = ctrl->pairs_per_scan;
                 }
+                w_passes += 1;
             }
-            open_pass();
+            open_pass(vnew);
             continue;
         }
 
         // ---- a swap wins: lowest (min(i,k), max(i,k)) among swaps of value V.  An improving swap
-        // involves the critical client; k0 = the lowest-index non-critical job of a best swap. ----
+        // involves the critical client, and its other job f is flagged (rowkey[f] == V).  k0 = the
+        // lowest-index flagged job.  Candidates: k0 with its critical partners, and the critical
+        // jobs with a lower index than k0 ("early") with theirs. ----
         const unsigned long long k0key = ctrl->k0key;
         if ((uint32_t)(k0key >> 32) != V) {              // cannot happen: the best swap is in a critical tile
-            if (lane == 0) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
+            w_status = MMBP_ST_INTERNAL; w_stop = true;
+            open_pass(vload);
             continue;
         }
-        const uint32_t k0job = (uint32_t)(k0key >> 16) & 0xFFFFu;
-        const int k0pos = min((int)(k0key & 0xFFFFu), P - 1);
-        const uint32_t lstar = load32(astar);
-        const int sbase = min(max(l.gstart[astar], 0), P), scnt = min(max(l.cnt[astar], 0), P - sbase);
+        const uint32_t k0job = uniu((uint32_t)(k0key >> 16) & 0xFFFFu);
+        const int k0pos = min(uni((int)(k0key & 0xFFFFu)), P - 1);
+        const uint32_t lstar = wload(astar);
+        const int sbase = min(max(uni(l.gstart[astar]), 0), P), scnt = min(max(uni(l.cnt[astar]), 0), P - sbase);
         const int send = sbase + scnt;
-        // E: critical jobs with a lower index than k0 (only they can give a lower id than k0's swaps)
+        unsigned long long best = ~0ull;
+
+        // all critical jobs against the flagged job at pf (uniform): every swap of value V
+        auto pair_with = [&](int pf) {
+            const int g = uni(l.seg_grp[pf >> 6]);
+            const uint32_t lg = wload(g), jf = uniu(l.job[pf]);
+            const uint32_t xf = uniu(l.cu[pf]) - (lg - lstar);
+            const uint32_t oth = others_max(top, g, astar);
+            for (int p = sbase + lane; p < send; p += kWave) {
+                const uint32_t je = l.job[p];
+                if (swap_value(absdiff_u32(l.cu[p], xf), lg + lstar, oth) == V) {
+                    const unsigned long long lo = je < jf ? ((unsigned long long)je << 48) | ((unsigned long long)jf << 32) |
+                                                                ((unsigned long long)p << 16) | (unsigned long long)pf
+                                                          : ((unsigned long long)jf << 48) | ((unsigned long long)je << 32) |
+                                                                ((unsigned long long)pf << 16) | (unsigned long long)p;
+                    best = min(best, lo);
+                }
+            }
+        };
+        pair_with(k0pos);
+
+        // early critical jobs: are there any?
         int nE = 0;
         for (int p0 = sbase; p0 < send; p0 += kWave) {
             const int p = p0 + lane;
-            const bool early = p < send && (uint32_t)l.job[p] < k0job;
-            const unsigned long long m = __ballot(early);
-            if (early) l.list[P - 1 - (nE + __popcll(m & ((1ull << lane) - 1ull)))] = (uint16_t)p;
-            nE += __popcll(m);
+            nE += __popcll(__ballot(p < send && (uint32_t)l.job[p] < k0job));
         }
-        unsigned long long best = ~0ull;
         if (nE > 0) {
-            // F: flagged jobs (rowkey == V), then the pairs (early critical job e, flagged job f)
-            int nF = 0;
-            for (int p0 = 0; p0 < P; p0 += kWave) {
-                const int p = p0 + lane;
-                const bool flag = l.rowkey[p] == V;
-                const unsigned long long m = __ballot(flag);
-                if (flag) l.list[nF + __popcll(m & ((1ull << lane) - 1ull))] = (uint16_t)p;
-                nF += __popcll(m);
+            // Per client g, for a flagged job f of g and a critical job e: the swap has value V
+            // <=> |cu_e - (cu_f - tdl[g])| < tr1[g]  (tr1 = 0: no swap with g reaches V).
+            for (int g = lane; g < M; g += kWave) {
+                const uint32_t lg = load32(g), lsum = lg + lstar;
+                const bool ok = g != astar && others_max(top, g, astar) <= V && lsum <= 2u * V + 1u;
+                l.tdl[g] = lg - lstar;
+                l.tr1[g] = ok ? 2u * V + 2u - lsum : 0u;
             }
-            __builtin_amdgcn_wave_barrier();             // the lists are read by other lanes of this wave
-            const int npair = nE * nF;
-            for (int q = lane; q < npair; q += kWave) {
-                const int e = q / nF, f = q - e * nF;
-                const int pe = l.list[P - 1 - e], pf = l.list[f];
-                const int g = l.seg_grp[pf >> 6];
-                const uint32_t lg = load32(g);
-                const uint32_t key = absdiff_u32(l.cu[pe], l.cu[pf] - (lg - lstar));
-                if (swap_value(key, lg + lstar, others_max(top, g, astar)) == V)
-                    best = min(best, ((unsigned long long)l.job[pe] << 48) | ((unsigned long long)l.job[pf] << 32) |
-                                         ((unsigned long long)pe << 16) | (unsigned long long)pf);
-            }
-        }
-        {
-            // k0's partners among the later critical jobs: id (k0, job)
-            const int g = l.seg_grp[k0pos >> 6];
-            const uint32_t lg = load32(g);
-            const uint32_t xk = l.cu[k0pos] - (lg - lstar);
-            const uint32_t oth = others_max(top, g, astar);
-            for (int p = sbase + lane; p < send; p += kWave) {
-                const uint32_t jb = l.job[p];
-                if (jb > k0job && swap_value(absdiff_u32(l.cu[p], xk), lg + lstar, oth) == V)
-                    best = min(best, ((unsigned long long)k0job << 48) | ((unsigned long long)jb << 32) |
-                                         ((unsigned long long)k0pos << 16) | (unsigned long long)p);
+            __builtin_amdgcn_wave_barrier();
+            const uint4 *cu4 = reinterpret_cast<const uint4 *>(l.cu);
+            const uint4 *rk4 = reinterpret_cast<const uint4 *>(l.rowkey);
+            const uint2 *job2 = reinterpret_cast<const uint2 *>(l.job);
+            // The early jobs are taken in increasing index order, four at a time, each batch against
+            // every flagged job; the first batch with a partner holds the lowest id (a partner f of an
+            // early job e is flagged, so job(f) >= job(k0) > job(e)).  If the first batch finds nothing
+            // and few jobs are flagged, those are paired with all critical jobs instead.
+            int lastjob = -1, nF = 0, nrec = 0;
+            int f0 = 0, f1 = 0, f2 = 0, f3 = 0;
+            for (int round = 0; round * 4 < nE; round++) {
+                int ne = 0;
+                uint32_t ecu0 = 0, ecu1 = 0, ecu2 = 0, ecu3 = 0, ejp0 = 0, ejp1 = 0, ejp2 = 0, ejp3 = 0;   // cu, job << 16 | pos
+                for (int k = 0; k < 4; k++) {
+                    uint32_t m = kInf;
+                    for (int p = sbase + lane; p < send; p += kWave) {
+                        const uint32_t je = l.job[p];
+                        if ((int)je > lastjob && je < k0job) m = min(m, (je << 16) | (uint32_t)p);
+                    }
+                    m = wave_min_u32(m);
+                    if (m == kInf) break;
+                    lastjob = (int)(m >> 16);
+                    ecu3 = ecu2; ecu2 = ecu1; ecu1 = ecu0;
+                    ejp3 = ejp2; ejp2 = ejp1; ejp1 = ejp0;
+                    ejp0 = m;
+                    ecu0 = uniu(l.cu[min((int)(m & 0xFFFFu), P - 1)]);
+                    ne += 1;
+                }
+                if (ne == 0) break;
+                uint32_t b0 = kInf, b1 = kInf, b2 = kInf, b3 = kInf;   // per early job: lowest (job << 16 | pos) partner
+                for (int q0 = 0; q0 < (P >> 2); q0 += kWave) {
+                    const int q = q0 + lane;                            // positions 4q .. 4q+3 (P % 256 == 0 is not given)
+                    const bool in = q < (P >> 2);
+                    const int g = in ? min((int)l.seg_grp[q >> 4], M - 1) : 0;
+                    const uint4 cc = in ? cu4[q] : make_uint4(kPad, kPad, kPad, kPad);
+                    const uint4 rr = in ? rk4[q] : make_uint4(kInf, kInf, kInf, kInf);
+                    const uint2 jj = in ? job2[q] : uint2{0u, 0u};
+                    const uint32_t dl = l.tdl[g], r1 = l.tr1[g];
+                    const uint32_t pq = (uint32_t)q << 2;
+                    const uint32_t x[4] = {cc.x - dl, cc.y - dl, cc.z - dl, cc.w - dl};
+                    const bool fl[4] = {rr.x == V, rr.y == V, rr.z == V, rr.w == V};
+                    const uint32_t id[4] = {fl[0] ? ((jj.x & 0xFFFFu) << 16) | pq : kInf,
+                                            fl[1] ? (jj.x & 0xFFFF0000u) | (pq + 1u) : kInf,
+                                            fl[2] ? ((jj.y & 0xFFFFu) << 16) | (pq + 2u) : kInf,
+                                            fl[3] ? (jj.y & 0xFFFF0000u) | (pq + 3u) : kInf};
+#pragma unroll
+                    for (int k = 0; k < 4; k++) {
+                        if (round == 0) {                               // count the flagged jobs, keep the first four
+                            unsigned long long m = __ballot(fl[k]);
+                            nF += __popcll(m);
+                            while (m && nrec < 4) {
+                                const int ln = __builtin_ctzll(m);
+                                m &= m - 1;
+                                f3 = f2; f2 = f1; f1 = f0;
+                                f0 = ((q0 + ln) << 2) + k;
+                                nrec += 1;
+                            }
+                        }
+                        b0 = min(b0, absdiff_u32(ecu0, x[k]) < r1 ? id[k] : kInf);
+                        if (ne > 1) b1 = min(b1, absdiff_u32(ecu1, x[k]) < r1 ? id[k] : kInf);
+                        if (ne > 2) b2 = min(b2, absdiff_u32(ecu2, x[k]) < r1 ? id[k] : kInf);
+                        if (ne > 3) b3 = min(b3, absdiff_u32(ecu3, x[k]) < r1 ? id[k] : kInf);
+                    }
+                }
+                auto early_pair = [&](uint32_t ejp, uint32_t b) {
+                    if (b != kInf)
+                        best = min(best, ((unsigned long long)(ejp >> 16) << 48) | ((unsigned long long)(b >> 16) << 32) |
+                                             ((unsigned long long)(ejp & 0xFFFFu) << 16) | (unsigned long long)(b & 0xFFFFu));
+                };
+                early_pair(ejp0, b0);
+                if (ne > 1) early_pair(ejp1, b1);
+                if (ne > 2) early_pair(ejp2, b2);
+                if (ne > 3) early_pair(ejp3, b3);
+                if (__ballot(min(min(b0, b1), min(b2, b3)) != kInf)) break;
+                if (round == 0 && nF <= 4) {
+                    if (nrec > 0 && f0 != k0pos) pair_with(min(f0, P - 1));
+                    if (nrec > 1 && f1 != k0pos) pair_with(min(f1, P - 1));
+                    if (nrec > 2 && f2 != k0pos) pair_with(min(f2, P - 1));
+                    if (nrec > 3 && f3 != k0pos) pair_with(min(f3, P - 1));
+                    break;
+                }
             }
         }
         best = wave_min_u64(best);
-        if (lane == 0) {
+        {
             const unsigned long long pr = best;
             const uint32_t ji = (uint32_t)(pr >> 48), jk = (uint32_t)(pr >> 32) & 0xFFFFu;     // ji < jk
             const int pi = (int)((pr >> 16) & 0xFFFFu), pk = (int)(pr & 0xFFFFu);
+            uint32_t vnew = vload;
             if (pr == ~0ull || ji >= (uint32_t)N || jk >= (uint32_t)N || pi >= P || pk >= P) {
-                ctrl->status = MMBP_ST_INTERNAL;         // cannot happen: the best swap was found above
-                ctrl->stop = 1;
+                w_status = MMBP_ST_INTERNAL;             // cannot happen: the best swap was found above
+                w_stop = true;
             } else {
-                const int ga = l.seg_grp[pi >> 6], gb = l.seg_grp[pk >> 6];
-                const uint32_t xi = l.cu[pi], xk = l.cu[pk];
-                const long long d = (long long)((xi - kBias) >> 1) - (long long)((xk - kBias) >> 1);
-                l.load[ga] -= d; l.load[gb] += d;
-                l.cu[pi] = xk; l.cu[pk] = xi;
-                l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
-                asg[ji] = gb; asg[jk] = ga;
-                if (applied_log)
-                    applied_log[(size_t)s * max_passes + ctrl->passes] =
-                        (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
-                ctrl->passes += 1;
+                const int ga = uni(l.seg_grp[pi >> 6]), gb = uni(l.seg_grp[pk >> 6]);
+                const uint32_t xi = uniu(l.cu[pi]), xk = uniu(l.cu[pk]);
+                const uint32_t d = ((xi - kBias) >> 1) - ((xk - kBias) >> 1);     // modulo 2^32; the loads stay in range
+                if (SMALLM) {
+                    vnew = vload - (lane == ga ? d : 0u) + (lane == gb ? d : 0u);
+                    if (lane == ga || lane == gb) l.load[lane] = (long long)vnew;
+                }
+                if (lane == 0) {
+                    if (!SMALLM) { l.load[ga] -= (long long)(int32_t)d; l.load[gb] += (long long)(int32_t)d; }
+                    l.cu[pi] = xk; l.cu[pk] = xi;
+                    l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
+                    asg[ji] = gb; asg[jk] = ga;
+                    if (applied_log)
+                        applied_log[(size_t)s * max_passes + w_passes] =
+                            (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
+                }
+                w_passes += 1;
             }
+            open_pass(vnew);
         }
-        open_pass();
     }
 
     // ---------------- write back ----------------
@@ -595,9 +682,9 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         long long t = 0;
         for (int j = 0; j < M; j++) t = max(t, l.load[j]);
         makespan_out[s] = t;
-        passes_out[s] = ctrl->passes;
-        if (evals_out) evals_out[s] = ctrl->evals;
-        status_out[s] = ctrl->status;
+        passes_out[s] = w_passes;
+        if (evals_out) evals_out[s] = w_evals;
+        status_out[s] = w_status;
     }
 }
 

@@ -15,7 +15,10 @@ constexpr uint32_t kKeyLimit = 1u << 29;      // |y - x| of a real candidate is 
                                               // from empty columns or from the absent side are >= 3 * 2^29
 constexpr uint32_t kInf = 0xFFFFFFFFu;
 constexpr uint16_t kNoJob = 0xFFFFu;
-constexpr int kRMax = 4;                       // row segments (of 64 positions) per tile
+#ifndef MMBP_RMAX
+#define MMBP_RMAX 4
+#endif
+constexpr int kRMax = MMBP_RMAX;                       // row segments (of 64 positions) per tile
 
 __device__ __forceinline__ uint32_t absdiff_u32(uint32_t a, uint32_t b) { return max(a, b) - min(a, b); }
 
@@ -44,17 +47,16 @@ __device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlan
 __device__ __forceinline__ uint32_t uniu(uint32_t x) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)x); }
 
 // three largest loads with their clients (lowest client index first among equal loads)
+// (scalar members, not arrays: the selection below must stay in registers)
 struct Top3 {
-    uint32_t v[3];
-    int j[3];
+    uint32_t v0, v1, v2;
+    int j0, j1, j2;
 };
 
 __device__ __forceinline__ Top3 wave_top3(const long long *load, int M, int lane)
 {
-    Top3 t;
-    int ex0 = -1, ex1 = -1;
-#pragma unroll
-    for (int r = 0; r < 3; r++) {
+    // largest load among the clients other than ex0 and ex1; client -1 when there is none
+    auto next = [&](int ex0, int ex1, uint32_t &v, int &jout) {
         uint32_t bv = 0, bj = kInf;
         for (int j = lane; j < M; j += kWave) {
             if (j == ex0 || j == ex1) continue;
@@ -63,18 +65,21 @@ __device__ __forceinline__ Top3 wave_top3(const long long *load, int M, int lane
         }
         uint32_t mv = wave_max_u32(bv);
         uint32_t mj = wave_min_u32((bv == mv) ? bj : kInf);
-        t.v[r] = (mj == kInf) ? 0u : mv;
-        t.j[r] = (int)mj;                       // -1 when fewer than r+1 clients
-        if (r == 0) ex0 = (int)mj; else ex1 = (int)mj;
-    }
+        v = (mj == kInf) ? 0u : mv;
+        jout = (int)mj;
+    };
+    Top3 t;
+    next(-1, -1, t.v0, t.j0);
+    next(t.j0, -1, t.v1, t.j1);
+    next(t.j0, t.j1, t.v2, t.j2);
     return t;
 }
 
 __device__ __forceinline__ uint32_t others_max(const Top3 &t, int a, int b)
 {
-    if (t.j[0] != a && t.j[0] != b) return t.v[0];
-    if (t.j[1] != a && t.j[1] != b) return t.v[1];
-    return t.v[2];
+    const bool f0 = t.j0 != a && t.j0 != b;
+    const bool f1 = t.j1 != a && t.j1 != b;
+    return f0 ? t.v0 : (f1 ? t.v1 : t.v2);
 }
 
 // makespan of a swap candidate from its key |y - x|: twice the larger changed load is
