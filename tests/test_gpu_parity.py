@@ -204,6 +204,39 @@ def test_sim_paper_constants(oracle):
     compare_sim(g, o, label="paper-shaped")
 
 
+def test_sim_wide_fields_and_sparse_arrivals(oracle):
+    """Records whose fields leave the small-number range of the fast hash (long decode runs, times
+    beyond 2^40, prefills of 2^16 tokens and more), decode runs cut by an arrival that finds a free
+    slot, and a time model whose decode iterations take no time."""
+    rng = np.random.default_rng(77)
+    S, N = 6, 40
+
+    def both(arr, inl, outl, p, cap, label):
+        say("sim " + label)
+        compare_sim(gpu_online_sim(arr, inl, outl, p, S, cap), oracle.online_iter_sim(arr, inl, outl, p, S, cap),
+                    label=label)
+
+    # one slot, very long outputs: decode runs of more than 2^16 iterations
+    arr = np.sort(rng.integers(0, 10_000, (S, N))).astype(np.int64)
+    inl = rng.integers(1, 50, (S, N)).astype(np.int32)
+    outl = rng.integers(60_000, 200_000, (S, N)).astype(np.int32)
+    both(arr, inl, outl, dict(cap=1, a_prefill=3, b_decode=2, c_prefill=10, c_decode=1, max_prefill_tokens=0),
+         4 * N, "long decode runs")
+    # arrivals late on the clock (beyond 2^40 us) and far apart: idle jumps, runs cut by arrivals
+    arr = ((1 << 41) + np.cumsum(rng.integers(0, 3_000_000, (S, N)), axis=1)).astype(np.int64)
+    outl = rng.integers(1, 400, (S, N)).astype(np.int32)
+    both(arr, inl, outl, dict(W.C5_PARAMS, cap=8), 6 * N, "late clock, sparse arrivals")
+    # big prompts admitted together: P >= 2^16
+    arr = np.zeros((S, N), np.int64)
+    inl = rng.integers(30_000, 90_000, (S, N)).astype(np.int32)
+    both(arr, inl, outl, dict(W.C5_PARAMS, cap=16), 6 * N, "large prefills")
+    # decode iterations of zero duration while requests keep arriving
+    arr = np.cumsum(rng.integers(0, 2000, (S, N)), axis=1).astype(np.int64)
+    inl = rng.integers(1, 300, (S, N)).astype(np.int32)
+    both(arr, inl, outl, dict(cap=4, a_prefill=7, b_decode=0, c_prefill=100, c_decode=0, max_prefill_tokens=500),
+         6 * N, "zero-time decode")
+
+
 def test_sim_bad_input(oracle):
     w = W.config5(S=5, N=50)
     w.arrival_us[1, 10] = w.arrival_us[1, 9] - 1
