@@ -4,7 +4,8 @@
 Prints ONE JSON line.  `value` = candidate moves/swaps evaluated per second (sum of the library's
 own evals_out counters / wall time of the timed steps, inputs resident in HBM).  `roofline`
 prices the local-search kernel against the chip's int32 vector-ALU issue rate with the fixed
-algorithmic op counts (5 per swap candidate, 3 per move candidate).  `cpu_baseline` times the
+algorithmic op counts (5 per swap candidate, 3 per move candidate); `frac_issued` beside it uses the
+2 vector ops per swap candidate that the kernel's inner loop really issues.  `cpu_baseline` times the
 CPU oracle on the same batch on the host cores.  `online_sim` reports the second metric
 (simulated scenarios per second on the 8192 x 2048 online configuration).
 """
@@ -19,6 +20,7 @@ sys.path.insert(0, ROOT)
 
 ALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9      # 256 CUs x 64 int32 lanes/clk x 2.4 GHz
 OPS_PER_SWAP, OPS_PER_MOVE = 5, 3
+ISSUED_PER_SWAP = 2                       # v_sub_u32 + half a v_min3_u32 + half a v_max3_u32
 
 
 def main():
@@ -28,6 +30,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sim", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also launch one plain 256 MiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (scenarios are independent; see DESIGN.md for how "
@@ -68,6 +72,12 @@ def main():
         if timed_idx is not None:
             ev[timed_idx][1].record()
 
+    if args.copy_probe:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for k in range(Wm):
         step(k)
     torch.cuda.synchronize()
@@ -103,7 +113,8 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
                      "unit": "Tops/s (int32 lane-ops; 5 per swap, 3 per move candidate)",
                      "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
-                     "kernel": "mmbp_local_search launch", "kernel_ms": ls_avg_s * 1e3},
+                     "kernel": "ls_lds_kernel (the mmbp_local_search launch)", "kernel_ms": ls_avg_s * 1e3,
+                     "frac_issued": swap_evals * ISSUED_PER_SWAP / ls_avg_s / ALU_PEAK_LANE_OPS},
     }
 
     if not args.no_sim:
