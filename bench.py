@@ -132,9 +132,24 @@ def main():
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / reps
         iters = int(r["n_prefill_iter"].sum().item() + r["n_decode_iter"].sum().item())
+
+        def utilisation():
+            busy = r["busy_slot_us"].double()
+            return float((busy / (w.params["cap"] * r["total_us"].double())).mean().item())
+
         out["online_sim"] = {"metric": "online sim scenarios/sec", "value": w.S / dt, "unit": "scenarios/s",
                              "ms_per_call": dt * 1e3, "iterations_per_s": iters / dt,
-                             "workload": "configs[4]: 8192 scenarios x 2048 requests, cap 64"}
+                             "workload": "configs[4]: 8192 scenarios x 2048 requests, cap 64",
+                             "slot_utilisation": {"rule": utilisation()}}
+        # the paper's baseline (prefill first, with / without batched prefill) on the same scenarios
+        for name, pol in (("prefill_first", api.POLICY_PREFILL_FIRST), ("prefill_first_single", api.POLICY_PREFILL_FIRST_SINGLE)):
+            pp = dict(w.params, policy=pol)
+            t0 = time.perf_counter()
+            api.online_iter_sim(arr, il, ol, pp, r["finish_us"], r["total_us"], r["busy_slot_us"],
+                                r["n_prefill_iter"], r["n_decode_iter"], r["trace_hash"], r["status"])
+            torch.cuda.synchronize()
+            out["online_sim"]["slot_utilisation"][name] = utilisation()
+            out["online_sim"].setdefault("baseline_ms_per_call", {})[name] = (time.perf_counter() - t0) * 1e3
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O

@@ -28,7 +28,7 @@ extern "C" {
 
 /* return codes */
 #define MMBP_OK            0
-#define MMBP_EINVAL       -1  /* null pointer, non-positive size, bad dtype, negative max_passes */
+#define MMBP_EINVAL       -1  /* null pointer, non-positive size, bad dtype, negative max_passes, unknown policy */
 #define MMBP_EINFEASIBLE  -2  /* N > M * cap: no assignment satisfies the cardinality limit */
 #define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 64) */
 #define MMBP_EWORKSPACE   -4  /* workspace missing or smaller than mmbp_workspace_bytes() */
@@ -104,13 +104,25 @@ int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap,
                       int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
                       int32_t *status_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Iteration-scheduling policy of the simulator.
+ * MMBP_POLICY_RULE: the paper's rule (section "Online requests and iteration scheduling"):
+ *     C_p >= C_d keeps decoding, otherwise the prefill is dispatched.
+ * MMBP_POLICY_PREFILL_FIRST: the baseline the paper measures against (FCFS, prefill first, see its
+ *     introduction and section "Experiment settings and baseline"): whenever an arrived request
+ *     finds a free slot, the prefill of the admissible requests is dispatched at the next boundary.
+ * MMBP_POLICY_PREFILL_FIRST_SINGLE: the same, one request per prefill iteration (the paper notes
+ *     that the baseline does not process several requests in one prefill stage). */
+#define MMBP_POLICY_RULE                 0
+#define MMBP_POLICY_PREFILL_FIRST        1
+#define MMBP_POLICY_PREFILL_FIRST_SINGLE 2
+
 /* Parameters of the iteration simulator (HOST struct).  Times in integer microseconds.
  * Affine time model of the paper's section "Experiment settings and baseline":
  * a prefill iteration over P tokens takes a_prefill*P + c_prefill, a decode iteration over D
  * running requests takes b_decode*D + c_decode. */
 typedef struct mmbp_sim_params {
     int32_t cap;                /* batch size |J|: requests processed simultaneously, 1..64 */
-    int32_t reserved;           /* must be 0 */
+    int32_t policy;             /* MMBP_POLICY_* */
     int64_t a_prefill;          /* T^p per token */
     int64_t b_decode;           /* T^d per token (one token per running request per round) */
     int64_t c_prefill;          /* fixed prefill overhead */
@@ -132,8 +144,9 @@ typedef struct mmbp_trace_rec {
  * iteration boundary the admissible requests (FCFS prefix of the arrived ones that fits the
  * free slots and the token capacity) define the prefill cost C_p = a_prefill*P + c_prefill;
  * the waited decode time C_d is b_decode times the tokens decoded since the last prefill.
- * C_p >= C_d keeps decoding, otherwise the prefill is dispatched; with nothing running the
- * prefill is forced; with nothing running and nothing arrived time jumps to the next arrival.
+ * C_p >= C_d keeps decoding, otherwise the prefill is dispatched (params->policy selects the
+ * baseline policies instead); with nothing running the prefill is forced; with nothing running
+ * and nothing arrived time jumps to the next arrival.
  * arrival_us [S,N] int64 nondecreasing along N; in_len, out_len [S,N] int32 >= 1
  * finish_us  [S,N] int64;  total_us, busy_slot_us [S] int64;  n_prefill_iter, n_decode_iter [S]
  * trace_hash [S] uint64: FNV-1a (64 bit) over the canonical records

@@ -317,7 +317,7 @@ uint64_t oracle_fnv1a64_init(void) { return 0xcbf29ce484222325ULL; }
  * ------------------------------------------------------------------------------------------ */
 typedef struct {
     int32_t cap;
-    int32_t pad_;
+    int32_t policy;             /* 0: the paper's rule; 1: prefill first; 2: prefill first, one request per prefill */
     int64_t a_prefill, b_decode, c_prefill, c_decode;
     int64_t max_prefill_tokens; /* <= 0: unlimited */
 } oracle_sim_params;
@@ -395,6 +395,7 @@ static void sim_one(const int64_t *arrival, const int32_t *in_len, const int32_t
             }
             P += tok; nA++;
         }
+        if (p->policy == 2 && nA > 1) { nA = 1; P = in_len[next]; }   /* baseline without batched prefill */
         if (nA == 0 && nR == 0) {           /* IDLE: jump to the next arrival */
             trace_other(&tr, 2, 1, t, 0);
             t = arrival[next];
@@ -402,6 +403,7 @@ static void sim_one(const int64_t *arrival, const int32_t *in_len, const int32_t
         }
         int do_prefill;
         if (nA == 0) do_prefill = 0;
+        else if (p->policy != 0) do_prefill = 1;      /* baseline: a waiting request is prefilled at once */
         else {
             int64_t Cp = p->a_prefill * P + p->c_prefill;
             if (nR == 0) do_prefill = 1;          /* nothing to decode: forced prefill */
@@ -451,7 +453,7 @@ int oracle_online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, con
 {
     if (!arrival_us || !in_len || !out_len || !p || !finish_us || !total_us || !busy_slot_us ||
         !n_prefill_iter || !n_decode_iter || !trace_hash || !status_out) return -1;
-    if (S <= 0 || N <= 0 || p->cap <= 0) return -1;
+    if (S <= 0 || N <= 0 || p->cap <= 0 || p->policy < 0 || p->policy > 2) return -1;
     if (p->a_prefill < 0 || p->b_decode < 0 || p->c_prefill < 0 || p->c_decode < 0) return -1;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int s = 0; s < S; s++) {

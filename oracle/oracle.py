@@ -13,7 +13,7 @@ _lib = None
 
 
 class SimParams(C.Structure):
-    _fields_ = [("cap", C.c_int32), ("pad_", C.c_int32), ("a_prefill", C.c_int64),
+    _fields_ = [("cap", C.c_int32), ("policy", C.c_int32), ("a_prefill", C.c_int64),
                 ("b_decode", C.c_int64), ("c_prefill", C.c_int64), ("c_decode", C.c_int64),
                 ("max_prefill_tokens", C.c_int64)]
 
@@ -80,8 +80,8 @@ def lower_bound(cost, M, prefill_tokens=None, ncap_L=0, tp_L=0):
     return dict(rc=rc, lb=lb, status=status)
 
 
-def make_params(cap, a_prefill, b_decode, c_prefill, c_decode, max_prefill_tokens=0):
-    return SimParams(cap, 0, a_prefill, b_decode, c_prefill, c_decode, max_prefill_tokens)
+def make_params(cap, a_prefill, b_decode, c_prefill, c_decode, max_prefill_tokens=0, policy=0):
+    return SimParams(cap, policy, a_prefill, b_decode, c_prefill, c_decode, max_prefill_tokens)
 
 
 def online_iter_sim(arrival_us, in_len, out_len, params: dict, trace_scenarios=0, trace_capacity=0):

@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmmbp.so")
 
 I32, I64 = 0, 1
+POLICY_RULE, POLICY_PREFILL_FIRST, POLICY_PREFILL_FIRST_SINGLE = 0, 1, 2
 ST_OK, ST_TRUNCATED, ST_BAD_ASSIGN, ST_BAD_COST, ST_BAD_SIM_INPUT = 0, 1, 2, 3, 4
 EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 
@@ -22,7 +23,7 @@ EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_lower_
 
 
 class SimParams(C.Structure):
-    _fields_ = [("cap", C.c_int32), ("reserved", C.c_int32), ("a_prefill", C.c_int64),
+    _fields_ = [("cap", C.c_int32), ("policy", C.c_int32), ("a_prefill", C.c_int64),
                 ("b_decode", C.c_int64), ("c_prefill", C.c_int64), ("c_decode", C.c_int64),
                 ("max_prefill_tokens", C.c_int64)]
 
@@ -150,7 +151,7 @@ def online_iter_sim(arrival_us, in_len, out_len, params: dict, finish_us, total_
     """trace_buf: optional uint8 tensor [trace_scenarios, trace_capacity, 24]."""
     torch = _torch()
     S, N = arrival_us.shape
-    p = SimParams(int(params["cap"]), 0, int(params["a_prefill"]), int(params["b_decode"]),
+    p = SimParams(int(params["cap"]), int(params.get("policy", 0)), int(params["a_prefill"]), int(params["b_decode"]),
                   int(params["c_prefill"]), int(params["c_decode"]), int(params.get("max_prefill_tokens", 0)))
     tsc = tcap = 0
     if trace_buf is not None:

@@ -22,7 +22,7 @@ const char *mmbp_strerror(int code)
 {
     switch (code) {
     case MMBP_OK: return "ok";
-    case MMBP_EINVAL: return "invalid argument (null pointer, non-positive size, bad dtype or negative max_passes)";
+    case MMBP_EINVAL: return "invalid argument (null pointer, non-positive size, bad dtype, negative max_passes or unknown policy)";
     case MMBP_EINFEASIBLE: return "infeasible: N > M * cap";
     case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64)";
     case MMBP_EWORKSPACE: return "workspace missing or too small (see mmbp_workspace_bytes)";
@@ -91,7 +91,8 @@ int online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, const int3
     if (!arrival_us || !in_len || !out_len || !params || !finish_us || !total_us || !busy_slot_us ||
         !n_prefill_iter || !n_decode_iter || !trace_hash || !status_out)
         return MMBP_EINVAL;
-    if (S <= 0 || N <= 0 || params->cap <= 0 || params->reserved != 0) return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || params->cap <= 0) return MMBP_EINVAL;
+    if (params->policy < MMBP_POLICY_RULE || params->policy > MMBP_POLICY_PREFILL_FIRST_SINGLE) return MMBP_EINVAL;
     if (params->a_prefill < 0 || params->b_decode < 0 || params->c_prefill < 0 || params->c_decode < 0)
         return MMBP_EINVAL;
     if (trace_buf && (trace_scenarios < 0 || trace_capacity < 0 || !trace_len)) return MMBP_EINVAL;

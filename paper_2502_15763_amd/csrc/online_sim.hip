@@ -255,6 +255,10 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
             }
             P = nA == 1 ? uniform_i64(tok) : wave_sum_i64(lane < nA ? tok : 0);
         }
+        if (p.policy == MMBP_POLICY_PREFILL_FIRST_SINGLE && nA > 1) {      // baseline without batched prefill
+            nA = 1;
+            P = uniform_i64((int64_t)win_in[w][next & (2 * kWave - 1)]);
+        }
         if (nA == 0 && nR == 0) {              // nothing running, nothing arrived: jump to the next arrival
             tr.other(2u, 1u, t, 0, lane);
             t = head_arr;
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
         bool do_prefill = false;
         if (nA > 0) {
             const int64_t Cp = p.a_prefill * P + p.c_prefill;
-            do_prefill = (nR == 0) || (Cp < Cd);
+            do_prefill = (nR == 0) || (Cp < Cd) || p.policy != MMBP_POLICY_RULE;   // baseline: prefill at once
         }
         if (do_prefill) {
             const int64_t dt = p.a_prefill * P + p.c_prefill;

@@ -37,6 +37,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layout_matches_header():
     assert C.sizeof(api.SimParams) == 48
     assert api.SimParams.a_prefill.offset == 8 and api.SimParams.max_prefill_tokens.offset == 40
+    assert api.SimParams.policy.offset == 4
 
 
 def test_host_side_argument_validation():
@@ -67,6 +68,8 @@ def test_host_side_argument_validation():
     assert sim(*args(p)) == api.EINVAL
     p = api.SimParams(4, 0, -1, 1, 1, 1, 0)
     assert sim(*args(p)) == api.EINVAL
+    for bad_policy in (-1, 3):
+        assert sim(*args(api.SimParams(4, bad_policy, 1, 1, 1, 1, 0))) == api.EINVAL
     assert sim(one, one, one, 1, 4, None, one, one, one, one, one, one, None, None, 0, 0, one, None) == api.EINVAL
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(api.mmbp_strerror(code), str) and api.mmbp_strerror(code)

@@ -237,6 +237,25 @@ def test_sim_wide_fields_and_sparse_arrivals(oracle):
          6 * N, "zero-time decode")
 
 
+@pytest.mark.parametrize("policy", [1, 2])
+def test_sim_baseline_policies(oracle, policy):
+    """The prefill-first baselines (with and without batched prefill) on online and on
+    all-at-once workloads, with and without a prefill token cap."""
+    for (S, N, cap, tok, rate) in [(9, 300, 16, 0, 50), (9, 300, 16, 600, 200), (6, 500, 64, 0, 20), (5, 64, 64, 0, 1e6)]:
+        w = W.config5(S=S, N=N, rate_per_s=rate, seed_offset=policy + N)
+        p = dict(w.params, cap=cap, max_prefill_tokens=tok, policy=policy)
+        say(f"sim policy={policy} N={N} cap={cap} tok={tok} rate={rate}")
+        o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, p, trace_scenarios=S, trace_capacity=4 * N)
+        g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, p, trace_scenarios=S, trace_capacity=4 * N)
+        compare_sim(g, o, label=f"policy {policy} N={N}")
+    in_len, out_len = W.paper_shaped(S=4, N=1319)
+    arr = np.zeros_like(in_len, dtype=np.int64)
+    p = dict(W.PAPER_PARAMS, cap=64, policy=policy)
+    say(f"sim policy={policy} paper-shaped lengths")
+    compare_sim(gpu_online_sim(arr, in_len, out_len, p, 2, 6000), oracle.online_iter_sim(arr, in_len, out_len, p, 2, 6000),
+                label=f"policy {policy} paper-shaped")
+
+
 def test_sim_bad_input(oracle):
     w = W.config5(S=5, N=50)
     w.arrival_us[1, 10] = w.arrival_us[1, 9] - 1

@@ -227,3 +227,79 @@ def test_sim_bad_input(oracle):
     r = oracle.online_iter_sim(arr, inl, outl, _params(2))
     assert r["status"].tolist() == [4, 4, 4, 0]
     assert (r["finish_us"][:3] == 0).all() and (r["total_us"][:3] == 0).all()
+
+
+# ------------------------------------------------------------------ baseline policies of the simulator
+GOLD_POLICIES = os.path.join(os.path.dirname(__file__), "golden", "sim_policies_hand_worked.txt")
+
+
+def test_sim_policies_hand_worked(oracle):
+    """Traces worked by hand for the paper's rule and for the two readings of its baseline
+    (prefill first, with and without batched prefill)."""
+    arr = np.array([[0, 0, 30]], np.int64)
+    inl = np.array([[10, 20, 100]], np.int32)
+    outl = np.array([[3, 2, 2]], np.int32)
+    seen = 0
+    for line in open(GOLD_POLICIES):
+        if line.startswith("#") or not line.strip():
+            continue
+        pol, total, busy, npre, ndec, fin, recs = [f.strip() for f in line.split("|")]
+        p = dict(cap=2, a_prefill=1, b_decode=10, c_prefill=5, c_decode=2, max_prefill_tokens=0, policy=int(pol))
+        r = oracle.online_iter_sim(arr, inl, outl, p, trace_scenarios=1, trace_capacity=16)
+        assert r["rc"] == 0 and int(r["status"][0]) == 0
+        assert int(r["total_us"][0]) == int(total) and int(r["busy_slot_us"][0]) == int(busy)
+        assert int(r["n_prefill_iter"][0]) == int(npre) and int(r["n_decode_iter"][0]) == int(ndec)
+        assert r["finish_us"][0].tolist() == [int(x) for x in fin.split(",")]
+        want = [tuple(int(x) for x in rec.split(":")) for rec in recs.split()]
+        got = [tuple(int(x) for x in rec) for rec in r["trace"][0][: int(r["trace_len"][0])]]
+        assert got == want
+        # the hash is FNV-1a over the little-endian bytes of exactly these records
+        raw = b"".join(np.array([w], dtype=oracle.TRACE_DTYPE).tobytes() for w in want)
+        assert int(r["trace_hash"][0]) == oracle.fnv1a64(raw)
+        seen += 1
+    assert seen == 3
+
+
+@pytest.mark.parametrize("policy", [1, 2])
+def test_sim_prefill_first_never_decodes_past_a_waiting_request(oracle, policy):
+    """Property that defines the baseline: a decode iteration starts only if no arrived request
+    could take a free slot.  Checked from the trace and the arrivals alone."""
+    c5 = W.config5(S=5, N=200, rate_per_s=30)
+    p = dict(c5.params, cap=8, policy=policy)
+    r = oracle.online_iter_sim(c5.arrival_us, c5.in_len, c5.out_len, p, trace_scenarios=5, trace_capacity=3000)
+    assert (r["status"] == 0).all()
+    b, cd = p["b_decode"], p["c_decode"]
+    for s in range(5):
+        tr = r["trace"][s][: int(r["trace_len"][s])]
+        admitted = 0
+        n_pre_single = 0
+        for kind, count, t0, x in tr.tolist():
+            if kind == 1:
+                admitted += count
+                n_pre_single += count == 1
+                if policy == 2:
+                    assert count == 1
+            elif kind == 0 and x < p["cap"] and admitted < 200:
+                last_boundary = t0 + (count - 1) * (b * x + cd)      # start of the run's last iteration
+                assert c5.arrival_us[s][admitted] > last_boundary
+        assert admitted == 200
+        # conservation as for the rule
+        dec = tr[tr["kind"] == 0]
+        assert int((dec["count"].astype(np.int64) * dec["x"]).sum()) == int(c5.out_len[s].sum())
+
+
+def test_sim_policies_agree_where_they_must(oracle):
+    """cap = 1 leaves no choice (serial FCFS), and requests that all fit at t = 0 are prefilled at
+    once by the rule (forced) and by the batched baseline alike."""
+    c5 = W.config5(S=4, N=40)
+    base = dict(c5.params, cap=1)
+    ref = oracle.online_iter_sim(c5.arrival_us, c5.in_len, c5.out_len, base)
+    for pol in (1, 2):
+        r = oracle.online_iter_sim(c5.arrival_us, c5.in_len, c5.out_len, dict(base, policy=pol))
+        assert np.array_equal(r["finish_us"], ref["finish_us"]) and np.array_equal(r["trace_hash"], ref["trace_hash"])
+    arr = np.zeros((4, 40), np.int64)
+    wide = dict(c5.params, cap=64)
+    ref = oracle.online_iter_sim(arr, c5.in_len, c5.out_len, wide)
+    r = oracle.online_iter_sim(arr, c5.in_len, c5.out_len, dict(wide, policy=1))
+    assert np.array_equal(r["finish_us"], ref["finish_us"]) and np.array_equal(r["trace_hash"], ref["trace_hash"])
+    assert oracle.online_iter_sim(arr, c5.in_len, c5.out_len, dict(wide, policy=3))["rc"] != 0
