@@ -117,6 +117,23 @@ def main():
                      "frac_issued": swap_evals * ISSUED_PER_SWAP / ls_avg_s / ALU_PEAK_LANE_OPS},
     }
 
+    # the same search with the pruned scan (identical results): reported on its own, never mixed
+    # into `value` or the roofline, which count evaluated candidates only
+    pr_assign = [assign0.clone() for _ in range(K)]
+    api.mmbp_local_search_pruned(cost, M, c.cap, c.max_passes, assign0.clone(), load, mk, passes, status,
+                                 evals_out=evals, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        api.mmbp_local_search_pruned(cost, M, c.cap, c.max_passes, pr_assign[k], load, mk, passes, status,
+                                     evals_out=evals, workspace=ws)
+    torch.cuda.synchronize()
+    pr_s = (time.perf_counter() - t0) / K
+    out["pruned_scan"] = {"entry": "mmbp_local_search_pruned", "ms_per_call": pr_s * 1e3,
+                          "passes_per_s": float(passes_np.sum()) / pr_s,
+                          "full_scan_equivalent_candidates_per_s": total_evals / pr_s,
+                          "same_result_as_full_scan": bool(torch.equal(pr_assign[K - 1], assigns[Wm + K - 1]))}
+
     if not args.no_sim:
         w = W.config5()
         arr = torch.from_numpy(w.arrival_us).cuda()

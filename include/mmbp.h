@@ -104,6 +104,20 @@ int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap,
                       int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
                       int32_t *status_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The same search with a pruned scan.  The objective of the MMBP model (same section) is
+ * max_j t_j, so a candidate lowers it only if it takes load off the client that attains it: each
+ * pass evaluates only the moves off that client and the swaps with it, and stops when none of
+ * them improves.  Assignments, loads, makespans, pass counts, applied_log and status are identical
+ * to mmbp_local_search on every input.  evals_out reports the candidates a full scan would have
+ * enumerated (the same numbers mmbp_local_search reports), not the smaller number evaluated here.
+ * Arguments, workspace and error behaviour as for mmbp_local_search.
+ */
+int mmbp_local_search_pruned(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+                             int32_t *assign, int64_t *load_out, int64_t *makespan_out,
+                             int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
+                             int32_t *status_out, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Iteration-scheduling policy of the simulator.
  * MMBP_POLICY_RULE: the paper's rule (section "Online requests and iteration scheduling"):
  *     C_p >= C_d keeps decoding, otherwise the prefill is dispatched.

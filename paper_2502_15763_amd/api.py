@@ -19,7 +19,7 @@ ST_OK, ST_TRUNCATED, ST_BAD_ASSIGN, ST_BAD_COST, ST_BAD_SIM_INPUT = 0, 1, 2, 3, 
 EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 
 EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_lower_bound",
-           "mmbp_local_search", "online_iter_sim")
+           "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim")
 
 
 class SimParams(C.Structure):
@@ -55,6 +55,8 @@ def load_library() -> C.CDLL:
     lib.mmbp_lower_bound.argtypes = [vp, i, i, i, i, vp, i64, i64, vp, vp, vp]
     lib.mmbp_local_search.restype = i
     lib.mmbp_local_search.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.mmbp_local_search_pruned.restype = i
+    lib.mmbp_local_search_pruned.argtypes = lib.mmbp_local_search.argtypes
     lib.online_iter_sim.restype = i
     lib.online_iter_sim.argtypes = [vp, vp, vp, i, i, C.POINTER(SimParams), vp, vp, vp, vp, vp, vp, vp, vp, i, i,
                                     vp, vp]
@@ -129,13 +131,14 @@ def mmbp_lower_bound(cost, M, lb_out, status_out, prefill_tokens=None, ncap_L=0,
 
 
 def mmbp_local_search(cost, M, cap, max_passes, assign, load_out, makespan_out, passes_out, status_out,
-                      evals_out=None, applied_log=None, workspace=None, stream=None, raise_on_error=True) -> int:
+                      evals_out=None, applied_log=None, workspace=None, stream=None, raise_on_error=True,
+                      _entry="mmbp_local_search") -> int:
     torch = _torch()
     S, N = cost.shape
     ws_ptr, ws_bytes = None, 0
     if workspace is not None:
         ws_ptr, ws_bytes = _ptr(workspace, name="workspace"), workspace.numel() * workspace.element_size()
-    rc = load_library().mmbp_local_search(
+    rc = getattr(load_library(), _entry)(
         _ptr(cost, name="cost"), _cost_dtype(cost), S, N, int(M), int(cap), int(max_passes),
         _ptr(assign, torch.int32, (S, N), "assign"), _ptr(load_out, torch.int64, (S, M), "load_out"),
         _ptr(makespan_out, torch.int64, (S,), "makespan_out"), _ptr(passes_out, torch.int32, (S,), "passes_out"),
@@ -143,6 +146,13 @@ def mmbp_local_search(cost, M, cap, max_passes, assign, load_out, makespan_out, 
         _ptr(applied_log, torch.int64, (S, max(int(max_passes), 0)), "applied_log") if applied_log is not None else None,
         _ptr(status_out, torch.int32, (S,), "status_out"), ws_ptr, ws_bytes, _stream(stream))
     return _check(rc, raise_on_error)
+
+
+def mmbp_local_search_pruned(cost, M, cap, max_passes, assign, load_out, makespan_out, passes_out, status_out,
+                             evals_out=None, applied_log=None, workspace=None, stream=None, raise_on_error=True) -> int:
+    return mmbp_local_search(cost, M, cap, max_passes, assign, load_out, makespan_out, passes_out, status_out,
+                             evals_out=evals_out, applied_log=applied_log, workspace=workspace, stream=stream,
+                             raise_on_error=raise_on_error, _entry="mmbp_local_search_pruned")
 
 
 def online_iter_sim(arrival_us, in_len, out_len, params: dict, finish_us, total_us, busy_slot_us,
@@ -173,7 +183,8 @@ def online_iter_sim(arrival_us, in_len, out_len, params: dict, finish_us, total_
 # Convenience wrappers used by tests, the smoke check and the benchmark: allocate outputs with
 # torch, call the entry point, hand back tensors.  They add no computation.
 # ------------------------------------------------------------------------------------------
-def run_local_search(cost, assign0, M, cap, max_passes, want_log=False, stream=None, raise_on_error=True):
+def run_local_search(cost, assign0, M, cap, max_passes, want_log=False, stream=None, raise_on_error=True,
+                     pruned=False):
     torch = _torch()
     dev = cost.device
     S, N = cost.shape
@@ -187,9 +198,10 @@ def run_local_search(cost, assign0, M, cap, max_passes, want_log=False, stream=N
         log = torch.full((S, max_passes), -1, dtype=torch.int64, device=dev)
     ws_bytes = mmbp_workspace_bytes(S, N, M)
     ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev) if ws_bytes else None
-    rc = mmbp_local_search(cost, M, cap, max_passes, out["assign"], out["load"], out["makespan"], out["passes"],
-                           out["status"], evals_out=out["evals"], applied_log=log, workspace=ws, stream=stream,
-                           raise_on_error=raise_on_error)
+    fn = mmbp_local_search_pruned if pruned else mmbp_local_search
+    rc = fn(cost, M, cap, max_passes, out["assign"], out["load"], out["makespan"], out["passes"],
+            out["status"], evals_out=out["evals"], applied_log=log, workspace=ws, stream=stream,
+            raise_on_error=raise_on_error)
     out["rc"] = rc
     out["log"] = log
     out["workspace"] = ws

@@ -33,7 +33,7 @@ struct GCtrl {
     unsigned long long evals, pairs_per_scan, k0, pair, mv;
     uint32_t vswap, vmove;
     Top3 top;
-    int P, nfeas, ntask, passes, status, stop, iters;
+    int P, nfeas, ntask, passes, status, stop, iters, prune;
 };
 
 struct GTask {
@@ -191,6 +191,7 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
     for (int q = tid; q < M * M; q += kSelBlock) {
         const int g = q / M, b = q - g * M;
         if (g >= b) continue;
+        if (ctrl->prune && g != astar && b != astar) continue;      // pruned scan: pairs with the critical client only
         const int X = (g == astar) ? b : g, Y = (g == astar) ? g : b;
         const int nx = w.cnt[X], ny = w.cnt[Y];
         if (nx <= 0 || ny <= 0) continue;
@@ -218,8 +219,8 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
 // ---- kernel 0: validation, narrowing decision, layout, first pass preparation ----
 template <typename CostT>
 __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__restrict__ cost_all, int N, int M, int cap,
-                                                               int max_passes, int32_t *assign_all, OutPtrs o,
-                                                               void *workspace)
+                                                               int max_passes, int prune, int32_t *assign_all,
+                                                               OutPtrs o, void *workspace)
 {
     const int s = blockIdx.x;
     const GWs w = grid_ws(workspace, s, N, M);
@@ -237,6 +238,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
     if (tid == 0) {
         s_bad_cost = 0; s_bad_assign = 0;
         ctrl->passes = 0; ctrl->status = MMBP_ST_OK; ctrl->stop = 0; ctrl->evals = 0; ctrl->iters = 0; ctrl->ntask = 0;
+        ctrl->prune = prune;
     }
     __syncthreads();
     {
@@ -358,6 +360,7 @@ __global__ __launch_bounds__(kEvalBlock) void grid_eval_kernel(int N, int M, voi
         const int nseg = P >> 6;
         for (int seg = blockIdx.x * (kEvalBlock / kWave) + wave; seg < nseg; seg += gridDim.x * (kEvalBlock / kWave)) {
             const int g = w.seg_grp[seg];
+            if (ctrl->prune && g != astar) continue;                 // an improving move leaves the critical client
             const uint32_t x = w.cu[seg * 64 + lane];
             const uint32_t ci = (x - kBias) >> 1;
             const uint32_t la = (uint32_t)w.load[g];
@@ -551,7 +554,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
 
 size_t ls_grid_workspace_bytes(int S, int N, int M) { return (size_t)S * grid_layout(N, M).total; }
 
-hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                           int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                           uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, void *workspace,
                           hipStream_t st)
@@ -559,10 +562,10 @@ hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int 
     OutPtrs o{load_out, makespan_out, passes_out, status_out, evals_out, applied_log};
     if (dtype == MMBP_I32)
         grid_stage_kernel<int32_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int32_t *)cost, N, M, cap, max_passes,
-                                                                       assign, o, workspace);
+                                                                       prune, assign, o, workspace);
     else
         grid_stage_kernel<int64_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int64_t *)cost, N, M, cap, max_passes,
-                                                                       assign, o, workspace);
+                                                                       prune, assign, o, workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int launches = max_passes < kMaxPassLaunches ? max_passes : kMaxPassLaunches;

@@ -259,7 +259,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
 
 template <typename CostT, int BLOCK, bool SMALLM>
 __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
-    const CostT *__restrict__ cost_all, int N, int M, int cap, int max_passes, int32_t *assign_all,
+    const CostT *__restrict__ cost_all, int N, int M, int cap, int max_passes, int prune, int32_t *assign_all,
     int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
     uint64_t *applied_log, int32_t *status_out)
 {
@@ -399,6 +399,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         if (nfeas > 0) {
             for (int seg = wave; seg < nseg; seg += kWaves) {
                 const int g = l.seg_grp[seg];
+                if (prune && g != astar) continue;               // an improving move leaves the critical client
                 const uint32_t x = l.cu[seg * 64 + lane];
                 const uint32_t ci = (x - kBias) >> 1;
                 const uint32_t la = load32(g);
@@ -417,15 +418,19 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         uint32_t sbest = kInf;
         unsigned long long kbest = ~0ull;
         {
-            const int lo = (int)(((long long)ntask * twave) / kWaves);
-            const int hi = (int)(((long long)ntask * (twave + 1)) / kWaves);
+            // full scan: a contiguous range per wave; pruned scan: tasks dealt round the waves, those that
+            // do not involve the critical client skipped
+            const int lo = prune ? twave : (int)(((long long)ntask * twave) / kWaves);
+            const int hi = prune ? ntask : (int)(((long long)ntask * (twave + 1)) / kWaves);
+            const int tstep = prune ? kWaves : 1;
             unsigned long long rec = lo < hi ? l.tasks[lo] : 0ull;
-            for (int t = lo; t < hi; t++) {
+            for (int t = lo; t < hi; t += tstep) {
                 const uint32_t w0 = uniu((uint32_t)rec), w1 = uniu((uint32_t)(rec >> 32));
-                if (t + 1 < hi) rec = l.tasks[t + 1];                      // next record while this tile runs
+                if (t + tstep < hi) rec = l.tasks[t + tstep];              // next record while this tile runs
                 int rowbase = (int)(w0 & 0x3FFu) << 6, R = (int)((w0 >> 10) & 7u), X = (int)((w0 >> 13) & 0xFFu);
                 int c0 = (int)(w1 & 0x3FFu) << 6, Y = (int)((w1 >> 19) & 0xFFu);
                 int c1 = c0 + (int)((w1 >> 10) & 0x1FFu);
+                if (prune && X != astar && Y != astar) continue;
                 if (X == astar) {                                            // the critical client must be the column side
                     const int rb = c0, rr = (c1 - c0 + 63) >> 6;
                     c0 = rowbase; c1 = rowbase + 64 * R;
@@ -689,7 +694,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
 }
 
 template <typename CostT, int BLOCK, bool SMALLM>
-hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_passes, int32_t *assign,
+hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_passes, int prune, int32_t *assign,
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
@@ -707,7 +712,7 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
         }
     }
     ls_lds_kernel<CostT, BLOCK, SMALLM><<<dim3(S), dim3(BLOCK), bytes, st>>>(
-        (const CostT *)cost, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out,
+        (const CostT *)cost, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out, evals_out,
         applied_log, status_out);
     return hipGetLastError();
 }
@@ -716,7 +721,7 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
 
 bool ls_lds_fits(int N, int M) { return N < 65535 && N + 64 * M <= 65536 && lds_bytes(N, M) <= kLdsLimit; }
 
-hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                          uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
@@ -729,7 +734,7 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
     const int block = pmax <= 512 ? 256 : 512;
 #endif
 #define MMBP_LDS_LAUNCH(T, B, SM) \
-    launch_one<T, B, SM>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
+    launch_one<T, B, SM>(cost, S, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out, evals_out, \
                          applied_log, status_out, st)
 #define MMBP_LDS_PICK(T) \
     (block == 256 ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 256, true) : MMBP_LDS_LAUNCH(T, 256, false)) \

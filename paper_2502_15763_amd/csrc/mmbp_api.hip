@@ -51,7 +51,7 @@ int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M, const int
     return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_lower_bound");
 }
 
-int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int32_t *assign,
+static int local_search_impl(int prune, const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int32_t *assign,
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, void *workspace, size_t workspace_bytes,
                       void *stream)
@@ -69,17 +69,35 @@ int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap,
     // exactly, pending otherwise; the 64-bit kernel then takes the pending ones.
     hipError_t e;
     if (mmbp::ls_lds_fits(N, M)) {
-        e = mmbp::launch_ls_lds(cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+        e = mmbp::launch_ls_lds(cost, dtype, S, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out,
                                 evals_out, applied_log, status_out, st);
         if (e != hipSuccess) return fail_hip(e, "mmbp_local_search(lds)");
     } else {
-        e = mmbp::launch_ls_grid(cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+        e = mmbp::launch_ls_grid(cost, dtype, S, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out,
                                  evals_out, applied_log, status_out, workspace, st);
         if (e != hipSuccess) return fail_hip(e, "mmbp_local_search(grid)");
     }
     e = mmbp::launch_ls_generic(cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
                                 evals_out, applied_log, status_out, st);
     return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_local_search(generic)");
+}
+
+int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int32_t *assign,
+                      int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
+                      uint64_t *applied_log, int32_t *status_out, void *workspace, size_t workspace_bytes,
+                      void *stream)
+{
+    return local_search_impl(0, cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+                             evals_out, applied_log, status_out, workspace, workspace_bytes, stream);
+}
+
+int mmbp_local_search_pruned(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+                             int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
+                             uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    return local_search_impl(1, cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+                             evals_out, applied_log, status_out, workspace, workspace_bytes, stream);
 }
 
 int online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, const int32_t *out_len, int S, int N,

@@ -19,13 +19,13 @@ hipError_t launch_ls_generic(const void *cost, int dtype, int S, int N, int M, i
 
 // LDS-resident path: true if shapes fit (N + 64*M padded positions in one workgroup's LDS).
 bool ls_lds_fits(int N, int M);
-hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                          uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st);
 
 // multi-workgroup path (large N): state in the caller's workspace
 size_t ls_grid_workspace_bytes(int S, int N, int M);
-hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                           int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                           uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, void *workspace,
                           hipStream_t st);

@@ -19,10 +19,11 @@ def u64(t):
     return t.cpu().numpy().view(np.uint64)
 
 
-def gpu_local_search(cost, assign0, M, cap, max_passes, want_log=True):
+def gpu_local_search(cost, assign0, M, cap, max_passes, want_log=True, pruned=False):
     import torch
     from paper_2502_15763_amd import api
-    r = api.run_local_search(to_dev(cost), to_dev(assign0.astype(np.int32)), M, cap, max_passes, want_log=want_log)
+    r = api.run_local_search(to_dev(cost), to_dev(assign0.astype(np.int32)), M, cap, max_passes, want_log=want_log,
+                             pruned=pruned)
     torch.cuda.synchronize()
     out = dict(rc=r["rc"], assign=r["assign"].cpu().numpy(), load=r["load"].cpu().numpy(),
                makespan=r["makespan"].cpu().numpy(), passes=r["passes"].cpu().numpy(), evals=u64(r["evals"]),

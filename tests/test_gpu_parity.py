@@ -153,6 +153,46 @@ def test_ls_multi_workgroup_path_batch(oracle):
     compare_ls(g, o, label="multi-workgroup batch")
 
 
+# ------------------------------------------------------------------ pruned scan (identical results)
+def test_ls_pruned_small_random(oracle):
+    """The pruned scan must return exactly what the full search returns (the oracle is the full
+    search): assignments, loads, passes, applied ids, status and the full-scan candidate count."""
+    rng = np.random.default_rng(2025)
+    for (N, M, cap, hi) in SMALL_SHAPES:
+        S = 5
+        say(f"ls_pruned N={N} M={M} cap={cap} hi={hi}")
+        cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=hi, dtype=np.int32)
+        o = oracle.local_search(cost, assign, M, cap, 200, want_log=True)
+        g = gpu_local_search(cost, assign, M, cap, 200, pruned=True)
+        compare_ls(g, o, label=f"pruned N={N} M={M} cap={cap}")
+
+
+def test_ls_pruned_configs(oracle):
+    c = W.config2()
+    say("ls_pruned config2 full")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+    compare_ls(gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, pruned=True), o, label="pruned c2")
+    c = W.config2(S=16, slack=64)
+    say("ls_pruned config2 slack (moves applied)")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+    compare_ls(gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, pruned=True), o, label="pruned c2 slack")
+    c = W.config3(S=6, max_passes=4000)
+    say("ls_pruned config3 S=6 int64 costs, to convergence")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+    compare_ls(gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, pruned=True), o, label="pruned c3")
+    c = W.config4(slack=256)
+    say("ls_pruned config4 (multi-workgroup path), 12 passes, slack")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, 12, want_log=True)
+    compare_ls(gpu_local_search(c.cost, c.assign0, c.M, c.cap, 12, pruned=True), o, label="pruned c4")
+    # a scenario that needs the 64-bit kernel next to narrow ones
+    rng = np.random.default_rng(5)
+    cost, assign = W.random_offline(rng, 3, 200, 5, 50, cost_hi=1000, dtype=np.int64)
+    cost[1] *= 1 << 22
+    say("ls_pruned with a 64-bit scenario")
+    o = oracle.local_search(cost, assign, 5, 50, 300, want_log=True)
+    compare_ls(gpu_local_search(cost, assign, 5, 50, 300, pruned=True), o, label="pruned 64-bit mix")
+
+
 # ------------------------------------------------------------------ lower bound
 def test_lb_parity(oracle):
     rng = np.random.default_rng(31)
