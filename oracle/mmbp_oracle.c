@@ -468,6 +468,156 @@ int oracle_online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, con
     return 0;
 }
 
+/* ------------------------------------------------------------------------------------------
+ * Iteration simulator fed by an offline assignment: the "Sorting and Online Preemptive Method"
+ * of the paper's section "Online requests and iteration scheduling".
+ *   I_j = requests assigned to client j, sorted by N^p_i + N^d_i, longest first (equal lengths:
+ *         lower request index first);  remain_token(j) = sum of N^p_i + N^d_i over what is left in I_j.
+ *   At an iteration boundary the clients are visited in index order; an idle client takes the
+ *   head of its own I_j if there is one, otherwise the head of the I_v of the client v with the
+ *   largest remain_token (v lowest among equals), provided that is positive; remain_token of the
+ *   queue the request came from is reduced by its length.
+ * All requests are known at t = 0 (the algorithm works on the offline request set).  The requests
+ * picked at a boundary form the prefill that could be dispatched: C_p = a*P + c_p over their
+ * input tokens, limited by the prefill token cap like the FCFS prefix (the first pick always
+ * fits), and the policy decides as in the FCFS simulator; picks are only taken when the prefill
+ * is dispatched.  Trace, times and counters as in the FCFS simulator.
+ * ------------------------------------------------------------------------------------------ */
+static void sim_assigned_one(const int32_t *in_len, const int32_t *out_len, const int32_t *assign, int N,
+                             const oracle_sim_params *p, int64_t *finish, int64_t *total_us,
+                             int64_t *busy_slot_us, int32_t *n_prefill_iter, int32_t *n_decode_iter,
+                             uint64_t *trace_hash, int32_t *served_by, int64_t *start_us, trace_rec *trace_buf,
+                             int trace_capacity, int32_t *trace_len, int32_t *status)
+{
+    int cap = p->cap;
+    for (int i = 0; i < N; i++) { finish[i] = 0; if (served_by) served_by[i] = -1; if (start_us) start_us[i] = 0; }
+    *total_us = 0; *busy_slot_us = 0; *n_prefill_iter = 0; *n_decode_iter = 0; *trace_hash = 0;
+    if (trace_len) *trace_len = 0;
+    for (int i = 0; i < N; i++)
+        if (in_len[i] < 1 || out_len[i] < 1 || assign[i] < 0 || assign[i] >= cap) { *status = ST_BAD_SIM_INPUT; return; }
+
+    /* the sorted queues I_j, stored one after the other in q[] */
+    int *q = (int *)malloc((size_t)N * sizeof(int));
+    int *qbeg = (int *)calloc((size_t)cap + 1, sizeof(int));
+    int *head = (int *)malloc((size_t)cap * sizeof(int)), *th = (int *)malloc((size_t)cap * sizeof(int));
+    int64_t *remain = (int64_t *)calloc((size_t)cap, sizeof(int64_t)), *tr_ = (int64_t *)malloc((size_t)cap * sizeof(int64_t));
+    int32_t *run_req = (int32_t *)malloc((size_t)cap * sizeof(int32_t)), *run_rem = (int32_t *)malloc((size_t)cap * sizeof(int32_t));
+    int *pick_client = (int *)malloc((size_t)cap * sizeof(int)), *pick_req = (int *)malloc((size_t)cap * sizeof(int));
+    for (int i = 0; i < N; i++) qbeg[assign[i] + 1]++;
+    for (int j = 0; j < cap; j++) qbeg[j + 1] += qbeg[j];
+    for (int j = 0; j < cap; j++) head[j] = qbeg[j];
+    for (int i = 0; i < N; i++) {                       /* insertion into I_j, longest first */
+        int j = assign[i];
+        int64_t len = (int64_t)in_len[i] + out_len[i];
+        int pos = head[j]++;
+        while (pos > qbeg[j] && (int64_t)in_len[q[pos - 1]] + out_len[q[pos - 1]] < len) { q[pos] = q[pos - 1]; pos--; }
+        q[pos] = i;
+        remain[j] += len;
+    }
+    for (int j = 0; j < cap; j++) { head[j] = qbeg[j]; run_req[j] = -1; run_rem[j] = 0; }
+
+    int nR = 0, done = 0;
+    int64_t t = 0, Cd = 0, busy = 0;
+    int32_t npre = 0, ndec = 0;
+    trace_t tr; memset(&tr, 0, sizeof tr);
+    tr.hash = oracle_fnv1a64_init(); tr.buf = trace_buf; tr.cap = trace_capacity;
+
+    while (done < N) {
+        /* what the idle clients would take now, in client order (nothing is taken yet) */
+        int nA = 0; int64_t P = 0;
+        for (int j = 0; j < cap; j++) { th[j] = head[j]; tr_[j] = remain[j]; }
+        for (int j = 0; j < cap; j++) {
+            if (run_req[j] >= 0) continue;
+            if (p->policy == 2 && nA >= 1) break;
+            int src = -1;
+            if (th[j] < qbeg[j + 1]) src = j;
+            else {
+                int64_t best = 0;
+                for (int v = 0; v < cap; v++) if (tr_[v] > best) { best = tr_[v]; src = v; }
+            }
+            if (src < 0) continue;
+            int req = q[th[src]];
+            int64_t tok = in_len[req];
+            if (p->max_prefill_tokens > 0 && P + tok > p->max_prefill_tokens && nA > 0) break;
+            pick_client[nA] = j; pick_req[nA] = req;
+            th[src]++; tr_[src] -= (int64_t)in_len[req] + out_len[req];
+            P += tok; nA++;
+            if (p->max_prefill_tokens > 0 && P > p->max_prefill_tokens) break;   /* oversized first pick: alone */
+        }
+        if (nA == 0 && nR == 0) break;       /* cannot happen while requests are left */
+        int do_prefill;
+        if (nA == 0) do_prefill = 0;
+        else if (p->policy != 0) do_prefill = 1;
+        else {
+            int64_t Cp = p->a_prefill * P + p->c_prefill;
+            if (nR == 0) do_prefill = 1;
+            else if (Cp >= Cd) do_prefill = 0;
+            else do_prefill = 1;
+        }
+        if (do_prefill) {
+            int64_t dt = p->a_prefill * P + p->c_prefill;
+            trace_other(&tr, 1, (uint32_t)nA, t, P);
+            t += dt;
+            for (int j = 0; j < cap; j++) { head[j] = th[j]; remain[j] = tr_[j]; }
+            for (int k = 0; k < nA; k++) {
+                int j = pick_client[k], req = pick_req[k];
+                run_req[j] = req; run_rem[j] = out_len[req];
+                if (served_by) served_by[req] = j;
+                if (start_us) start_us[req] = t - dt;      /* start of the prefill iteration */
+            }
+            nR += nA;
+            busy += (int64_t)nA * dt;
+            Cd = 0;
+            npre++;
+        } else {
+            int64_t D = nR;
+            int64_t dt = p->b_decode * D + p->c_decode;
+            trace_decode(&tr, t, D);
+            t += dt;
+            for (int j = 0; j < cap; j++) {
+                if (run_req[j] < 0) continue;
+                run_rem[j] -= 1;
+                if (run_rem[j] == 0) { finish[run_req[j]] = t; run_req[j] = -1; done++; nR--; }
+            }
+            busy += D * dt;
+            Cd += p->b_decode * D;
+            ndec++;
+        }
+    }
+    trace_flush(&tr);
+    *total_us = t; *busy_slot_us = busy; *n_prefill_iter = npre; *n_decode_iter = ndec;
+    *trace_hash = tr.hash;
+    if (trace_len) *trace_len = tr.len;
+    *status = done == N ? ST_OK : ST_BAD_SIM_INPUT;
+    free(q); free(qbeg); free(head); free(th); free(remain); free(tr_); free(run_req); free(run_rem);
+    free(pick_client); free(pick_req);
+}
+
+int oracle_online_iter_sim_assigned(const int32_t *in_len, const int32_t *out_len, const int32_t *assign,
+                                    int S, int N, const oracle_sim_params *p, int64_t *finish_us,
+                                    int64_t *total_us, int64_t *busy_slot_us, int32_t *n_prefill_iter,
+                                    int32_t *n_decode_iter, uint64_t *trace_hash, int32_t *served_by,
+                                    int64_t *start_us, void *trace_buf, int32_t *trace_len, int trace_scenarios,
+                                    int trace_capacity, int32_t *status_out)
+{
+    if (!in_len || !out_len || !assign || !p || !finish_us || !total_us || !busy_slot_us ||
+        !n_prefill_iter || !n_decode_iter || !trace_hash || !status_out) return -1;
+    if (S <= 0 || N <= 0 || p->cap <= 0 || p->policy < 0 || p->policy > 2) return -1;
+    if (p->a_prefill < 0 || p->b_decode < 0 || p->c_prefill < 0 || p->c_decode < 0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < S; s++) {
+        int traced = trace_buf && s < trace_scenarios;
+        sim_assigned_one(in_len + (size_t)s * N, out_len + (size_t)s * N, assign + (size_t)s * N, N, p,
+                         finish_us + (size_t)s * N, total_us + s, busy_slot_us + s, n_prefill_iter + s,
+                         n_decode_iter + s, trace_hash + s, served_by ? served_by + (size_t)s * N : 0,
+                         start_us ? start_us + (size_t)s * N : 0,
+                         traced ? (trace_rec *)trace_buf + (size_t)s * trace_capacity : 0,
+                         traced ? trace_capacity : 0, (trace_len && s < trace_scenarios) ? trace_len + s : 0,
+                         status_out + s);
+    }
+    return 0;
+}
+
 /* affine iteration-time model of the paper's experiment section, exposed for the worked-example pins */
 int64_t oracle_prefill_time(const oracle_sim_params *p, int64_t tokens) { return p->a_prefill * tokens + p->c_prefill; }
 int64_t oracle_decode_time(const oracle_sim_params *p, int64_t seqs) { return p->b_decode * seqs + p->c_decode; }

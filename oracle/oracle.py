@@ -108,6 +108,32 @@ def online_iter_sim(arrival_us, in_len, out_len, params: dict, trace_scenarios=0
                 n_decode_iter=ndec, trace_hash=h, trace=tb, trace_len=tl, status=status)
 
 
+def online_iter_sim_assigned(in_len, out_len, assign, params: dict, trace_scenarios=0, trace_capacity=0):
+    in_len = np.ascontiguousarray(in_len, dtype=np.int32)
+    out_len = np.ascontiguousarray(out_len, dtype=np.int32)
+    assign = np.ascontiguousarray(assign, dtype=np.int32)
+    S, N = in_len.shape
+    p = make_params(**params)
+    finish = np.zeros((S, N), np.int64)
+    total = np.zeros(S, np.int64)
+    busy = np.zeros(S, np.int64)
+    npre = np.zeros(S, np.int32)
+    ndec = np.zeros(S, np.int32)
+    h = np.zeros(S, np.uint64)
+    served = np.zeros((S, N), np.int32)
+    start = np.zeros((S, N), np.int64)
+    status = np.zeros(S, np.int32)
+    tb = tl = None
+    if trace_scenarios > 0 and trace_capacity > 0:
+        tb = np.zeros((trace_scenarios, trace_capacity), TRACE_DTYPE)
+        tl = np.zeros(trace_scenarios, np.int32)
+    rc = lib().oracle_online_iter_sim_assigned(_p(in_len), _p(out_len), _p(assign), S, N, C.byref(p), _p(finish),
+                                               _p(total), _p(busy), _p(npre), _p(ndec), _p(h), _p(served), _p(start), _p(tb),
+                                               _p(tl), int(trace_scenarios), int(trace_capacity), _p(status))
+    return dict(rc=rc, finish_us=finish, total_us=total, busy_slot_us=busy, n_prefill_iter=npre,
+                n_decode_iter=ndec, trace_hash=h, served_by=served, start_us=start, trace=tb, trace_len=tl, status=status)
+
+
 def fnv1a64(data: bytes) -> int:
     buf = (C.c_uint8 * len(data)).from_buffer_copy(data) if data else None
     return int(lib().oracle_fnv1a64(buf, len(data), lib().oracle_fnv1a64_init()))

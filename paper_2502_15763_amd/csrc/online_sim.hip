@@ -7,165 +7,12 @@
 // per-request remaining tokens live one per lane.
 #include "mmbp_dev.hpp"
 
+#include "sim_trace.hpp"
+
 namespace mmbp {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr uint64_t kFnvBasis = 0xcbf29ce484222325ull;
-constexpr uint64_t kFnvPrime = 0x100000001b3ull;
-
-__device__ __forceinline__ int64_t uniform_i64(int64_t x)
-{
-    uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)x);
-    uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)x >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
-__device__ __forceinline__ int64_t wave_sum_i64(int64_t x)
-{
-    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor((long long)x, off);
-    return uniform_i64(x);
-}
-
-__device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t x, int lane)
-{
-    for (int off = 1; off < 64; off <<= 1) {
-        int64_t y = __shfl_up((long long)x, off);
-        if (lane >= off) x += y;
-    }
-    return x;
-}
-
-template <int NBYTES>
-__device__ __forceinline__ uint64_t fnv_plain(uint64_t h, uint64_t w)
-{
-#pragma unroll
-    for (int b = 0; b < NBYTES; b++) {
-        h = (h ^ (w & 0xffull)) * kFnvPrime;
-        w >>= 8;
-    }
-    return h;
-}
-
-// FNV-1a of one 24-byte trace record (kind u32, count u32, t_start i64, x i64, little endian).
-//
-// A byte step is (hi:lo) <- ((hi:lo) ^ b) * prime.  The xor only touches lo, and a run of z zero
-// bytes is one multiplication by prime^z, so every step has the form
-//     v = lo ^ b;   lo' = v * Pl;   hi' = hi * Pl + v * Ph + mulhi(v, Pl)      (Ph:Pl = prime^z)
-// The lo chain is the only sequential part (scalar: xor, multiply).  hi is linear in the v of the
-// steps: hi_end = hi_0 * prod(Pl) + sum_s e_s * W_s,  e_s = v_s * Ph_s + mulhi(v_s, Pl_s),
-// W_s = product of the Pl of the later steps, so lane s takes v_s and one 16-lane sum finishes the
-// record.  Trace fields are small numbers in wide words; for count < 2^16, 0 <= t_start < 2^40 and
-// 0 <= x < 2^16 the record is the fixed sequence of 14 steps below (bytes known to be zero are
-// folded into runs).  Anything else takes the byte-by-byte path.
-constexpr uint64_t fnv_pow(int z) { uint64_t r = 1; for (int i = 0; i < z; i++) r *= kFnvPrime; return r; }
-constexpr int kHashSteps = 14;
-constexpr int kStepBytes[kHashSteps] = {1, 3, 1, 1, 2, 1, 1, 1, 1, 1, 3, 1, 1, 6};   // kind, 0*3, count*2, 0*2, t*5, 0*3, x*2, 0*6
-constexpr int step_after(int s) { int n = 24; for (int i = 0; i <= s; i++) n -= kStepBytes[i]; return n; }
-
-struct HashLane {          // per-lane constants of the record hash (lane s = step s; zero beyond the steps)
-    uint32_t pl, ph, w;
-};
-
-__device__ __forceinline__ HashLane hash_lane_init(int lane)
-{
-    HashLane c;
-    c.pl = 0; c.ph = 0; c.w = 0;
-#pragma unroll
-    for (int st = 0; st < kHashSteps; st++)
-        if (lane == st) {
-            c.pl = (uint32_t)fnv_pow(kStepBytes[st]);
-            c.ph = (uint32_t)(fnv_pow(kStepBytes[st]) >> 32);
-            c.w = (uint32_t)fnv_pow(step_after(st));
-        }
-    return c;
-}
-
-__device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32_t count, int64_t t_start, int64_t x,
-                                               const HashLane &c, int lane)
-{
-    const uint64_t ut = (uint64_t)t_start, ux = (uint64_t)x;
-    if (((uint64_t)(count >> 16) | (ut >> 40) | (ux >> 16) | (uint64_t)(kind >> 8)) != 0) {
-        h = fnv_plain<8>(h, (uint64_t)kind | ((uint64_t)count << 32));
-        h = fnv_plain<8>(h, ut);
-        return fnv_plain<8>(h, ux);
-    }
-    uint32_t lo = (uint32_t)h, hi = (uint32_t)(h >> 32);
-    uint32_t vv = 0;
-    constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP2 = (uint32_t)fnv_pow(2), kP3 = (uint32_t)fnv_pow(3),
-                       kP6 = (uint32_t)fnv_pow(6), kP24 = (uint32_t)fnv_pow(24);
-    int st = 0;
-    auto byte_step = [&](uint32_t b) {
-        const uint32_t v = lo ^ b;
-        vv = lane == st ? v : vv;
-        lo = v * kP1;
-        st++;
-    };
-    auto run_step = [&](uint32_t pl) {
-        vv = lane == st ? lo : vv;
-        lo = lo * pl;
-        st++;
-    };
-    const uint32_t tl = (uint32_t)ut, th = (uint32_t)(ut >> 32);
-    byte_step(kind);
-    run_step(kP3);
-    byte_step(count & 0xffu);
-    byte_step(count >> 8);
-    run_step(kP2);
-    byte_step(tl & 0xffu);
-    byte_step((tl >> 8) & 0xffu);
-    byte_step((tl >> 16) & 0xffu);
-    byte_step(tl >> 24);
-    byte_step(th);
-    run_step(kP3);
-    byte_step((uint32_t)ux & 0xffu);
-    byte_step((uint32_t)ux >> 8);
-    run_step(kP6);
-    uint32_t e = (vv * c.ph + __umulhi(vv, c.pl)) * c.w;
-    e += dpp_u32<0x111, 0xf>(0u, e);           // sum over the first row of 16 lanes
-    e += dpp_u32<0x112, 0xf>(0u, e);
-    e += dpp_u32<0x114, 0xf>(0u, e);
-    e += dpp_u32<0x118, 0xf>(0u, e);
-    hi = hi * kP24 + (uint32_t)__builtin_amdgcn_readlane((int)e, 15);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-struct Trace {
-    uint64_t h;
-    HashLane hc;
-    mmbp_trace_rec *buf;
-    int cap, len;
-    int run_open;
-    uint32_t run_count;
-    int64_t run_t, run_D;
-
-    __device__ __forceinline__ void emit(uint32_t kind, uint32_t count, int64_t t_start, int64_t x, int lane)
-    {
-        h = fnv_record(h, kind, count, t_start, x, hc, lane);
-        if (buf && len < cap && lane == 0) {
-            mmbp_trace_rec r;
-            r.kind = kind; r.count = count; r.t_start = t_start; r.x = x;
-            buf[len] = r;
-        }
-        len++;
-    }
-    __device__ __forceinline__ void flush(int lane)
-    {
-        if (run_open) { emit(0u, run_count, run_t, run_D, lane); run_open = 0; }
-    }
-    // k consecutive decode iterations with D running requests, the first starting at t
-    __device__ __forceinline__ void decode(int64_t t, int64_t D, uint32_t k, int lane)
-    {
-        if (run_open && run_D == D) { run_count += k; return; }
-        flush(lane);
-        run_open = 1; run_count = k; run_t = t; run_D = D;
-    }
-    __device__ __forceinline__ void other(uint32_t kind, uint32_t count, int64_t t, int64_t x, int lane)
-    {
-        flush(lane);
-        emit(kind, count, t, x, lane);
-    }
-};
 
 __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
     const int64_t *__restrict__ arrival_all, const int32_t *__restrict__ in_all, const int32_t *__restrict__ out_all,

@@ -303,3 +303,93 @@ def test_sim_policies_agree_where_they_must(oracle):
     r = oracle.online_iter_sim(arr, c5.in_len, c5.out_len, dict(wide, policy=1))
     assert np.array_equal(r["finish_us"], ref["finish_us"]) and np.array_equal(r["trace_hash"], ref["trace_hash"])
     assert oracle.online_iter_sim(arr, c5.in_len, c5.out_len, dict(wide, policy=3))["rc"] != 0
+
+
+# ------------------------------------------------------------------ simulator fed by an offline assignment
+GOLD_ASSIGNED = os.path.join(os.path.dirname(__file__), "golden", "sim_assigned_hand_worked.txt")
+
+
+def test_sim_assigned_hand_worked(oracle):
+    seen = 0
+    for line in open(GOLD_ASSIGNED):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = [x.strip() for x in line.split("|")]
+        ints = lambda k: [int(x) for x in f[k].split(",")]
+        p = dict(cap=int(f[1]), a_prefill=1, b_decode=10, c_prefill=5, c_decode=2, max_prefill_tokens=0, policy=int(f[2]))
+        r = oracle.online_iter_sim_assigned(np.array([ints(3)]), np.array([ints(4)]), np.array([ints(5)]), p, 1, 32)
+        assert r["rc"] == 0 and int(r["status"][0]) == 0
+        assert [int(r[k][0]) for k in ("total_us", "busy_slot_us", "n_prefill_iter", "n_decode_iter")] == [int(f[k]) for k in (6, 7, 8, 9)]
+        assert r["finish_us"][0].tolist() == ints(10) and r["served_by"][0].tolist() == ints(11)
+        assert r["start_us"][0].tolist() == ints(12)
+        want = [tuple(int(x) for x in rec.split(":")) for rec in f[13].split()]
+        assert [tuple(int(x) for x in rec) for rec in r["trace"][0][: int(r["trace_len"][0])]] == want
+        raw = b"".join(np.array([w], dtype=oracle.TRACE_DTYPE).tobytes() for w in want)
+        assert int(r["trace_hash"][0]) == oracle.fnv1a64(raw)
+        seen += 1
+    assert seen == 2
+
+
+@pytest.mark.parametrize("policy,tok_cap", [(0, 0), (1, 0), (1, 700), (2, 0)])
+def test_sim_assigned_properties(oracle, policy, tok_cap):
+    """What the method fixes, checked from the outputs alone: every request runs once on one client,
+    a client runs one request at a time, own-queue requests start longest first, a client steals
+    only when its own queue is used up, and what it steals is the longest request left in the
+    victim's queue."""
+    rng = np.random.default_rng(100 + policy)
+    S, N, cap = 6, 180, 7
+    c5 = W.config5(S=S, N=N)
+    inl, outl = c5.in_len, c5.out_len
+    assign = rng.integers(0, cap, (S, N)).astype(np.int32)
+    assign[0] = np.arange(N) % cap                     # balanced
+    assign[1] = np.minimum(np.arange(N) // 60, cap - 1)  # three loaded clients, four that only steal
+    p = dict(c5.params, cap=cap, max_prefill_tokens=tok_cap, policy=policy)
+    r = oracle.online_iter_sim_assigned(inl, outl, assign, p, S, 2000)
+    assert (r["status"] == 0).all()
+    for s in range(S):
+        ln = inl[s].astype(np.int64) + outl[s]
+        st, fi, by = r["start_us"][s], r["finish_us"][s], r["served_by"][s]
+        assert ((by >= 0) & (by < cap)).all() and (fi > st).all()
+        for j in range(cap):
+            mine = np.where(by == j)[0]
+            o = mine[np.argsort(st[mine], kind="stable")]
+            assert (st[o][1:] >= fi[o][:-1]).all()                      # one at a time
+            own = np.where((assign[s] == j))[0]
+            own_sorted = own[np.lexsort((own, -ln[own]))]              # I_j: longest first, then index
+            assert (np.diff(st[own_sorted]) >= 0).all()                 # whoever runs them, they leave I_j in order
+            stolen = mine[assign[s][mine] != j]
+            if len(stolen) and len(own):
+                assert st[stolen].min() >= st[own].max()                # steals only after the own queue is used up
+        tr = r["trace"][s][: int(r["trace_len"][s])]
+        dec, pre = tr[tr["kind"] == 0], tr[tr["kind"] == 1]
+        assert int((dec["count"].astype(np.int64) * dec["x"]).sum()) == int(outl[s].sum())
+        assert int(pre["count"].sum()) == N and int(pre["x"].sum()) == int(inl[s].sum())
+        assert (tr["kind"] != 2).all()
+        if policy == 2:
+            assert (pre["count"] == 1).all()
+        if tok_cap:
+            assert (pre[pre["count"] > 1]["x"] <= tok_cap).all()
+    assert (r["served_by"][1] >= 3).any()                              # the idle clients did steal
+
+
+def test_sim_assigned_reduces_to_known_cases(oracle):
+    c5 = W.config5(S=3, N=30)
+    inl, outl = c5.in_len, c5.out_len
+    # one client: the requests run one after the other, longest first; the total has a closed form
+    p = dict(c5.params, cap=1)
+    r = oracle.online_iter_sim_assigned(inl, outl, np.zeros_like(inl), p)
+    a, b, cp, cd = p["a_prefill"], p["b_decode"], p["c_prefill"], p["c_decode"]
+    expect = (a * inl.astype(np.int64) + cp + outl.astype(np.int64) * (b + cd)).sum(axis=1)
+    assert r["total_us"].tolist() == expect.tolist()
+    ln = inl.astype(np.int64) + outl
+    for s in range(3):
+        order = np.argsort(r["start_us"][s], kind="stable")
+        assert (np.diff(ln[s][order]) <= 0).all()
+    # one request per client: everything is prefilled at t = 0, as in the FCFS simulator
+    p = dict(c5.params, cap=30)
+    r = oracle.online_iter_sim_assigned(inl, outl, np.tile(np.arange(30, dtype=np.int32), (3, 1)), p)
+    f = oracle.online_iter_sim(np.zeros_like(inl, dtype=np.int64), inl, outl, p)
+    assert np.array_equal(r["finish_us"], f["finish_us"]) and np.array_equal(r["trace_hash"], f["trace_hash"])
+    # bad input: a client index outside [0, cap)
+    bad = np.zeros_like(inl); bad[1, 5] = 30
+    assert oracle.online_iter_sim_assigned(inl, outl, bad, p)["status"].tolist() == [0, 4, 0]
