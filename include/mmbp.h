@@ -30,7 +30,8 @@ extern "C" {
 #define MMBP_OK            0
 #define MMBP_EINVAL       -1  /* null pointer, non-positive size, bad dtype, negative max_passes, unknown policy */
 #define MMBP_EINFEASIBLE  -2  /* N > M * cap: no assignment satisfies the cardinality limit */
-#define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 64) */
+#define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 64,
+                                 assigned simulator N <= 8192) */
 #define MMBP_EWORKSPACE   -4  /* workspace missing or smaller than mmbp_workspace_bytes() */
 #define MMBP_EHIP         -5  /* a HIP call or kernel launch failed; see mmbp_strerror() */
 
@@ -50,6 +51,7 @@ extern "C" {
 #define MMBP_MAX_N (1 << 20)
 #define MMBP_MAX_M 256
 #define MMBP_SIM_MAX_CAP 64
+#define MMBP_SIM_ASSIGNED_MAX_N 8192
 
 int mmbp_version(void);
 
@@ -175,6 +177,33 @@ int online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, const int3
                     int32_t *n_prefill_iter, int32_t *n_decode_iter, uint64_t *trace_hash,
                     mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
                     int trace_capacity, int32_t *status_out, void *stream);
+
+/*
+ * The iteration simulator fed by an offline assignment (for example the result of
+ * mmbp_local_search with M = params->cap clients): request scheduling by the sorting and online
+ * preemptive method of the paper's section "Online requests and iteration scheduling".
+ *   I_j = the requests with assign == j, sorted by in_len + out_len, longest first (equal lengths:
+ *   lower index first); remain_token(j) = sum of in_len + out_len over what is left in I_j.  At an
+ *   iteration boundary the clients are visited in index order: an idle client takes the head of
+ *   its own I_j if there is one, otherwise the head of the I_v with the largest positive
+ *   remain_token (lowest v among equals).  The requests picked form the prefill that could be
+ *   dispatched (cut by max_prefill_tokens like the FCFS prefix; the first pick always fits); the
+ *   decision between prefill and decode, the time model, the trace and all other outputs are those
+ *   of online_iter_sim, and picks are only taken when the prefill is dispatched.  All requests are
+ *   known at t = 0 (the method works on the offline request set): there are no arrival times.
+ * in_len, out_len [S,N] int32 >= 1;  assign [S,N] int32 in [0, params->cap)
+ * served_by  nullable, [S,N] int32: the client that ran the request (differs from assign when stolen)
+ * start_us   nullable, [S,N] int64: start of the prefill iteration that admitted the request
+ * status_out [S]: MMBP_ST_OK or MMBP_ST_BAD_SIM_INPUT (then every output of the scenario is 0 and
+ *            served_by is -1)
+ * N <= MMBP_SIM_ASSIGNED_MAX_N (the queues of a scenario are kept in LDS).
+ */
+int online_iter_sim_assigned(const int32_t *in_len, const int32_t *out_len, const int32_t *assign, int S, int N,
+                             const mmbp_sim_params *params /* host */, int64_t *finish_us, int64_t *total_us,
+                             int64_t *busy_slot_us, int32_t *n_prefill_iter, int32_t *n_decode_iter,
+                             uint64_t *trace_hash, int32_t *served_by, int64_t *start_us,
+                             mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
+                             int trace_capacity, int32_t *status_out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -19,7 +19,7 @@ ST_OK, ST_TRUNCATED, ST_BAD_ASSIGN, ST_BAD_COST, ST_BAD_SIM_INPUT = 0, 1, 2, 3, 
 EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 
 EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_lower_bound",
-           "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim")
+           "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim", "online_iter_sim_assigned")
 
 
 class SimParams(C.Structure):
@@ -60,6 +60,9 @@ def load_library() -> C.CDLL:
     lib.online_iter_sim.restype = i
     lib.online_iter_sim.argtypes = [vp, vp, vp, i, i, C.POINTER(SimParams), vp, vp, vp, vp, vp, vp, vp, vp, i, i,
                                     vp, vp]
+    lib.online_iter_sim_assigned.restype = i
+    lib.online_iter_sim_assigned.argtypes = [vp, vp, vp, i, i, C.POINTER(SimParams), vp, vp, vp, vp, vp, vp, vp, vp,
+                                             vp, vp, i, i, vp, vp]
     _lib = lib
     return lib
 
@@ -183,6 +186,36 @@ def online_iter_sim(arrival_us, in_len, out_len, params: dict, finish_us, total_
 # Convenience wrappers used by tests, the smoke check and the benchmark: allocate outputs with
 # torch, call the entry point, hand back tensors.  They add no computation.
 # ------------------------------------------------------------------------------------------
+def _sim_params(params: dict) -> SimParams:
+    return SimParams(int(params["cap"]), int(params.get("policy", 0)), int(params["a_prefill"]), int(params["b_decode"]),
+                     int(params["c_prefill"]), int(params["c_decode"]), int(params.get("max_prefill_tokens", 0)))
+
+
+def online_iter_sim_assigned(in_len, out_len, assign, params: dict, finish_us, total_us, busy_slot_us,
+                             n_prefill_iter, n_decode_iter, trace_hash, status_out, served_by=None, start_us=None,
+                             trace_buf=None, trace_len=None, stream=None, raise_on_error=True) -> int:
+    """trace_buf: optional uint8 tensor [trace_scenarios, trace_capacity, 24]."""
+    torch = _torch()
+    S, N = in_len.shape
+    p = _sim_params(params)
+    tsc = tcap = 0
+    if trace_buf is not None:
+        if trace_buf.dtype != torch.uint8 or trace_buf.dim() != 3 or trace_buf.shape[2] != 24:
+            raise ValueError("trace_buf must be uint8 [scenarios, capacity, 24]")
+        tsc, tcap = int(trace_buf.shape[0]), int(trace_buf.shape[1])
+    rc = load_library().online_iter_sim_assigned(
+        _ptr(in_len, torch.int32, (S, N), "in_len"), _ptr(out_len, torch.int32, (S, N), "out_len"),
+        _ptr(assign, torch.int32, (S, N), "assign"), S, N, C.byref(p),
+        _ptr(finish_us, torch.int64, (S, N), "finish_us"), _ptr(total_us, torch.int64, (S,), "total_us"),
+        _ptr(busy_slot_us, torch.int64, (S,), "busy_slot_us"), _ptr(n_prefill_iter, torch.int32, (S,), "n_prefill_iter"),
+        _ptr(n_decode_iter, torch.int32, (S,), "n_decode_iter"), _ptr(trace_hash, torch.int64, (S,), "trace_hash"),
+        _ptr(served_by, torch.int32, (S, N), "served_by") if served_by is not None else None,
+        _ptr(start_us, torch.int64, (S, N), "start_us") if start_us is not None else None,
+        _ptr(trace_buf, name="trace_buf"), _ptr(trace_len, torch.int32, (tsc,), "trace_len") if trace_buf is not None else None,
+        tsc, tcap, _ptr(status_out, torch.int32, (S,), "status_out"), _stream(stream))
+    return _check(rc, raise_on_error)
+
+
 def run_local_search(cost, assign0, M, cap, max_passes, want_log=False, stream=None, raise_on_error=True,
                      pruned=False):
     torch = _torch()
@@ -235,5 +268,29 @@ def run_online_sim(arrival_us, in_len, out_len, params, trace_scenarios=0, trace
                          out["busy_slot_us"], out["n_prefill_iter"], out["n_decode_iter"], out["trace_hash"],
                          out["status"], trace_buf=out["trace"], trace_len=out["trace_len"], stream=stream,
                          raise_on_error=raise_on_error)
+    out["rc"] = rc
+    return out
+
+
+def run_online_sim_assigned(in_len, out_len, assign, params, trace_scenarios=0, trace_capacity=0, stream=None,
+                            raise_on_error=True):
+    torch = _torch()
+    dev = in_len.device
+    S, N = in_len.shape
+    i64 = dict(dtype=torch.int64, device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    out = dict(finish_us=torch.empty((S, N), **i64), total_us=torch.empty(S, **i64),
+               busy_slot_us=torch.empty(S, **i64), n_prefill_iter=torch.empty(S, **i32),
+               n_decode_iter=torch.empty(S, **i32), trace_hash=torch.empty(S, **i64),
+               served_by=torch.empty((S, N), **i32), start_us=torch.empty((S, N), **i64),
+               status=torch.empty(S, **i32), trace=None, trace_len=None)
+    if trace_scenarios > 0 and trace_capacity > 0:
+        out["trace"] = torch.zeros((trace_scenarios, trace_capacity, 24), dtype=torch.uint8, device=dev)
+        out["trace_len"] = torch.zeros(trace_scenarios, **i32)
+    rc = online_iter_sim_assigned(in_len, out_len, assign, params, out["finish_us"], out["total_us"],
+                                  out["busy_slot_us"], out["n_prefill_iter"], out["n_decode_iter"], out["trace_hash"],
+                                  out["status"], served_by=out["served_by"], start_us=out["start_us"],
+                                  trace_buf=out["trace"], trace_len=out["trace_len"], stream=stream,
+                                  raise_on_error=raise_on_error)
     out["rc"] = rc
     return out

@@ -24,7 +24,7 @@ const char *mmbp_strerror(int code)
     case MMBP_OK: return "ok";
     case MMBP_EINVAL: return "invalid argument (null pointer, non-positive size, bad dtype, negative max_passes or unknown policy)";
     case MMBP_EINFEASIBLE: return "infeasible: N > M * cap";
-    case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64)";
+    case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64, assigned simulator N <= 8192)";
     case MMBP_EWORKSPACE: return "workspace missing or too small (see mmbp_workspace_bytes)";
     case MMBP_EHIP: return g_hip_err;
     default: return "unknown error code";
@@ -121,6 +121,30 @@ int online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, const int3
                                            trace_buf ? trace_len : nullptr, trace_scenarios, trace_capacity,
                                            status_out, (hipStream_t)stream);
     return e == hipSuccess ? MMBP_OK : fail_hip(e, "online_iter_sim");
+}
+
+int online_iter_sim_assigned(const int32_t *in_len, const int32_t *out_len, const int32_t *assign, int S, int N,
+                             const mmbp_sim_params *params, int64_t *finish_us, int64_t *total_us,
+                             int64_t *busy_slot_us, int32_t *n_prefill_iter, int32_t *n_decode_iter,
+                             uint64_t *trace_hash, int32_t *served_by, int64_t *start_us, mmbp_trace_rec *trace_buf,
+                             int32_t *trace_len, int trace_scenarios, int trace_capacity, int32_t *status_out,
+                             void *stream)
+{
+    if (!in_len || !out_len || !assign || !params || !finish_us || !total_us || !busy_slot_us || !n_prefill_iter ||
+        !n_decode_iter || !trace_hash || !status_out)
+        return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || params->cap <= 0) return MMBP_EINVAL;
+    if (params->policy < MMBP_POLICY_RULE || params->policy > MMBP_POLICY_PREFILL_FIRST_SINGLE) return MMBP_EINVAL;
+    if (params->a_prefill < 0 || params->b_decode < 0 || params->c_prefill < 0 || params->c_decode < 0)
+        return MMBP_EINVAL;
+    if (trace_buf && (trace_scenarios < 0 || trace_capacity < 0 || !trace_len)) return MMBP_EINVAL;
+    if (params->cap > MMBP_SIM_MAX_CAP || N > MMBP_SIM_ASSIGNED_MAX_N) return MMBP_EUNSUPPORTED;
+    if (!trace_buf) { trace_scenarios = 0; trace_capacity = 0; }
+    hipError_t e = mmbp::launch_online_sim_assigned(in_len, out_len, assign, S, N, *params, finish_us, total_us,
+                                                    busy_slot_us, n_prefill_iter, n_decode_iter, trace_hash, served_by,
+                                                    start_us, trace_buf, trace_buf ? trace_len : nullptr,
+                                                    trace_scenarios, trace_capacity, status_out, (hipStream_t)stream);
+    return e == hipSuccess ? MMBP_OK : fail_hip(e, "online_iter_sim_assigned");
 }
 
 }  // extern "C"

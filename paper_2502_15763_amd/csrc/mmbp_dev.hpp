@@ -38,6 +38,13 @@ hipError_t launch_online_sim(const int64_t *arrival_us, const int32_t *in_len, c
                              int32_t *n_prefill_iter, int32_t *n_decode_iter, uint64_t *trace_hash,
                              mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios, int trace_capacity,
                              int32_t *status_out, hipStream_t st);
+size_t sim_assigned_lds_bytes(int N);
+hipError_t launch_online_sim_assigned(const int32_t *in_len, const int32_t *out_len, const int32_t *assign, int S, int N,
+                                      const mmbp_sim_params &p, int64_t *finish_us, int64_t *total_us,
+                                      int64_t *busy_slot_us, int32_t *n_prefill_iter, int32_t *n_decode_iter,
+                                      uint64_t *trace_hash, int32_t *served_by, int64_t *start_us,
+                                      mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
+                                      int trace_capacity, int32_t *status_out, hipStream_t st);
 
 #if defined(__HIPCC__)
 // ------------------------------------------------------------------------------------------

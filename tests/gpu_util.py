@@ -76,12 +76,32 @@ def gpu_online_sim(arrival, in_len, out_len, params, trace_scenarios=0, trace_ca
     return out
 
 
+def gpu_online_sim_assigned(in_len, out_len, assign, params, trace_scenarios=0, trace_capacity=0):
+    import torch
+    from paper_2502_15763_amd import api
+    r = api.run_online_sim_assigned(to_dev(in_len.astype(np.int32)), to_dev(out_len.astype(np.int32)),
+                                    to_dev(assign.astype(np.int32)), params, trace_scenarios, trace_capacity)
+    torch.cuda.synchronize()
+    out = dict(rc=r["rc"])
+    for k in ("finish_us", "total_us", "busy_slot_us", "n_prefill_iter", "n_decode_iter", "status", "served_by", "start_us"):
+        out[k] = r[k].cpu().numpy()
+    out["trace_hash"] = u64(r["trace_hash"])
+    if r["trace"] is not None:
+        from oracle.oracle import TRACE_DTYPE
+        out["trace"] = r["trace"].cpu().numpy().view(TRACE_DTYPE).reshape(trace_scenarios, trace_capacity)
+        out["trace_len"] = r["trace_len"].cpu().numpy()
+    return out
+
+
 def compare_sim(g, o, label=""):
     assert g["rc"] == 0 and o["rc"] == 0
     for k in ("status", "total_us", "busy_slot_us", "n_prefill_iter", "n_decode_iter", "trace_hash", "finish_us"):
         if not np.array_equal(g[k], o[k]):
             bad = np.argwhere(g[k].reshape(g[k].shape[0], -1) != o[k].reshape(o[k].shape[0], -1))
             raise AssertionError(f"{label}: {k} differs, first at {bad[0].tolist()}: gpu={g[k][tuple(bad[0]) if g[k].ndim > 1 else bad[0][0]]}")
+    for k in ("served_by", "start_us"):
+        if k in g and k in o:
+            assert np.array_equal(g[k], o[k]), f"{label}: {k} differs"
     if "trace" in g and o.get("trace") is not None:
         assert np.array_equal(g["trace_len"], o["trace_len"]), f"{label}: trace_len"
         for s in range(g["trace"].shape[0]):

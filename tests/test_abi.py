@@ -21,7 +21,8 @@ def _declared_functions():
 
 def test_header_declares_expected_entry_points():
     names = _declared_functions()
-    for n in ("mmbp_lower_bound", "mmbp_local_search", "online_iter_sim", "mmbp_workspace_bytes",
+    for n in ("mmbp_lower_bound", "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim",
+              "online_iter_sim_assigned", "mmbp_workspace_bytes",
               "mmbp_strerror", "mmbp_version"):
         assert n in names
 
@@ -71,6 +72,13 @@ def test_host_side_argument_validation():
     for bad_policy in (-1, 3):
         assert sim(*args(api.SimParams(4, bad_policy, 1, 1, 1, 1, 0))) == api.EINVAL
     assert sim(one, one, one, 1, 4, None, one, one, one, one, one, one, None, None, 0, 0, one, None) == api.EINVAL
+    sa = lib.online_iter_sim_assigned
+    aargs = lambda pp, n=4: (one, one, one, 1, n, C.byref(pp), one, one, one, one, one, one, None, None, None, None, 0, 0, one, None)
+    assert sa(*aargs(api.SimParams(65, 0, 1, 1, 1, 1, 0))) == api.EUNSUPPORTED
+    assert sa(*aargs(api.SimParams(4, 0, 1, 1, 1, 1, 0), 8193)) == api.EUNSUPPORTED
+    assert sa(*aargs(api.SimParams(4, 5, 1, 1, 1, 1, 0))) == api.EINVAL
+    assert sa(*aargs(api.SimParams(0, 0, 1, 1, 1, 1, 0))) == api.EINVAL
+    assert sa(None, one, one, 1, 4, C.byref(api.SimParams(4, 0, 1, 1, 1, 1, 0)), one, one, one, one, one, one, None, None, None, None, 0, 0, one, None) == api.EINVAL
     for code in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(api.mmbp_strerror(code), str) and api.mmbp_strerror(code)
 

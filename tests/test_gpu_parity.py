@@ -7,7 +7,8 @@ import numpy as np
 import pytest
 
 from paper_2502_15763_amd import workloads as W
-from gpu_util import (say, gpu_local_search, compare_ls, gpu_lower_bound, gpu_online_sim, compare_sim)
+from gpu_util import (say, gpu_local_search, compare_ls, gpu_lower_bound, gpu_online_sim, compare_sim,
+                      gpu_online_sim_assigned)
 
 pytestmark = pytest.mark.gpu
 
@@ -324,3 +325,70 @@ def test_sim_config5_full(oracle):
     say("sim config5 oracle, all scenarios")
     o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, w.params, trace_scenarios=4, trace_capacity=8192)
     compare_sim(g, o, label="c5")
+
+
+# ------------------------------------------------------------------ simulator fed by an offline assignment
+def test_sim_assigned_hand_worked_cases(oracle):
+    for (cap, pol, inl, outl, asg) in [(2, 0, [10, 20, 5, 8], [3, 2, 4, 1], [0, 0, 0, 1]),
+                                       (3, 1, [4, 6, 5, 3, 2, 2], [2, 3, 2, 3, 2, 1], [0, 1, 1, 2, 2, 2])]:
+        p = dict(cap=cap, a_prefill=1, b_decode=10, c_prefill=5, c_decode=2, max_prefill_tokens=0, policy=pol)
+        a, b, c = np.array([inl], np.int32), np.array([outl], np.int32), np.array([asg], np.int32)
+        say(f"sim assigned hand-worked cap={cap}")
+        compare_sim(gpu_online_sim_assigned(a, b, c, p, 1, 32), oracle.online_iter_sim_assigned(a, b, c, p, 1, 32),
+                    label=f"assigned hand-worked cap={cap}")
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2])
+def test_sim_assigned_random(oracle, policy):
+    rng = np.random.default_rng(300 + policy)
+    for (S, N, cap, tok) in [(7, 1, 1, 0), (7, 5, 3, 0), (6, 180, 7, 0), (6, 180, 7, 700), (5, 400, 64, 0), (4, 1000, 33, 3000),
+                             (3, 64, 64, 0)]:
+        w = W.config5(S=S, N=N, seed_offset=N + cap + policy)
+        assign = rng.integers(0, cap, (S, N)).astype(np.int32)
+        assign[0] = np.arange(N) % cap
+        if S > 1:
+            assign[1] = np.minimum(np.arange(N) // max(N // 3, 1), cap - 1)      # few loaded clients, the others steal
+        if S > 2:
+            assign[2] = 0                                                       # one queue, everybody else steals
+        p = dict(w.params, cap=cap, max_prefill_tokens=tok, policy=policy)
+        say(f"sim assigned policy={policy} N={N} cap={cap} tok={tok}")
+        o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
+        g = gpu_online_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
+        compare_sim(g, o, label=f"assigned policy={policy} N={N} cap={cap}")
+
+
+def test_sim_assigned_equal_lengths_and_bad_input(oracle):
+    S, N, cap = 4, 200, 16
+    inl = np.full((S, N), 50, np.int32)
+    outl = np.full((S, N), 20, np.int32)            # all lengths equal: ties everywhere (index order, lowest client)
+    assign = (np.arange(S * N).reshape(S, N) * 7 % cap).astype(np.int32)
+    assign[3, :150] = 2
+    p = dict(W.C5_PARAMS, cap=cap)
+    say("sim assigned equal lengths")
+    compare_sim(gpu_online_sim_assigned(inl, outl, assign, p, S, 900), oracle.online_iter_sim_assigned(inl, outl, assign, p, S, 900),
+                label="assigned equal lengths")
+    bad = assign.copy()
+    bad[1, 7] = cap
+    bad[2, 0] = -1
+    inl2 = inl.copy(); inl2[3, 5] = 0
+    say("sim assigned bad input")
+    o = oracle.online_iter_sim_assigned(inl2, outl, bad, p)
+    assert o["status"].tolist() == [0, 4, 4, 4]
+    compare_sim(gpu_online_sim_assigned(inl2, outl, bad, p), o, label="assigned bad input")
+
+
+def test_hybrid_pipeline_offline_search_then_assigned_sim(oracle):
+    """The paper's offline + online combination on synthetic requests: the local search balances the
+    estimated costs over cap clients, the assigned simulator runs the result."""
+    S, N, cap = 64, 2048, 64
+    w = W.config5(S=S, N=N)
+    cost = W.job_cost(w.in_len, w.out_len, np.int32)
+    assign0 = np.tile((np.arange(N) % cap).astype(np.int32), (S, 1))
+    say("hybrid: local search M=64")
+    ls = gpu_local_search(cost, assign0, cap, N, 300, want_log=False)
+    assert (ls["status"] <= 1).all()
+    say("hybrid: assigned simulator")
+    p = dict(w.params, cap=cap)
+    o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, ls["assign"], p, 2, 8192)
+    g = gpu_online_sim_assigned(w.in_len, w.out_len, ls["assign"], p, 2, 8192)
+    compare_sim(g, o, label="hybrid")
