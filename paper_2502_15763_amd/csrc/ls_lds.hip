@@ -54,8 +54,8 @@ namespace {
 #define MMBP_LDS_WPE 4
 #endif
 constexpr int kChunk = MMBP_LDS_CHUNK;         // columns per task (multiple of 64, at most 256)
-constexpr size_t kLdsLimit = 78 * 1024;        // two workgroups per CU (160 KB); above 64 KB the launch raises the
-                                               // kernel's dynamic-LDS attribute first
+constexpr size_t kLdsLimit = 156 * 1024;       // a CU has 160 KB, all of which one workgroup may use; above 64 KB the
+                                               // launch raises the kernel's dynamic-LDS attribute first
 static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnable as the row side of a tile");
 
 struct Ctrl {

@@ -35,6 +35,17 @@ def test_ls_small_random(oracle, dtype):
         compare_ls(g, o, label=f"N={N} M={M} cap={cap}")
 
 
+def test_ls_shapes_between_64_and_156_kb_of_lds(oracle):
+    """Layouts that need more than the default 64 KB of LDS per workgroup but still fit one CU."""
+    rng = np.random.default_rng(31)
+    for (S, N, M, cap, passes) in [(5, 2048, 64, 40, 400), (3, 8192, 16, 600, 40), (3, 10000, 8, 1300, 30)]:
+        cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=50000, dtype=np.int32, start="rr")
+        say(f"ls large-LDS shapes S={S} N={N} M={M}")
+        o = oracle.local_search(cost, assign, M, cap, passes, want_log=True)
+        g = gpu_local_search(cost, assign, M, cap, passes)
+        compare_ls(g, o, label=f"large LDS N={N} M={M}")
+
+
 def test_ls_pass_limits_and_resume(oracle):
     rng = np.random.default_rng(5)
     cost, assign = W.random_offline(rng, 6, 90, 5, 20, cost_hi=5000, dtype=np.int32)
@@ -144,7 +155,7 @@ def test_ls_multi_workgroup_path_batch(oracle):
     """Shapes too large for one workgroup's LDS, several scenarios per call, slack capacity so that
     moves and swaps are both applied; one scenario needs the 64-bit path."""
     rng = np.random.default_rng(77)
-    S, N, M, cap = 3, 6000, 6, 1100
+    S, N, M, cap = 3, 14000, 6, 2500
     cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=30000, dtype=np.int32, start="rr")
     cost = cost.astype(np.int64)
     cost[2] *= 1 << 16                      # loads above the 32-bit narrowing bound
