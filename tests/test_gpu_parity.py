@@ -134,6 +134,27 @@ def test_ls_config3_sampled(oracle):
     assert cnt.max() <= c.cap
 
 
+def test_ls_config3_first_32_to_convergence(oracle):
+    c = W.config3(S=32, max_passes=4000)
+    say("ls_config3 scenarios 0..31 to convergence")
+    g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes)
+    say("ls_config3 oracle on the same 32 scenarios")
+    o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
+    assert (o["status"] == 0).all()
+    compare_ls(g, o, label="c3 0..31 converged")
+
+
+def test_ls_repeatable(oracle):
+    """Same input three times, through the LDS path and the multi-workgroup path: identical outputs
+    (the argmin has a total order, so nothing may depend on scheduling)."""
+    for c, passes in ((W.config2(S=64), 1024), (W.config4(slack=256), 5)):
+        say(f"ls repeatable {c.name if hasattr(c, 'name') else ''} N={c.N}")
+        runs = [gpu_local_search(c.cost, c.assign0, c.M, c.cap, passes) for _ in range(3)]
+        for r in runs[1:]:
+            for k in ("assign", "load", "makespan", "passes", "evals", "status", "log"):
+                assert np.array_equal(r[k], runs[0][k]), k
+
+
 def test_ls_config3_slack_converged(oracle):
     c = W.config3(S=4, slack=128, max_passes=4000)
     say("ls_config3 slack, to convergence, S=4")
