@@ -46,6 +46,24 @@ def test_ls_shapes_between_64_and_156_kb_of_lds(oracle):
         compare_ls(g, o, label=f"large LDS N={N} M={M}")
 
 
+def test_ls_maximum_sizes(oracle):
+    """The largest client count (256), a long request list (2^18 requests, two passes against the
+    oracle) and the largest request count (2^20: loads only, max_passes = 0)."""
+    rng = np.random.default_rng(8)
+    cost, assign = W.random_offline(rng, 2, 3000, 256, 20, cost_hi=40000, dtype=np.int32)
+    say("ls M=256 N=3000")
+    compare_ls(gpu_local_search(cost, assign, 256, 20, 40), oracle.local_search(cost, assign, 256, 20, 40, want_log=True),
+               label="M=256")
+    cost, assign = W.random_offline(rng, 1, 1 << 18, 4, 1 << 17, cost_hi=3000, dtype=np.int32, start="rr")
+    say("ls N=2^18 M=4, 2 passes")
+    compare_ls(gpu_local_search(cost, assign, 4, 1 << 17, 2), oracle.local_search(cost, assign, 4, 1 << 17, 2, want_log=True),
+               label="N=2^18")
+    cost, assign = W.random_offline(rng, 1, 1 << 20, 3, 1 << 19, cost_hi=500, dtype=np.int32, start="rr")
+    say("ls N=2^20 M=3, loads only")
+    compare_ls(gpu_local_search(cost, assign, 3, 1 << 19, 0), oracle.local_search(cost, assign, 3, 1 << 19, 0, want_log=True),
+               label="N=2^20")
+
+
 def test_ls_pass_limits_and_resume(oracle):
     rng = np.random.default_rng(5)
     cost, assign = W.random_offline(rng, 6, 90, 5, 20, cost_hi=5000, dtype=np.int32)
