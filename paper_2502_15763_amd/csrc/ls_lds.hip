@@ -702,14 +702,11 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
 #ifdef MMBP_LDS_MINBYTES
     if (bytes < (size_t)(MMBP_LDS_MINBYTES)) bytes = (size_t)(MMBP_LDS_MINBYTES);
 #endif
-    if (bytes > 64 * 1024) {
-        static bool raised = false;                      // per instantiation; setting it twice is harmless
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ls_lds_kernel<CostT, BLOCK, SMALLM>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
+    if (bytes > 64 * 1024) {                             // beyond the default limit: raise it for this kernel (per device,
+                                                         // cheap, so done at every such launch)
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ls_lds_kernel<CostT, BLOCK, SMALLM>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
+        if (e != hipSuccess) return e;
     }
     ls_lds_kernel<CostT, BLOCK, SMALLM><<<dim3(S), dim3(BLOCK), bytes, st>>>(
         (const CostT *)cost, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out, evals_out,
