@@ -54,6 +54,7 @@ namespace {
 #define MMBP_LDS_WPE 4
 #endif
 constexpr int kChunk = MMBP_LDS_CHUNK;         // columns per task (multiple of 64, at most 256)
+constexpr int kSpinLimit = 1 << 20;            // bound of the one in-workgroup wait (far above any real wait)
 constexpr size_t kLdsLimit = 156 * 1024;       // a CU has 160 KB, all of which one workgroup may use; above 64 KB the
                                                // launch raises the kernel's dynamic-LDS attribute first
 static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnable as the row side of a tile");
@@ -64,8 +65,10 @@ struct Ctrl {
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
-    uint32_t vswap, vmove;
+    uint32_t vswap, vmove, vrest;  // per-pass minima: swaps and moves that involve the critical client, the rest
     int nfeas, P, rebuild, ntask, nchunk;
+    int next;                     // work counter of the rest of the scan
+    int adone;                    // waves that have posted their phase-A minima
     Top3 top;                     // three largest loads and their clients, published by wave 0
     int stop;
     int bad_cost, bad_assign;
@@ -76,6 +79,7 @@ struct Lds {
     uint16_t *job;
     unsigned long long *tasks;    // (rowbase/64 | R << 10 | g << 13) | chunk record << 32
     uint32_t *chunks;             // c0/64 | ncols << 10 | b << 19
+    uint32_t *uinfo;              // per row unit: rowbase/64 | R << 10 | g << 13
     long long *load;
     int *cnt, *gstart, *fillc, *feas, *chpre, *upre;
     uint32_t *tdl, *tr1;          // per client, for the selection: l_g - l_critical and the key bound of a best swap
@@ -108,6 +112,7 @@ __host__ __device__ inline size_t lds_bytes(int N, int M)
     b = align_up(b, 16);
     b += 8 * d.T;                     // tasks
     b += 4 * d.C;                     // chunks
+    b += 4 * d.U;                     // uinfo
     b = align_up(b, 16);
     b += 8 * (size_t)M;               // load
     b += 4 * (size_t)(M + 1) * 8;     // cnt, gstart, fillc, feas, chpre, upre, tdl, tr1
@@ -128,6 +133,7 @@ __device__ inline Lds carve(unsigned char *base, int N, int M)
     o = align_up(o, 16);
     l.tasks = (unsigned long long *)(base + o); o += 8 * d.T;
     l.chunks = (uint32_t *)(base + o); o += 4 * d.C;
+    l.uinfo = (uint32_t *)(base + o); o += 4 * d.U;
     o = align_up(o, 16);
     l.load = (long long *)(base + o); o += 8 * (size_t)M;
     l.cnt = (int *)(base + o); o += 4 * (size_t)(M + 1);
@@ -248,6 +254,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
         const int blk = (u - l.upre[g]) * kRMax;
         const int gseg = (l.gstart[g + 1] - l.gstart[g]) >> 6;
         const uint32_t w0 = (uint32_t)((l.gstart[g] >> 6) + blk) | ((uint32_t)min(kRMax, gseg - blk) << 10) | ((uint32_t)g << 13);
+        if (u < (int)d.U) l.uinfo[u] = w0;
         const int k0 = l.chpre[g + 1], n = nCh - k0;
         if (n <= 0) continue;
         const int base = atomicAdd(&l.ctrl->ntask, n);
@@ -334,7 +341,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     // loads stay below 2^29 on this path: their low words are used
     auto load32 = [&](int g) -> uint32_t { return (uint32_t)l.load[g]; };
     const int Pmax = N + 64 * M;
-    const int Tmax = (int)lds_dims(N, M).T;
+    const int Tmax = (int)lds_dims(N, M).T, Umax = (int)lds_dims(N, M).U, Cmax = (int)lds_dims(N, M).C;
     // A workgroup's waves go round the four SIMDs of its CU; the two halves of a SIMD's waves get
     // neighbouring ranges of the task table, so the SIMDs carry equal shares when waves outnumber them.
     const int twave = kWaves >= 8 ? (wave & 3) * (kWaves / 4) + (wave >> 2) : wave;
@@ -358,7 +365,8 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         const Top3 t = SMALLM ? wave_top3_small(vnew, M, lane) : wave_top3(l.load, M, lane);
         if (lane == 0) {
             ctrl->top = t;
-            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->k0key = ~0ull;
+            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->vrest = kInf; ctrl->k0key = ~0ull;
+            ctrl->next = 0; ctrl->adone = 0;
             if (w_stop) ctrl->stop = 1;
         }
         const int P = min(ctrl->P, Pmax) & ~63;
@@ -368,6 +376,13 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     if (wave == 0) open_pass(SMALLM ? (lane < M ? load32(lane) : 0u) : 0u);   // (build_layout ended with a barrier)
 
     // ---------------- pass loop ----------------
+    // A pass has three phases.  A: the candidates that can lower the makespan (they take load off
+    // the critical client): its moves and its swap tiles, all waves; barrier B1.  B: wave 0 selects
+    // the candidate to apply, changing nothing yet.  C: the rest of the scan (candidates that leave
+    // the critical client alone: their makespan is at least the current one, so they cannot change
+    // the decision), dealt out tile by tile from a counter to all waves, wave 0 joining when its
+    // selection is done; barrier B2.  Then wave 0 applies the candidate and opens the next pass.
+    enum { kActNone = 0, kActStop, kActMove, kActSwap, kActError };
     for (;;) {
         __syncthreads();                                 // B0: layout, loads, top-3 and flags are published
         if (ctrl->stop) break;
@@ -393,13 +408,18 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         auto wload = [&](int g) -> uint32_t {
             return SMALLM ? (uint32_t)__builtin_amdgcn_readlane((int)vload, g) : uniu(load32(g));
         };
-
-        // ---- moves: value only ----
-        uint32_t mbest = kInf;
-        if (nfeas > 0) {
-            for (int seg = wave; seg < nseg; seg += kWaves) {
-                const int g = l.seg_grp[seg];
-                if (prune && g != astar) continue;               // an improving move leaves the critical client
+        auto run = [&](int rowbase, int R, int X, int c0, int c1, int Y, bool star, uint32_t &sb, unsigned long long &kb) {
+            if (R < 1 || R > kRMax || c1 <= c0 || c1 > Pmax || rowbase + 64 * R > Pmax) return;   // cannot happen
+            const uint32_t lx = wload(X), ly = wload(Y);
+            const uint32_t oth = others_max(top, X, Y);
+            if (R == 1) run_tile<1>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sb, kb);
+            else if (R == 2) run_tile<2>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sb, kb);
+            else if constexpr (kRMax >= 3) {
+                if (R == 3) run_tile<3>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sb, kb);
+                else run_tile<kRMax>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sb, kb);
+            }
+        };
+        auto segment_moves = [&](int seg, int g) -> uint32_t {     // best move makespan of the 64 positions of a segment
                 const uint32_t x = l.cu[seg * 64 + lane];
                 const uint32_t ci = (x - kBias) >> 1;
                 const uint32_t la = load32(g);
@@ -410,42 +430,32 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                     const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
                     m = min(m, v);
                 }
-                if (x != kPad) mbest = min(mbest, m);
-            }
-        }
+            return x != kPad ? m : kInf;
+        };
 
-        // ---- swaps: value only; this wave's contiguous range of the task table ----
-        uint32_t sbest = kInf;
+        // ---- phase A: moves off the critical client, swap tiles (row unit of another client) x
+        //      (column chunk of the critical client); each wave a contiguous range of them ----
+        uint32_t mbest = kInf, sbest = kInf;
         unsigned long long kbest = ~0ull;
+        const int sega = min(max(uni(l.gstart[astar]), 0), P) >> 6, segb = min(max(uni(l.gstart[astar + 1]), 0), P) >> 6;
+        if (nfeas > 0)
+            for (int seg = sega + wave; seg < segb; seg += kWaves) mbest = min(mbest, segment_moves(seg, astar));
         {
-            // full scan: a contiguous range per wave; pruned scan: tasks dealt round the waves, those that
-            // do not involve the critical client skipped
-            const int lo = prune ? twave : (int)(((long long)ntask * twave) / kWaves);
-            const int hi = prune ? ntask : (int)(((long long)ntask * (twave + 1)) / kWaves);
-            const int tstep = prune ? kWaves : 1;
-            unsigned long long rec = lo < hi ? l.tasks[lo] : 0ull;
-            for (int t = lo; t < hi; t += tstep) {
-                const uint32_t w0 = uniu((uint32_t)rec), w1 = uniu((uint32_t)(rec >> 32));
-                if (t + tstep < hi) rec = l.tasks[t + tstep];              // next record while this tile runs
-                int rowbase = (int)(w0 & 0x3FFu) << 6, R = (int)((w0 >> 10) & 7u), X = (int)((w0 >> 13) & 0xFFu);
-                int c0 = (int)(w1 & 0x3FFu) << 6, Y = (int)((w1 >> 19) & 0xFFu);
-                int c1 = c0 + (int)((w1 >> 10) & 0x1FFu);
-                if (prune && X != astar && Y != astar) continue;
-                if (X == astar) {                                            // the critical client must be the column side
-                    const int rb = c0, rr = (c1 - c0 + 63) >> 6;
-                    c0 = rowbase; c1 = rowbase + 64 * R;
-                    rowbase = rb; R = rr;
-                    const int q = X; X = Y; Y = q;
-                }
-                if (R < 1 || R > kRMax || c1 <= c0 || c1 > Pmax || rowbase + 64 * R > Pmax) continue;   // cannot happen
-                const uint32_t lx = wload(X), ly = wload(Y);
-                const uint32_t oth = others_max(top, X, Y);
-                const bool star = Y == astar;
-                if (R == 1) run_tile<1>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
-                else if (R == 2) run_tile<2>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
-                else if constexpr (kRMax >= 3) {
-                    if (R == 3) run_tile<3>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
-                    else run_tile<kRMax>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sbest, kbest);
+            const int nU = min(max(uni(l.upre[M]), 0), Umax);
+            const int ua0 = min(max(uni(l.upre[astar]), 0), nU), nua = min(max(uni(l.upre[astar + 1]), 0), nU) - ua0;
+            const int nCh = min(max(ctrl->nchunk, 0), Cmax);
+            const int ca0 = min(max(uni(l.chpre[astar]), 0), nCh), nca = min(max(uni(l.chpre[astar + 1]), 0), nCh) - ca0;
+            const int nstar = (nua >= 0 && nca > 0) ? (nU - nua) * nca : 0;
+            const int lo = (int)(((long long)nstar * twave) / kWaves), hi = (int)(((long long)nstar * (twave + 1)) / kWaves);
+            if (lo < hi) {
+                int uq = lo / nca, cq = lo - uq * nca;
+                for (int k = lo; k < hi; k++) {
+                    const int u = uq < ua0 ? uq : uq + nua;
+                    const uint32_t w0 = uniu(l.uinfo[min(u, Umax - 1)]), w1 = uniu(l.chunks[min(ca0 + cq, Cmax - 1)]);
+                    const int c0 = (int)(w1 & 0x3FFu) << 6;
+                    run((int)(w0 & 0x3FFu) << 6, (int)((w0 >> 10) & 7u), (int)((w0 >> 13) & 0xFFu), c0,
+                        c0 + (int)((w1 >> 10) & 0x1FFu), astar, true, sbest, kbest);
+                    if (++cq == nca) { cq = 0; uq++; }
                 }
             }
         }
@@ -457,44 +467,235 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             if (sbest != kInf) atomicMin(&ctrl->vswap, sbest);
             if (kbest != ~0ull) atomicMin(&ctrl->k0key, kbest);
         }
-        __syncthreads();                                 // B1: all candidate values are in
-        if (wave != 0) continue;                         // selection, apply and the next pass opening: wave 0
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");       // this wave's minima (rowkey included) before its post
+        if (lane == 0) atomicAdd(&ctrl->adone, 1);
 
-        const uint32_t Vm = uniu(ctrl->vmove), Vs = uniu(ctrl->vswap);
-        const uint32_t V = min(Vm, Vs);
-        if (V >= T) {                                    // local optimum (status stays OK)
+        // ---- phase B (wave 0): which candidate; nothing is changed before B2.  Only wave 0 needs
+        //      the values of phase A: it waits for the other waves' contributions on a counter (they
+        //      never wait for wave 0 before they post it) while they go straight on to phase C. ----
+        int act = kActNone;
+        unsigned long long win = ~0ull;
+        uint32_t Vm = kInf, Vs = kInf, V = kInf;
+        if (wave == 0) {
+            int posted = 0;
+            for (int spins = 0; spins < kSpinLimit; spins++) {
+                if (lane == 0) posted = atomicAdd(&ctrl->adone, 0);
+                posted = uni(posted);
+                if (posted >= kWaves) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            Vm = uniu(ctrl->vmove); Vs = uniu(ctrl->vswap);
+            V = min(Vm, Vs);
+            if (posted < kWaves) act = kActError;        // cannot happen: a wave never posted
+        }
+        if (wave == 0) {
+            if (act == kActError) { }
+            else if (V >= T) act = kActStop;                  // local optimum (status stays OK)
+            else if (Vm <= Vs) {
+                unsigned long long best = ~0ull;
+            // ---- a move wins (move ids are below swap ids): lowest id among moves of value V ----
+                for (int seg = 0; seg < nseg; seg++) {
+                    const int g = l.seg_grp[seg];
+                    const int p = seg * 64 + lane;
+                    const uint32_t x = l.cu[p];
+                    const uint32_t ci = (x - kBias) >> 1;
+                    const uint32_t la = load32(g);
+                    const uint32_t jb = l.job[p];
+                    for (int q = 0; q < nfeas; q++) {
+                        const int b = l.feas[q];
+                        if (b == g) continue;
+                        const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
+                        if (x != kPad && v == V) {
+                            const unsigned long long id = (unsigned long long)jb * (unsigned long long)M + (unsigned long long)b;
+                            best = min(best, (id << 32) | (unsigned long long)p);
+                        }
+                    }
+                }
+                win = wave_min_u64(best);
+                act = kActMove;
+            } else {
+                // ---- a swap wins: lowest (min(i,k), max(i,k)) among swaps of value V.  Its other job f is
+                // flagged (rowkey[f] == V).  k0 = the lowest-index flagged job.  Candidates: k0 with its
+                // critical partners, and the critical jobs with a lower index than k0 ("early") with theirs. ----
+                const unsigned long long k0key = ctrl->k0key;
+                if ((uint32_t)(k0key >> 32) != V) act = kActError;      // cannot happen: the best swap is in a critical tile
+                else {
+                const uint32_t k0job = uniu((uint32_t)(k0key >> 16) & 0xFFFFu);
+                const int k0pos = min(uni((int)(k0key & 0xFFFFu)), P - 1);
+                const uint32_t lstar = wload(astar);
+                const int sbase = min(max(uni(l.gstart[astar]), 0), P), scnt = min(max(uni(l.cnt[astar]), 0), P - sbase);
+                const int send = sbase + scnt;
+                unsigned long long best = ~0ull;
+
+                // all critical jobs against the flagged job at pf (uniform): every swap of value V
+                auto pair_with = [&](int pf) {
+                    const int g = uni(l.seg_grp[pf >> 6]);
+                    const uint32_t lg = wload(g), jf = uniu(l.job[pf]);
+                    const uint32_t xf = uniu(l.cu[pf]) - (lg - lstar);
+                    const uint32_t oth = others_max(top, g, astar);
+                    for (int p = sbase + lane; p < send; p += kWave) {
+                        const uint32_t je = l.job[p];
+                        if (swap_value(absdiff_u32(l.cu[p], xf), lg + lstar, oth) == V) {
+                            const unsigned long long lo = je < jf ? ((unsigned long long)je << 48) | ((unsigned long long)jf << 32) |
+                                                                        ((unsigned long long)p << 16) | (unsigned long long)pf
+                                                                  : ((unsigned long long)jf << 48) | ((unsigned long long)je << 32) |
+                                                                        ((unsigned long long)pf << 16) | (unsigned long long)p;
+                            best = min(best, lo);
+                        }
+                    }
+                };
+                pair_with(k0pos);
+
+                // early critical jobs: are there any?
+                int nE = 0;
+                for (int p0 = sbase; p0 < send; p0 += kWave) {
+                    const int p = p0 + lane;
+                    nE += __popcll(__ballot(p < send && (uint32_t)l.job[p] < k0job));
+                }
+                if (nE > 0) {
+                    // Per client g, for a flagged job f of g and a critical job e: the swap has value V
+                    // <=> |cu_e - (cu_f - tdl[g])| < tr1[g]  (tr1 = 0: no swap with g reaches V).
+                    for (int g = lane; g < M; g += kWave) {
+                        const uint32_t lg = load32(g), lsum = lg + lstar;
+                        const bool ok = g != astar && others_max(top, g, astar) <= V && lsum <= 2u * V + 1u;
+                        l.tdl[g] = lg - lstar;
+                        l.tr1[g] = ok ? 2u * V + 2u - lsum : 0u;
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                    const uint4 *cu4 = reinterpret_cast<const uint4 *>(l.cu);
+                    const uint4 *rk4 = reinterpret_cast<const uint4 *>(l.rowkey);
+                    const uint2 *job2 = reinterpret_cast<const uint2 *>(l.job);
+                    // The early jobs are taken in increasing index order, four at a time, each batch against
+                    // every flagged job; the first batch with a partner holds the lowest id (a partner f of an
+                    // early job e is flagged, so job(f) >= job(k0) > job(e)).  If the first batch finds nothing
+                    // and few jobs are flagged, those are paired with all critical jobs instead.
+                    int lastjob = -1, nF = 0, nrec = 0;
+                    int f0 = 0, f1 = 0, f2 = 0, f3 = 0;
+                    for (int round = 0; round * 4 < nE; round++) {
+                        int ne = 0;
+                        uint32_t ecu0 = 0, ecu1 = 0, ecu2 = 0, ecu3 = 0, ejp0 = 0, ejp1 = 0, ejp2 = 0, ejp3 = 0;   // cu, job << 16 | pos
+                        for (int k = 0; k < 4; k++) {
+                            uint32_t m = kInf;
+                            for (int p = sbase + lane; p < send; p += kWave) {
+                                const uint32_t je = l.job[p];
+                                if ((int)je > lastjob && je < k0job) m = min(m, (je << 16) | (uint32_t)p);
+                            }
+                            m = wave_min_u32(m);
+                            if (m == kInf) break;
+                            lastjob = (int)(m >> 16);
+                            ecu3 = ecu2; ecu2 = ecu1; ecu1 = ecu0;
+                            ejp3 = ejp2; ejp2 = ejp1; ejp1 = ejp0;
+                            ejp0 = m;
+                            ecu0 = uniu(l.cu[min((int)(m & 0xFFFFu), P - 1)]);
+                            ne += 1;
+                        }
+                        if (ne == 0) break;
+                        uint32_t b0 = kInf, b1 = kInf, b2 = kInf, b3 = kInf;   // per early job: lowest (job << 16 | pos) partner
+                        for (int q0 = 0; q0 < (P >> 2); q0 += kWave) {
+                            const int q = q0 + lane;                            // positions 4q .. 4q+3 (P % 256 == 0 is not given)
+                            const bool in = q < (P >> 2);
+                            const int g = in ? min((int)l.seg_grp[q >> 4], M - 1) : 0;
+                            const uint4 cc = in ? cu4[q] : make_uint4(kPad, kPad, kPad, kPad);
+                            const uint4 rr = in ? rk4[q] : make_uint4(kInf, kInf, kInf, kInf);
+                            const uint2 jj = in ? job2[q] : uint2{0u, 0u};
+                            const uint32_t dl = l.tdl[g], r1 = l.tr1[g];
+                            const uint32_t pq = (uint32_t)q << 2;
+                            const uint32_t x[4] = {cc.x - dl, cc.y - dl, cc.z - dl, cc.w - dl};
+                            const bool fl[4] = {rr.x == V, rr.y == V, rr.z == V, rr.w == V};
+                            const uint32_t id[4] = {fl[0] ? ((jj.x & 0xFFFFu) << 16) | pq : kInf,
+                                                    fl[1] ? (jj.x & 0xFFFF0000u) | (pq + 1u) : kInf,
+                                                    fl[2] ? ((jj.y & 0xFFFFu) << 16) | (pq + 2u) : kInf,
+                                                    fl[3] ? (jj.y & 0xFFFF0000u) | (pq + 3u) : kInf};
+#pragma unroll
+                            for (int k = 0; k < 4; k++) {
+                                if (round == 0) {                               // count the flagged jobs, keep the first four
+                                    unsigned long long m = __ballot(fl[k]);
+                                    nF += __popcll(m);
+                                    while (m && nrec < 4) {
+                                        const int ln = __builtin_ctzll(m);
+                                        m &= m - 1;
+                                        f3 = f2; f2 = f1; f1 = f0;
+                                        f0 = ((q0 + ln) << 2) + k;
+                                        nrec += 1;
+                                    }
+                                }
+                                b0 = min(b0, absdiff_u32(ecu0, x[k]) < r1 ? id[k] : kInf);
+                                if (ne > 1) b1 = min(b1, absdiff_u32(ecu1, x[k]) < r1 ? id[k] : kInf);
+                                if (ne > 2) b2 = min(b2, absdiff_u32(ecu2, x[k]) < r1 ? id[k] : kInf);
+                                if (ne > 3) b3 = min(b3, absdiff_u32(ecu3, x[k]) < r1 ? id[k] : kInf);
+                            }
+                        }
+                        auto early_pair = [&](uint32_t ejp, uint32_t b) {
+                            if (b != kInf)
+                                best = min(best, ((unsigned long long)(ejp >> 16) << 48) | ((unsigned long long)(b >> 16) << 32) |
+                                                     ((unsigned long long)(ejp & 0xFFFFu) << 16) | (unsigned long long)(b & 0xFFFFu));
+                        };
+                        early_pair(ejp0, b0);
+                        if (ne > 1) early_pair(ejp1, b1);
+                        if (ne > 2) early_pair(ejp2, b2);
+                        if (ne > 3) early_pair(ejp3, b3);
+                        if (__ballot(min(min(b0, b1), min(b2, b3)) != kInf)) break;
+                        if (round == 0 && nF <= 4) {
+                            if (nrec > 0 && f0 != k0pos) pair_with(min(f0, P - 1));
+                            if (nrec > 1 && f1 != k0pos) pair_with(min(f1, P - 1));
+                            if (nrec > 2 && f2 != k0pos) pair_with(min(f2, P - 1));
+                            if (nrec > 3 && f3 != k0pos) pair_with(min(f3, P - 1));
+                            break;
+                        }
+                    }
+                }
+                    win = wave_min_u64(best);
+                    act = kActSwap;
+                }
+            }
+        }
+
+        // ---- phase C: the rest of the scan, dealt from a counter: the swap tiles of the task table
+        //      that do not involve the critical client, then the move segments of the other clients ----
+        if (!prune) {
+            uint32_t rbest = kInf;
+            unsigned long long knone = ~0ull;
+            const int nwork = ntask + (nfeas > 0 ? nseg : 0);
+            for (;;) {
+                int t = 0;
+                if (lane == 0) t = atomicAdd(&ctrl->next, 1);
+                t = uni(t);
+                if (t >= nwork || t < 0) break;
+                if (t < ntask) {
+                    const unsigned long long rec = l.tasks[t];
+                    const uint32_t w0 = uniu((uint32_t)rec), w1 = uniu((uint32_t)(rec >> 32));
+                    const int X = (int)((w0 >> 13) & 0xFFu), Y = (int)((w1 >> 19) & 0xFFu);
+                    if (X == astar || Y == astar) continue;
+                    const int c0 = (int)(w1 & 0x3FFu) << 6;
+                    run((int)(w0 & 0x3FFu) << 6, (int)((w0 >> 10) & 7u), X, c0, c0 + (int)((w1 >> 10) & 0x1FFu), Y, false,
+                        rbest, knone);
+                } else {
+                    const int seg = t - ntask;
+                    const int g = l.seg_grp[seg];
+                    if (g != astar) rbest = min(rbest, segment_moves(seg, g));
+                }
+            }
+            rbest = wave_min_u32(rbest);
+            if (lane == 0 && rbest != kInf) atomicMin(&ctrl->vrest, rbest);
+        }
+        __syncthreads();                                 // B2: the scan is complete
+        if (wave != 0) continue;
+
+        // ---- wave 0: apply, open the next pass ----
+        uint32_t vnew = vload;
+        if (!prune && uniu(ctrl->vrest) < T) act = kActError;       // cannot happen: those candidates keep the critical load
+        if (act == kActStop) {
             if (lane == 0) ctrl->stop = 1;
             continue;
         }
-        if (Vm <= Vs) {
-            // ---- a move wins (move ids are below swap ids): lowest id among moves of value V ----
-            unsigned long long best = ~0ull;
-            for (int seg = 0; seg < nseg; seg++) {
-                const int g = l.seg_grp[seg];
-                const int p = seg * 64 + lane;
-                const uint32_t x = l.cu[p];
-                const uint32_t ci = (x - kBias) >> 1;
-                const uint32_t la = load32(g);
-                const uint32_t jb = l.job[p];
-                for (int q = 0; q < nfeas; q++) {
-                    const int b = l.feas[q];
-                    if (b == g) continue;
-                    const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
-                    if (x != kPad && v == V) {
-                        const unsigned long long id = (unsigned long long)jb * (unsigned long long)M + (unsigned long long)b;
-                        best = min(best, (id << 32) | (unsigned long long)p);
-                    }
-                }
-            }
-            best = wave_min_u64(best);
+        if (act == kActMove) {
+            const unsigned long long best = win;
             const uint32_t id = (uint32_t)(best >> 32);
             const int p = (int)(uint32_t)best;
             const int i = (int)(id / (uint32_t)M), b = (int)(id % (uint32_t)M);
-            uint32_t vnew = vload;
-            if (best == ~0ull || i >= N || p >= P) {
-                w_status = MMBP_ST_INTERNAL;             // cannot happen: the best move was found above
-                w_stop = true;
-            } else {
+            if (best == ~0ull || i >= N || p >= P) act = kActError;    // cannot happen: the best move was found above
+            else {
                 const int a = uni(l.seg_grp[p >> 6]);
                 const uint32_t ci = (uniu(l.cu[p]) - kBias) >> 1;
                 if (SMALLM) {
@@ -510,154 +711,12 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 }
                 w_passes += 1;
             }
-            open_pass(vnew);
-            continue;
-        }
-
-        // ---- a swap wins: lowest (min(i,k), max(i,k)) among swaps of value V.  An improving swap
-        // involves the critical client, and its other job f is flagged (rowkey[f] == V).  k0 = the
-        // lowest-index flagged job.  Candidates: k0 with its critical partners, and the critical
-        // jobs with a lower index than k0 ("early") with theirs. ----
-        const unsigned long long k0key = ctrl->k0key;
-        if ((uint32_t)(k0key >> 32) != V) {              // cannot happen: the best swap is in a critical tile
-            w_status = MMBP_ST_INTERNAL; w_stop = true;
-            open_pass(vload);
-            continue;
-        }
-        const uint32_t k0job = uniu((uint32_t)(k0key >> 16) & 0xFFFFu);
-        const int k0pos = min(uni((int)(k0key & 0xFFFFu)), P - 1);
-        const uint32_t lstar = wload(astar);
-        const int sbase = min(max(uni(l.gstart[astar]), 0), P), scnt = min(max(uni(l.cnt[astar]), 0), P - sbase);
-        const int send = sbase + scnt;
-        unsigned long long best = ~0ull;
-
-        // all critical jobs against the flagged job at pf (uniform): every swap of value V
-        auto pair_with = [&](int pf) {
-            const int g = uni(l.seg_grp[pf >> 6]);
-            const uint32_t lg = wload(g), jf = uniu(l.job[pf]);
-            const uint32_t xf = uniu(l.cu[pf]) - (lg - lstar);
-            const uint32_t oth = others_max(top, g, astar);
-            for (int p = sbase + lane; p < send; p += kWave) {
-                const uint32_t je = l.job[p];
-                if (swap_value(absdiff_u32(l.cu[p], xf), lg + lstar, oth) == V) {
-                    const unsigned long long lo = je < jf ? ((unsigned long long)je << 48) | ((unsigned long long)jf << 32) |
-                                                                ((unsigned long long)p << 16) | (unsigned long long)pf
-                                                          : ((unsigned long long)jf << 48) | ((unsigned long long)je << 32) |
-                                                                ((unsigned long long)pf << 16) | (unsigned long long)p;
-                    best = min(best, lo);
-                }
-            }
-        };
-        pair_with(k0pos);
-
-        // early critical jobs: are there any?
-        int nE = 0;
-        for (int p0 = sbase; p0 < send; p0 += kWave) {
-            const int p = p0 + lane;
-            nE += __popcll(__ballot(p < send && (uint32_t)l.job[p] < k0job));
-        }
-        if (nE > 0) {
-            // Per client g, for a flagged job f of g and a critical job e: the swap has value V
-            // <=> |cu_e - (cu_f - tdl[g])| < tr1[g]  (tr1 = 0: no swap with g reaches V).
-            for (int g = lane; g < M; g += kWave) {
-                const uint32_t lg = load32(g), lsum = lg + lstar;
-                const bool ok = g != astar && others_max(top, g, astar) <= V && lsum <= 2u * V + 1u;
-                l.tdl[g] = lg - lstar;
-                l.tr1[g] = ok ? 2u * V + 2u - lsum : 0u;
-            }
-            __builtin_amdgcn_wave_barrier();
-            const uint4 *cu4 = reinterpret_cast<const uint4 *>(l.cu);
-            const uint4 *rk4 = reinterpret_cast<const uint4 *>(l.rowkey);
-            const uint2 *job2 = reinterpret_cast<const uint2 *>(l.job);
-            // The early jobs are taken in increasing index order, four at a time, each batch against
-            // every flagged job; the first batch with a partner holds the lowest id (a partner f of an
-            // early job e is flagged, so job(f) >= job(k0) > job(e)).  If the first batch finds nothing
-            // and few jobs are flagged, those are paired with all critical jobs instead.
-            int lastjob = -1, nF = 0, nrec = 0;
-            int f0 = 0, f1 = 0, f2 = 0, f3 = 0;
-            for (int round = 0; round * 4 < nE; round++) {
-                int ne = 0;
-                uint32_t ecu0 = 0, ecu1 = 0, ecu2 = 0, ecu3 = 0, ejp0 = 0, ejp1 = 0, ejp2 = 0, ejp3 = 0;   // cu, job << 16 | pos
-                for (int k = 0; k < 4; k++) {
-                    uint32_t m = kInf;
-                    for (int p = sbase + lane; p < send; p += kWave) {
-                        const uint32_t je = l.job[p];
-                        if ((int)je > lastjob && je < k0job) m = min(m, (je << 16) | (uint32_t)p);
-                    }
-                    m = wave_min_u32(m);
-                    if (m == kInf) break;
-                    lastjob = (int)(m >> 16);
-                    ecu3 = ecu2; ecu2 = ecu1; ecu1 = ecu0;
-                    ejp3 = ejp2; ejp2 = ejp1; ejp1 = ejp0;
-                    ejp0 = m;
-                    ecu0 = uniu(l.cu[min((int)(m & 0xFFFFu), P - 1)]);
-                    ne += 1;
-                }
-                if (ne == 0) break;
-                uint32_t b0 = kInf, b1 = kInf, b2 = kInf, b3 = kInf;   // per early job: lowest (job << 16 | pos) partner
-                for (int q0 = 0; q0 < (P >> 2); q0 += kWave) {
-                    const int q = q0 + lane;                            // positions 4q .. 4q+3 (P % 256 == 0 is not given)
-                    const bool in = q < (P >> 2);
-                    const int g = in ? min((int)l.seg_grp[q >> 4], M - 1) : 0;
-                    const uint4 cc = in ? cu4[q] : make_uint4(kPad, kPad, kPad, kPad);
-                    const uint4 rr = in ? rk4[q] : make_uint4(kInf, kInf, kInf, kInf);
-                    const uint2 jj = in ? job2[q] : uint2{0u, 0u};
-                    const uint32_t dl = l.tdl[g], r1 = l.tr1[g];
-                    const uint32_t pq = (uint32_t)q << 2;
-                    const uint32_t x[4] = {cc.x - dl, cc.y - dl, cc.z - dl, cc.w - dl};
-                    const bool fl[4] = {rr.x == V, rr.y == V, rr.z == V, rr.w == V};
-                    const uint32_t id[4] = {fl[0] ? ((jj.x & 0xFFFFu) << 16) | pq : kInf,
-                                            fl[1] ? (jj.x & 0xFFFF0000u) | (pq + 1u) : kInf,
-                                            fl[2] ? ((jj.y & 0xFFFFu) << 16) | (pq + 2u) : kInf,
-                                            fl[3] ? (jj.y & 0xFFFF0000u) | (pq + 3u) : kInf};
-#pragma unroll
-                    for (int k = 0; k < 4; k++) {
-                        if (round == 0) {                               // count the flagged jobs, keep the first four
-                            unsigned long long m = __ballot(fl[k]);
-                            nF += __popcll(m);
-                            while (m && nrec < 4) {
-                                const int ln = __builtin_ctzll(m);
-                                m &= m - 1;
-                                f3 = f2; f2 = f1; f1 = f0;
-                                f0 = ((q0 + ln) << 2) + k;
-                                nrec += 1;
-                            }
-                        }
-                        b0 = min(b0, absdiff_u32(ecu0, x[k]) < r1 ? id[k] : kInf);
-                        if (ne > 1) b1 = min(b1, absdiff_u32(ecu1, x[k]) < r1 ? id[k] : kInf);
-                        if (ne > 2) b2 = min(b2, absdiff_u32(ecu2, x[k]) < r1 ? id[k] : kInf);
-                        if (ne > 3) b3 = min(b3, absdiff_u32(ecu3, x[k]) < r1 ? id[k] : kInf);
-                    }
-                }
-                auto early_pair = [&](uint32_t ejp, uint32_t b) {
-                    if (b != kInf)
-                        best = min(best, ((unsigned long long)(ejp >> 16) << 48) | ((unsigned long long)(b >> 16) << 32) |
-                                             ((unsigned long long)(ejp & 0xFFFFu) << 16) | (unsigned long long)(b & 0xFFFFu));
-                };
-                early_pair(ejp0, b0);
-                if (ne > 1) early_pair(ejp1, b1);
-                if (ne > 2) early_pair(ejp2, b2);
-                if (ne > 3) early_pair(ejp3, b3);
-                if (__ballot(min(min(b0, b1), min(b2, b3)) != kInf)) break;
-                if (round == 0 && nF <= 4) {
-                    if (nrec > 0 && f0 != k0pos) pair_with(min(f0, P - 1));
-                    if (nrec > 1 && f1 != k0pos) pair_with(min(f1, P - 1));
-                    if (nrec > 2 && f2 != k0pos) pair_with(min(f2, P - 1));
-                    if (nrec > 3 && f3 != k0pos) pair_with(min(f3, P - 1));
-                    break;
-                }
-            }
-        }
-        best = wave_min_u64(best);
-        {
-            const unsigned long long pr = best;
+        } else if (act == kActSwap) {
+            const unsigned long long pr = win;
             const uint32_t ji = (uint32_t)(pr >> 48), jk = (uint32_t)(pr >> 32) & 0xFFFFu;     // ji < jk
             const int pi = (int)((pr >> 16) & 0xFFFFu), pk = (int)(pr & 0xFFFFu);
-            uint32_t vnew = vload;
-            if (pr == ~0ull || ji >= (uint32_t)N || jk >= (uint32_t)N || pi >= P || pk >= P) {
-                w_status = MMBP_ST_INTERNAL;             // cannot happen: the best swap was found above
-                w_stop = true;
-            } else {
+            if (pr == ~0ull || ji >= (uint32_t)N || jk >= (uint32_t)N || pi >= P || pk >= P) act = kActError;   // cannot happen
+            else {
                 const int ga = uni(l.seg_grp[pi >> 6]), gb = uni(l.seg_grp[pk >> 6]);
                 const uint32_t xi = uniu(l.cu[pi]), xk = uniu(l.cu[pk]);
                 const uint32_t d = ((xi - kBias) >> 1) - ((xk - kBias) >> 1);     // modulo 2^32; the loads stay in range
@@ -676,8 +735,9 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 }
                 w_passes += 1;
             }
-            open_pass(vnew);
         }
+        if (act == kActError || act == kActNone) { w_status = MMBP_ST_INTERNAL; w_stop = true; }
+        open_pass(vnew);
     }
 
     // ---------------- write back ----------------
