@@ -150,24 +150,22 @@ __device__ inline Lds carve(unsigned char *base, int N, int M)
     return l;
 }
 
-// three largest loads with their clients for M <= 64 (one load per lane): every lane ranks its
-// load against all others (ties: lower client first), the lanes of rank 0, 1, 2 are read back
+// three largest loads with their clients for M <= 64 (one load per lane): three wave maxima, each
+// taking the lowest client among equal loads and leaving it out of the next
 __device__ __forceinline__ Top3 wave_top3_small(uint32_t vload, int M, int lane)
 {
-    int rank = 0;
-    for (int i = 0; i < M; i++) {
-        const uint32_t li = (uint32_t)__builtin_amdgcn_readlane((int)vload, i);
-        rank += (li > vload || (li == vload && i < lane)) ? 1 : 0;
-    }
-    auto ranked = [&](int r, uint32_t &v, int &jout) {
-        const unsigned long long m = __ballot(lane < M && rank == r);
+    bool in = lane < M;
+    auto next = [&](uint32_t &v, int &jout) {
+        const uint32_t mx = wave_max_u32(in ? vload : 0u);
+        const unsigned long long m = __ballot(in && vload == mx);
         jout = m ? (int)__builtin_ctzll(m) : -1;
-        v = m ? (uint32_t)__builtin_amdgcn_readlane((int)vload, jout & 63) : 0u;
+        v = m ? mx : 0u;
+        if (lane == jout) in = false;
     };
     Top3 t;
-    ranked(0, t.v0, t.j0);
-    ranked(1, t.v1, t.j1);
-    ranked(2, t.v2, t.j2);
+    next(t.v0, t.j0);
+    next(t.v1, t.j1);
+    next(t.v2, t.j2);
     return t;
 }
 
@@ -355,7 +353,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     // Opens a pass (wave 0 only, all 64 lanes): accounting, the three largest loads for everybody,
     // the per-pass minima and the row minima back to "none".  vnew: lane j holds the load of
     // client j (SMALLM only; otherwise the loads are read back from LDS).
-    auto open_pass = [&](uint32_t vnew) {
+    auto open_pass = [&](uint32_t vnew, bool reset_rows) {
         w_iters += 1;
         if ((long long)w_iters > (long long)max_passes + 1) { w_status = MMBP_ST_INTERNAL; w_stop = true; }
         else if (w_stop) { }
@@ -369,11 +367,13 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             ctrl->next = 0; ctrl->adone = 0;
             if (w_stop) ctrl->stop = 1;
         }
-        const int P = min(ctrl->P, Pmax) & ~63;
-        uint4 *rk = reinterpret_cast<uint4 *>(l.rowkey);
-        for (int q = lane; q < (P >> 2); q += kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
+        if (reset_rows) {
+            const int P = min(ctrl->P, Pmax) & ~63;
+            uint4 *rk = reinterpret_cast<uint4 *>(l.rowkey);
+            for (int q = lane; q < (P >> 2); q += kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
+        }
     };
-    if (wave == 0) open_pass(SMALLM ? (lane < M ? load32(lane) : 0u) : 0u);   // (build_layout ended with a barrier)
+    if (wave == 0) open_pass(SMALLM ? (lane < M ? load32(lane) : 0u) : 0u, true);   // (build_layout ended with a barrier)
 
     // ---------------- pass loop ----------------
     // A pass has three phases.  A: the candidates that can lower the makespan (they take load off
@@ -662,14 +662,15 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 if (lane == 0) t = atomicAdd(&ctrl->next, 1);
                 t = uni(t);
                 if (t >= nwork || t < 0) break;
+                const unsigned long long rec = t < ntask ? l.tasks[t] : 0ull;
                 if (t < ntask) {
-                    const unsigned long long rec = l.tasks[t];
                     const uint32_t w0 = uniu((uint32_t)rec), w1 = uniu((uint32_t)(rec >> 32));
                     const int X = (int)((w0 >> 13) & 0xFFu), Y = (int)((w1 >> 19) & 0xFFu);
-                    if (X == astar || Y == astar) continue;
-                    const int c0 = (int)(w1 & 0x3FFu) << 6;
-                    run((int)(w0 & 0x3FFu) << 6, (int)((w0 >> 10) & 7u), X, c0, c0 + (int)((w1 >> 10) & 0x1FFu), Y, false,
-                        rbest, knone);
+                    if (X != astar && Y != astar) {
+                        const int c0 = (int)(w1 & 0x3FFu) << 6;
+                        run((int)(w0 & 0x3FFu) << 6, (int)((w0 >> 10) & 7u), X, c0, c0 + (int)((w1 >> 10) & 0x1FFu), Y, false,
+                            rbest, knone);
+                    }
                 } else {
                     const int seg = t - ntask;
                     const int g = l.seg_grp[seg];
@@ -680,7 +681,11 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             if (lane == 0 && rbest != kInf) atomicMin(&ctrl->vrest, rbest);
         }
         __syncthreads();                                 // B2: the scan is complete
-        if (wave != 0) continue;
+        if (wave != 0) {                                 // the waves that now wait put the row minima back to "none"
+            uint4 *rk = reinterpret_cast<uint4 *>(l.rowkey);
+            for (int q = tid - kWave; q < (P >> 2); q += BLOCK - kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
+            continue;
+        }
 
         // ---- wave 0: apply, open the next pass ----
         uint32_t vnew = vload;
@@ -737,7 +742,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             }
         }
         if (act == kActError || act == kActNone) { w_status = MMBP_ST_INTERNAL; w_stop = true; }
-        open_pass(vnew);
+        open_pass(vnew, false);
     }
 
     // ---------------- write back ----------------
