@@ -651,6 +651,25 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             }
         }
 
+        // what the apply step will need, read while nothing has changed (wave 0)
+        int ap_g0 = 0, ap_g1 = 0, ap_j0 = 0, ap_j1 = 0;
+        uint32_t ap_x0 = 0, ap_x1 = 0;
+        if (act == kActMove) {
+            const uint32_t id = (uint32_t)(win >> 32);
+            const int p = (int)(uint32_t)win;
+            ap_j0 = (int)(id / (uint32_t)M); ap_g1 = (int)(id % (uint32_t)M);
+            if (win == ~0ull || ap_j0 >= N || p >= P) act = kActError;       // cannot happen: the best move was found above
+            else { ap_g0 = uni(l.seg_grp[p >> 6]); ap_x0 = (uniu(l.cu[p]) - kBias) >> 1; }
+        } else if (act == kActSwap) {
+            ap_j0 = (int)(uint32_t)(win >> 48); ap_j1 = (int)((uint32_t)(win >> 32) & 0xFFFFu);                  // j0 < j1
+            const int pi = (int)((win >> 16) & 0xFFFFu), pk = (int)(win & 0xFFFFu);
+            if (win == ~0ull || ap_j0 >= N || ap_j1 >= N || pi >= P || pk >= P) act = kActError;               // cannot happen
+            else {
+                ap_g0 = uni(l.seg_grp[pi >> 6]); ap_g1 = uni(l.seg_grp[pk >> 6]);
+                ap_x0 = uniu(l.cu[pi]); ap_x1 = uniu(l.cu[pk]);
+            }
+        }
+
         // ---- phase C: the rest of the scan, dealt from a counter: the swap tiles of the task table
         //      that do not involve the critical client, then the move segments of the other clients ----
         if (!prune) {
@@ -687,7 +706,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             continue;
         }
 
-        // ---- wave 0: apply, open the next pass ----
+        // ---- wave 0: apply (its operands were read before the barrier), open the next pass ----
         uint32_t vnew = vload;
         if (!prune && uniu(ctrl->vrest) < T) act = kActError;       // cannot happen: those candidates keep the critical load
         if (act == kActStop) {
@@ -695,51 +714,40 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             continue;
         }
         if (act == kActMove) {
-            const unsigned long long best = win;
-            const uint32_t id = (uint32_t)(best >> 32);
-            const int p = (int)(uint32_t)best;
-            const int i = (int)(id / (uint32_t)M), b = (int)(id % (uint32_t)M);
-            if (best == ~0ull || i >= N || p >= P) act = kActError;    // cannot happen: the best move was found above
-            else {
-                const int a = uni(l.seg_grp[p >> 6]);
-                const uint32_t ci = (uniu(l.cu[p]) - kBias) >> 1;
-                if (SMALLM) {
-                    vnew = vload - (lane == a ? ci : 0u) + (lane == b ? ci : 0u);
-                    if (lane == a || lane == b) l.load[lane] = (long long)vnew;
-                }
-                if (lane == 0) {
-                    if (!SMALLM) { l.load[a] -= (long long)ci; l.load[b] += (long long)ci; }
-                    l.cnt[a] -= 1; l.cnt[b] += 1;
-                    asg[i] = b;
-                    if (applied_log) applied_log[(size_t)s * max_passes + w_passes] = (uint64_t)id;
-                    ctrl->rebuild = 1;
-                }
-                w_passes += 1;
+            const uint32_t ci = ap_x0;
+            const int a = ap_g0, b = ap_g1, i = ap_j0;
+            if (SMALLM) {
+                vnew = vload - (lane == a ? ci : 0u) + (lane == b ? ci : 0u);
+                if (lane == a || lane == b) l.load[lane] = (long long)vnew;
             }
+            if (lane == 0) {
+                if (!SMALLM) { l.load[a] -= (long long)ci; l.load[b] += (long long)ci; }
+                l.cnt[a] -= 1; l.cnt[b] += 1;
+                asg[i] = b;
+                if (applied_log) applied_log[(size_t)s * max_passes + w_passes] = (uint64_t)(uint32_t)(win >> 32);
+                ctrl->rebuild = 1;
+            }
+            w_passes += 1;
         } else if (act == kActSwap) {
-            const unsigned long long pr = win;
-            const uint32_t ji = (uint32_t)(pr >> 48), jk = (uint32_t)(pr >> 32) & 0xFFFFu;     // ji < jk
-            const int pi = (int)((pr >> 16) & 0xFFFFu), pk = (int)(pr & 0xFFFFu);
-            if (pr == ~0ull || ji >= (uint32_t)N || jk >= (uint32_t)N || pi >= P || pk >= P) act = kActError;   // cannot happen
-            else {
-                const int ga = uni(l.seg_grp[pi >> 6]), gb = uni(l.seg_grp[pk >> 6]);
-                const uint32_t xi = uniu(l.cu[pi]), xk = uniu(l.cu[pk]);
-                const uint32_t d = ((xi - kBias) >> 1) - ((xk - kBias) >> 1);     // modulo 2^32; the loads stay in range
-                if (SMALLM) {
-                    vnew = vload - (lane == ga ? d : 0u) + (lane == gb ? d : 0u);
-                    if (lane == ga || lane == gb) l.load[lane] = (long long)vnew;
-                }
-                if (lane == 0) {
-                    if (!SMALLM) { l.load[ga] -= (long long)(int32_t)d; l.load[gb] += (long long)(int32_t)d; }
-                    l.cu[pi] = xk; l.cu[pk] = xi;
-                    l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
-                    asg[ji] = gb; asg[jk] = ga;
-                    if (applied_log)
-                        applied_log[(size_t)s * max_passes + w_passes] =
-                            (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
-                }
-                w_passes += 1;
+            const int ga = ap_g0, gb = ap_g1;
+            const uint32_t xi = ap_x0, xk = ap_x1;
+            const uint32_t ji = (uint32_t)ap_j0, jk = (uint32_t)ap_j1;
+            const int pi = (int)((win >> 16) & 0xFFFFu), pk = (int)(win & 0xFFFFu);
+            const uint32_t d = ((xi - kBias) >> 1) - ((xk - kBias) >> 1);     // modulo 2^32; the loads stay in range
+            if (SMALLM) {
+                vnew = vload - (lane == ga ? d : 0u) + (lane == gb ? d : 0u);
+                if (lane == ga || lane == gb) l.load[lane] = (long long)vnew;
             }
+            if (lane == 0) {
+                if (!SMALLM) { l.load[ga] -= (long long)(int32_t)d; l.load[gb] += (long long)(int32_t)d; }
+                l.cu[pi] = xk; l.cu[pk] = xi;
+                l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
+                asg[ji] = gb; asg[jk] = ga;
+                if (applied_log)
+                    applied_log[(size_t)s * max_passes + w_passes] =
+                        (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
+            }
+            w_passes += 1;
         }
         if (act == kActError || act == kActNone) { w_status = MMBP_ST_INTERNAL; w_stop = true; }
         open_pass(vnew, false);
