@@ -17,20 +17,28 @@
 // costs one v_sub_u32 plus half a v_min3_u32 and half a v_max3_u32, all full-rate VALU
 // (v_sad_u32 would fuse them but issues at quarter rate).
 //
-// Tasks.  Every unordered client pair is evaluated once.  A table built with the layout lists the
-// tasks (row unit of client g: up to 4 segments of 64 rows) x (chunk of up to kChunk columns of a
-// client b > g); each wave takes a contiguous range of it, so a pass costs a wave two readlanes and
-// one LDS record per task.  The client with the largest load ("critical") must be the column
-// side (the per-row minima against it resolve the tie-break, below): a task whose row client is
-// critical is run transposed (the chunk's positions become the rows, the unit's the columns).
+// Tasks.  Every unordered client pair is evaluated once per pass.  A table built with the layout
+// lists the tasks (row unit of client g: up to 4 segments of 64 rows) x (chunk of up to kChunk
+// columns of a client b > g), and per row unit / column chunk there is a record of its own.
 //
-// Exact lowest-id tie-break without a second full scan.  An improving swap involves the critical
-// client.  Phase 1 min-combines, per non-critical job, its best makespan against the critical
-// client (rowkey) and tracks the smallest (makespan, job) of those.  After the barrier wave 0 knows
-// the best value V and k0 = the lowest-index non-critical job of a best swap; only critical jobs
-// with a lower index than k0 can carry a lower id: if there are any, they are paired with the
-// flagged jobs (rowkey == V); k0's own partners are scanned; the packed minimum (i, k, pos_i,
-// pos_k) is applied.  Moves are value-only in phase 1 and rescanned for the id when a move wins.
+// A pass has three phases.  The makespan can only fall if load leaves the client with the largest
+// load ("critical"), so phase A evaluates what involves it: its moves, and its swap tiles, always
+// (row unit of another client) x (column chunk of the critical client), a contiguous range per
+// wave.  Wave 0 waits for the other waves' minima on a counter and selects the candidate while all
+// waves (wave 0 too, when it is done) evaluate the rest of the scan in phase C: the tasks of the
+// table that do not involve the critical client and the moves of the other clients, dealt out one
+// at a time from an LDS counter.  Those candidates keep the critical load, so their makespan is at
+// least the current one and cannot change the decision; their minimum is kept and checked against
+// that bound.  Nothing is changed before the barrier that ends phase C; then wave 0 applies the
+// candidate and opens the next pass while the other waves put the row minima back.
+//
+// Exact lowest-id tie-break without a second full scan.  Phase A min-combines, per non-critical
+// job, its best makespan against the critical client (rowkey) and tracks the smallest (makespan,
+// job) of those.  Wave 0 then knows the best value V and k0 = the lowest-index non-critical job of a
+// best swap; only critical jobs with a lower index than k0 ("early") can carry a lower id: they are
+// taken in index order, four at a time, against the flagged jobs (rowkey == V); k0's own partners
+// are scanned; the packed minimum (i, k, pos_i, pos_k) is applied.  Moves are value-only in phase A
+// and rescanned for the id when a move wins.
 //
 // Exactness: all loads stay at or below the initial makespan T0; with T0 + 2*max T_i < 2^29 every
 // quantity above is exact in 32 bits: x lies in (2^29, 3*2^29), a real |y - x| is below 2^29, a
@@ -39,8 +47,10 @@
 // that do not satisfy the bound stay pending for the 64-bit kernel.
 //
 // Termination by construction: every loop of a pass is bounded by N, M and the padded size, every
-// barrier is reached under conditions read from LDS after a barrier, the pass loop is capped, and
-// states that cannot occur stop the scenario with MMBP_ST_INTERNAL instead of being acted on.
+// barrier is reached under conditions read from LDS after a barrier, the pass loop is capped, the
+// one in-workgroup wait (wave 0 on the other waves' posts, which never depend on wave 0) has a spin
+// limit, and states that cannot occur stop the scenario with MMBP_ST_INTERNAL instead of being
+// acted on.
 #include "mmbp_dev.hpp"
 #include "ls_tile.hpp"
 
