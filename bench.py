@@ -21,6 +21,10 @@ sys.path.insert(0, ROOT)
 ALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9      # 256 CUs x 64 int32 lanes/clk x 2.4 GHz
 OPS_PER_SWAP, OPS_PER_MOVE = 5, 3
 ISSUED_PER_SWAP = 2                       # v_sub_u32 + half a v_min3_u32 + half a v_max3_u32
+# HBM bytes of one ls_lds_kernel launch on this workload, from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+# (factors from a 256 MiB device copy; profiles/ls_lds_kernel_c2_counters.md).  To be taken again, or
+# set to None, whenever the kernel changes.
+LS_LDS_HBM_BYTES_PER_LAUNCH = (4344 * 2.0 + 706 * 1.0) * 1024
 
 
 def main():
@@ -29,7 +33,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-sim", action="store_true")
+    ap.add_argument("--no-sim", action="store_true", help="skip the simulator and hybrid-pipeline legs")
+    ap.add_argument("--no-pruned", action="store_true", help="skip the pruned-scan leg")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 256 MiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -111,28 +116,30 @@ def main():
                    "S": S, "N": N, "M": M, "cap": c.cap, "max_passes": c.max_passes,
                    "mean_passes": float(passes_np.mean()), "candidates_per_step": total_evals},
         "roofline": {"bound": "alu", "achieved": achieved / 1e12, "peak": ALU_PEAK_LANE_OPS / 1e12,
-                     "unit": "Tops/s (int32 lane-ops; 5 per swap, 3 per move candidate)",
-                     "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": None,
+                     "unit": "Tops/s (int32 lane-ops priced at 5 per swap and 3 per move candidate; the kernel issues 2 per "
+                             "swap candidate, see frac_issued)",
+                     "frac": achieved / ALU_PEAK_LANE_OPS, "traffic": LS_LDS_HBM_BYTES_PER_LAUNCH,
                      "kernel": "ls_lds_kernel (the mmbp_local_search launch)", "kernel_ms": ls_avg_s * 1e3,
                      "frac_issued": swap_evals * ISSUED_PER_SWAP / ls_avg_s / ALU_PEAK_LANE_OPS},
     }
 
     # the same search with the pruned scan (identical results): reported on its own, never mixed
     # into `value` or the roofline, which count evaluated candidates only
-    pr_assign = [assign0.clone() for _ in range(K)]
-    api.mmbp_local_search_pruned(cost, M, c.cap, c.max_passes, assign0.clone(), load, mk, passes, status,
-                                 evals_out=evals, workspace=ws)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(K):
-        api.mmbp_local_search_pruned(cost, M, c.cap, c.max_passes, pr_assign[k], load, mk, passes, status,
-                                     evals_out=evals, workspace=ws)
-    torch.cuda.synchronize()
-    pr_s = (time.perf_counter() - t0) / K
-    out["pruned_scan"] = {"entry": "mmbp_local_search_pruned", "ms_per_call": pr_s * 1e3,
-                          "passes_per_s": float(passes_np.sum()) / pr_s,
-                          "full_scan_equivalent_candidates_per_s": total_evals / pr_s,
-                          "same_result_as_full_scan": bool(torch.equal(pr_assign[K - 1], assigns[Wm + K - 1]))}
+    if not args.no_pruned:
+      pr_assign = [assign0.clone() for _ in range(K)]
+      api.mmbp_local_search_pruned(cost, M, c.cap, c.max_passes, assign0.clone(), load, mk, passes, status,
+                                   evals_out=evals, workspace=ws)
+      torch.cuda.synchronize()
+      t0 = time.perf_counter()
+      for k in range(K):
+          api.mmbp_local_search_pruned(cost, M, c.cap, c.max_passes, pr_assign[k], load, mk, passes, status,
+                                       evals_out=evals, workspace=ws)
+      torch.cuda.synchronize()
+      pr_s = (time.perf_counter() - t0) / K
+      out["pruned_scan"] = {"entry": "mmbp_local_search_pruned", "ms_per_call": pr_s * 1e3,
+                            "passes_per_s": float(passes_np.sum()) / pr_s,
+                            "full_scan_equivalent_candidates_per_s": total_evals / pr_s,
+                            "same_result_as_full_scan": bool(torch.equal(pr_assign[K - 1], assigns[Wm + K - 1]))}
 
     if not args.no_sim:
         w = W.config5()
