@@ -503,8 +503,8 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             if (act == kActError) { }
             else if (V >= T) act = kActStop;                  // local optimum (status stays OK)
             else if (Vm <= Vs) {
+                // ---- a move wins (move ids are below swap ids): lowest id among moves of value V ----
                 unsigned long long best = ~0ull;
-            // ---- a move wins (move ids are below swap ids): lowest id among moves of value V ----
                 for (int seg = 0; seg < nseg; seg++) {
                     const int g = l.seg_grp[seg];
                     const int p = seg * 64 + lane;
@@ -531,130 +531,130 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 const unsigned long long k0key = ctrl->k0key;
                 if ((uint32_t)(k0key >> 32) != V) act = kActError;      // cannot happen: the best swap is in a critical tile
                 else {
-                const uint32_t k0job = uniu((uint32_t)(k0key >> 16) & 0xFFFFu);
-                const int k0pos = min(uni((int)(k0key & 0xFFFFu)), P - 1);
-                const uint32_t lstar = wload(astar);
-                const int sbase = min(max(uni(l.gstart[astar]), 0), P), scnt = min(max(uni(l.cnt[astar]), 0), P - sbase);
-                const int send = sbase + scnt;
-                unsigned long long best = ~0ull;
+                    const uint32_t k0job = uniu((uint32_t)(k0key >> 16) & 0xFFFFu);
+                    const int k0pos = min(uni((int)(k0key & 0xFFFFu)), P - 1);
+                    const uint32_t lstar = wload(astar);
+                    const int sbase = min(max(uni(l.gstart[astar]), 0), P), scnt = min(max(uni(l.cnt[astar]), 0), P - sbase);
+                    const int send = sbase + scnt;
+                    unsigned long long best = ~0ull;
 
-                // all critical jobs against the flagged job at pf (uniform): every swap of value V
-                auto pair_with = [&](int pf) {
-                    const int g = uni(l.seg_grp[pf >> 6]);
-                    const uint32_t lg = wload(g), jf = uniu(l.job[pf]);
-                    const uint32_t xf = uniu(l.cu[pf]) - (lg - lstar);
-                    const uint32_t oth = others_max(top, g, astar);
-                    for (int p = sbase + lane; p < send; p += kWave) {
-                        const uint32_t je = l.job[p];
-                        if (swap_value(absdiff_u32(l.cu[p], xf), lg + lstar, oth) == V) {
-                            const unsigned long long lo = je < jf ? ((unsigned long long)je << 48) | ((unsigned long long)jf << 32) |
-                                                                        ((unsigned long long)p << 16) | (unsigned long long)pf
-                                                                  : ((unsigned long long)jf << 48) | ((unsigned long long)je << 32) |
-                                                                        ((unsigned long long)pf << 16) | (unsigned long long)p;
-                            best = min(best, lo);
-                        }
-                    }
-                };
-                pair_with(k0pos);
-
-                // early critical jobs: are there any?
-                int nE = 0;
-                for (int p0 = sbase; p0 < send; p0 += kWave) {
-                    const int p = p0 + lane;
-                    nE += __popcll(__ballot(p < send && (uint32_t)l.job[p] < k0job));
-                }
-                if (nE > 0) {
-                    // Per client g, for a flagged job f of g and a critical job e: the swap has value V
-                    // <=> |cu_e - (cu_f - tdl[g])| < tr1[g]  (tr1 = 0: no swap with g reaches V).
-                    for (int g = lane; g < M; g += kWave) {
-                        const uint32_t lg = load32(g), lsum = lg + lstar;
-                        const bool ok = g != astar && others_max(top, g, astar) <= V && lsum <= 2u * V + 1u;
-                        l.tdl[g] = lg - lstar;
-                        l.tr1[g] = ok ? 2u * V + 2u - lsum : 0u;
-                    }
-                    __builtin_amdgcn_wave_barrier();
-                    const uint4 *cu4 = reinterpret_cast<const uint4 *>(l.cu);
-                    const uint4 *rk4 = reinterpret_cast<const uint4 *>(l.rowkey);
-                    const uint2 *job2 = reinterpret_cast<const uint2 *>(l.job);
-                    // The early jobs are taken in increasing index order, four at a time, each batch against
-                    // every flagged job; the first batch with a partner holds the lowest id (a partner f of an
-                    // early job e is flagged, so job(f) >= job(k0) > job(e)).  If the first batch finds nothing
-                    // and few jobs are flagged, those are paired with all critical jobs instead.
-                    int lastjob = -1, nF = 0, nrec = 0;
-                    int f0 = 0, f1 = 0, f2 = 0, f3 = 0;
-                    for (int round = 0; round * 4 < nE; round++) {
-                        int ne = 0;
-                        uint32_t ecu0 = 0, ecu1 = 0, ecu2 = 0, ecu3 = 0, ejp0 = 0, ejp1 = 0, ejp2 = 0, ejp3 = 0;   // cu, job << 16 | pos
-                        for (int k = 0; k < 4; k++) {
-                            uint32_t m = kInf;
-                            for (int p = sbase + lane; p < send; p += kWave) {
-                                const uint32_t je = l.job[p];
-                                if ((int)je > lastjob && je < k0job) m = min(m, (je << 16) | (uint32_t)p);
+                    // all critical jobs against the flagged job at pf (uniform): every swap of value V
+                    auto pair_with = [&](int pf) {
+                        const int g = uni(l.seg_grp[pf >> 6]);
+                        const uint32_t lg = wload(g), jf = uniu(l.job[pf]);
+                        const uint32_t xf = uniu(l.cu[pf]) - (lg - lstar);
+                        const uint32_t oth = others_max(top, g, astar);
+                        for (int p = sbase + lane; p < send; p += kWave) {
+                            const uint32_t je = l.job[p];
+                            if (swap_value(absdiff_u32(l.cu[p], xf), lg + lstar, oth) == V) {
+                                const unsigned long long lo = je < jf ? ((unsigned long long)je << 48) | ((unsigned long long)jf << 32) |
+                                                                            ((unsigned long long)p << 16) | (unsigned long long)pf
+                                                                      : ((unsigned long long)jf << 48) | ((unsigned long long)je << 32) |
+                                                                            ((unsigned long long)pf << 16) | (unsigned long long)p;
+                                best = min(best, lo);
                             }
-                            m = wave_min_u32(m);
-                            if (m == kInf) break;
-                            lastjob = (int)(m >> 16);
-                            ecu3 = ecu2; ecu2 = ecu1; ecu1 = ecu0;
-                            ejp3 = ejp2; ejp2 = ejp1; ejp1 = ejp0;
-                            ejp0 = m;
-                            ecu0 = uniu(l.cu[min((int)(m & 0xFFFFu), P - 1)]);
-                            ne += 1;
                         }
-                        if (ne == 0) break;
-                        uint32_t b0 = kInf, b1 = kInf, b2 = kInf, b3 = kInf;   // per early job: lowest (job << 16 | pos) partner
-                        for (int q0 = 0; q0 < (P >> 2); q0 += kWave) {
-                            const int q = q0 + lane;                            // positions 4q .. 4q+3 (P % 256 == 0 is not given)
-                            const bool in = q < (P >> 2);
-                            const int g = in ? min((int)l.seg_grp[q >> 4], M - 1) : 0;
-                            const uint4 cc = in ? cu4[q] : make_uint4(kPad, kPad, kPad, kPad);
-                            const uint4 rr = in ? rk4[q] : make_uint4(kInf, kInf, kInf, kInf);
-                            const uint2 jj = in ? job2[q] : uint2{0u, 0u};
-                            const uint32_t dl = l.tdl[g], r1 = l.tr1[g];
-                            const uint32_t pq = (uint32_t)q << 2;
-                            const uint32_t x[4] = {cc.x - dl, cc.y - dl, cc.z - dl, cc.w - dl};
-                            const bool fl[4] = {rr.x == V, rr.y == V, rr.z == V, rr.w == V};
-                            const uint32_t id[4] = {fl[0] ? ((jj.x & 0xFFFFu) << 16) | pq : kInf,
-                                                    fl[1] ? (jj.x & 0xFFFF0000u) | (pq + 1u) : kInf,
-                                                    fl[2] ? ((jj.y & 0xFFFFu) << 16) | (pq + 2u) : kInf,
-                                                    fl[3] ? (jj.y & 0xFFFF0000u) | (pq + 3u) : kInf};
-#pragma unroll
+                    };
+                    pair_with(k0pos);
+
+                    // early critical jobs: are there any?
+                    int nE = 0;
+                    for (int p0 = sbase; p0 < send; p0 += kWave) {
+                        const int p = p0 + lane;
+                        nE += __popcll(__ballot(p < send && (uint32_t)l.job[p] < k0job));
+                    }
+                    if (nE > 0) {
+                        // Per client g, for a flagged job f of g and a critical job e: the swap has value V
+                        // <=> |cu_e - (cu_f - tdl[g])| < tr1[g]  (tr1 = 0: no swap with g reaches V).
+                        for (int g = lane; g < M; g += kWave) {
+                            const uint32_t lg = load32(g), lsum = lg + lstar;
+                            const bool ok = g != astar && others_max(top, g, astar) <= V && lsum <= 2u * V + 1u;
+                            l.tdl[g] = lg - lstar;
+                            l.tr1[g] = ok ? 2u * V + 2u - lsum : 0u;
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                        const uint4 *cu4 = reinterpret_cast<const uint4 *>(l.cu);
+                        const uint4 *rk4 = reinterpret_cast<const uint4 *>(l.rowkey);
+                        const uint2 *job2 = reinterpret_cast<const uint2 *>(l.job);
+                        // The early jobs are taken in increasing index order, four at a time, each batch against
+                        // every flagged job; the first batch with a partner holds the lowest id (a partner f of an
+                        // early job e is flagged, so job(f) >= job(k0) > job(e)).  If the first batch finds nothing
+                        // and few jobs are flagged, those are paired with all critical jobs instead.
+                        int lastjob = -1, nF = 0, nrec = 0;
+                        int f0 = 0, f1 = 0, f2 = 0, f3 = 0;
+                        for (int round = 0; round * 4 < nE; round++) {
+                            int ne = 0;
+                            uint32_t ecu0 = 0, ecu1 = 0, ecu2 = 0, ecu3 = 0, ejp0 = 0, ejp1 = 0, ejp2 = 0, ejp3 = 0;   // cu, job << 16 | pos
                             for (int k = 0; k < 4; k++) {
-                                if (round == 0) {                               // count the flagged jobs, keep the first four
-                                    unsigned long long m = __ballot(fl[k]);
-                                    nF += __popcll(m);
-                                    while (m && nrec < 4) {
-                                        const int ln = __builtin_ctzll(m);
-                                        m &= m - 1;
-                                        f3 = f2; f2 = f1; f1 = f0;
-                                        f0 = ((q0 + ln) << 2) + k;
-                                        nrec += 1;
-                                    }
+                                uint32_t m = kInf;
+                                for (int p = sbase + lane; p < send; p += kWave) {
+                                    const uint32_t je = l.job[p];
+                                    if ((int)je > lastjob && je < k0job) m = min(m, (je << 16) | (uint32_t)p);
                                 }
-                                b0 = min(b0, absdiff_u32(ecu0, x[k]) < r1 ? id[k] : kInf);
-                                if (ne > 1) b1 = min(b1, absdiff_u32(ecu1, x[k]) < r1 ? id[k] : kInf);
-                                if (ne > 2) b2 = min(b2, absdiff_u32(ecu2, x[k]) < r1 ? id[k] : kInf);
-                                if (ne > 3) b3 = min(b3, absdiff_u32(ecu3, x[k]) < r1 ? id[k] : kInf);
+                                m = wave_min_u32(m);
+                                if (m == kInf) break;
+                                lastjob = (int)(m >> 16);
+                                ecu3 = ecu2; ecu2 = ecu1; ecu1 = ecu0;
+                                ejp3 = ejp2; ejp2 = ejp1; ejp1 = ejp0;
+                                ejp0 = m;
+                                ecu0 = uniu(l.cu[min((int)(m & 0xFFFFu), P - 1)]);
+                                ne += 1;
+                            }
+                            if (ne == 0) break;
+                            uint32_t b0 = kInf, b1 = kInf, b2 = kInf, b3 = kInf;   // per early job: lowest (job << 16 | pos) partner
+                            for (int q0 = 0; q0 < (P >> 2); q0 += kWave) {
+                                const int q = q0 + lane;                            // positions 4q .. 4q+3 (P % 256 == 0 is not given)
+                                const bool in = q < (P >> 2);
+                                const int g = in ? min((int)l.seg_grp[q >> 4], M - 1) : 0;
+                                const uint4 cc = in ? cu4[q] : make_uint4(kPad, kPad, kPad, kPad);
+                                const uint4 rr = in ? rk4[q] : make_uint4(kInf, kInf, kInf, kInf);
+                                const uint2 jj = in ? job2[q] : uint2{0u, 0u};
+                                const uint32_t dl = l.tdl[g], r1 = l.tr1[g];
+                                const uint32_t pq = (uint32_t)q << 2;
+                                const uint32_t x[4] = {cc.x - dl, cc.y - dl, cc.z - dl, cc.w - dl};
+                                const bool fl[4] = {rr.x == V, rr.y == V, rr.z == V, rr.w == V};
+                                const uint32_t id[4] = {fl[0] ? ((jj.x & 0xFFFFu) << 16) | pq : kInf,
+                                                        fl[1] ? (jj.x & 0xFFFF0000u) | (pq + 1u) : kInf,
+                                                        fl[2] ? ((jj.y & 0xFFFFu) << 16) | (pq + 2u) : kInf,
+                                                        fl[3] ? (jj.y & 0xFFFF0000u) | (pq + 3u) : kInf};
+#pragma unroll
+                                for (int k = 0; k < 4; k++) {
+                                    if (round == 0) {                               // count the flagged jobs, keep the first four
+                                        unsigned long long m = __ballot(fl[k]);
+                                        nF += __popcll(m);
+                                        while (m && nrec < 4) {
+                                            const int ln = __builtin_ctzll(m);
+                                            m &= m - 1;
+                                            f3 = f2; f2 = f1; f1 = f0;
+                                            f0 = ((q0 + ln) << 2) + k;
+                                            nrec += 1;
+                                        }
+                                    }
+                                    b0 = min(b0, absdiff_u32(ecu0, x[k]) < r1 ? id[k] : kInf);
+                                    if (ne > 1) b1 = min(b1, absdiff_u32(ecu1, x[k]) < r1 ? id[k] : kInf);
+                                    if (ne > 2) b2 = min(b2, absdiff_u32(ecu2, x[k]) < r1 ? id[k] : kInf);
+                                    if (ne > 3) b3 = min(b3, absdiff_u32(ecu3, x[k]) < r1 ? id[k] : kInf);
+                                }
+                            }
+                            auto early_pair = [&](uint32_t ejp, uint32_t b) {
+                                if (b != kInf)
+                                    best = min(best, ((unsigned long long)(ejp >> 16) << 48) | ((unsigned long long)(b >> 16) << 32) |
+                                                         ((unsigned long long)(ejp & 0xFFFFu) << 16) | (unsigned long long)(b & 0xFFFFu));
+                            };
+                            early_pair(ejp0, b0);
+                            if (ne > 1) early_pair(ejp1, b1);
+                            if (ne > 2) early_pair(ejp2, b2);
+                            if (ne > 3) early_pair(ejp3, b3);
+                            if (__ballot(min(min(b0, b1), min(b2, b3)) != kInf)) break;
+                            if (round == 0 && nF <= 4) {
+                                if (nrec > 0 && f0 != k0pos) pair_with(min(f0, P - 1));
+                                if (nrec > 1 && f1 != k0pos) pair_with(min(f1, P - 1));
+                                if (nrec > 2 && f2 != k0pos) pair_with(min(f2, P - 1));
+                                if (nrec > 3 && f3 != k0pos) pair_with(min(f3, P - 1));
+                                break;
                             }
                         }
-                        auto early_pair = [&](uint32_t ejp, uint32_t b) {
-                            if (b != kInf)
-                                best = min(best, ((unsigned long long)(ejp >> 16) << 48) | ((unsigned long long)(b >> 16) << 32) |
-                                                     ((unsigned long long)(ejp & 0xFFFFu) << 16) | (unsigned long long)(b & 0xFFFFu));
-                        };
-                        early_pair(ejp0, b0);
-                        if (ne > 1) early_pair(ejp1, b1);
-                        if (ne > 2) early_pair(ejp2, b2);
-                        if (ne > 3) early_pair(ejp3, b3);
-                        if (__ballot(min(min(b0, b1), min(b2, b3)) != kInf)) break;
-                        if (round == 0 && nF <= 4) {
-                            if (nrec > 0 && f0 != k0pos) pair_with(min(f0, P - 1));
-                            if (nrec > 1 && f1 != k0pos) pair_with(min(f1, P - 1));
-                            if (nrec > 2 && f2 != k0pos) pair_with(min(f2, P - 1));
-                            if (nrec > 3 && f3 != k0pos) pair_with(min(f3, P - 1));
-                            break;
-                        }
                     }
-                }
                     win = wave_min_u64(best);
                     act = kActSwap;
                 }
