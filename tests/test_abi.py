@@ -88,3 +88,24 @@ def test_binding_refuses_host_tensors():
     cost = torch.zeros((1, 4), dtype=torch.int32)
     with pytest.raises(ValueError):
         api.run_lower_bound(cost, 2)
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback: without the built HIP library the binding raises instead of computing elsewhere."""
+    monkeypatch.setattr(api, "_lib", None)
+    monkeypatch.setattr(api, "LIB_PATH", str(tmp_path / "libmmbp.so"))
+    with pytest.raises(ImportError):
+        api.load_library()
+    with pytest.raises(ImportError):
+        api.mmbp_version()
+
+
+def test_package_does_not_import_the_oracle():
+    """The oracle is test infrastructure: nothing under the package may reference it."""
+    import pathlib
+    pkg = pathlib.Path(api.__file__).parent
+    import re
+    for f in list(pkg.glob("*.py")) + [g for g in (pkg / "csrc").glob("*") if g.suffix in (".hip", ".hpp")]:
+        text = f.read_text(errors="ignore")
+        assert not re.search(r"^\s*(from|import)\s+oracle|#include\s+\".*oracle|CDLL\(.*oracle", text, re.M), \
+            f"{f} uses the oracle"
