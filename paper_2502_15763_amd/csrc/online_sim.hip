@@ -139,7 +139,8 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
             head_arr = next < N ? uniform_i64(win_arr[w][next & (2 * kWave - 1)]) : INT64_MAX;
         } else {
             const int64_t D = nR;
-            const int64_t dt = p.b_decode * D + p.c_decode;
+            const int64_t bD = p.b_decode * D;              // decode time of the D tokens of one iteration
+            const int64_t dt = bD + p.c_decode;
             // With nothing admissible, every boundary up to the next finish or the next arrival that
             // finds a free slot takes the same decision with the same D: those k iterations are
             // applied at once.  Otherwise (a prefill is waiting for C_d to pass C_p) one at a time.
@@ -152,7 +153,8 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
                 }
             }
             tr.decode(t, D, (uint32_t)k, lane);
-            t += k * dt;
+            const int64_t kdt = k * dt;
+            t += kdt;
             const bool active = rem > 0;
             if (active) rem -= (int32_t)k;
             const bool fin = active && rem == 0;
@@ -160,8 +162,8 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
             const int nf = __popcll(__ballot(fin));
             done += nf;
             nR -= nf;
-            busy += k * D * dt;
-            Cd += k * p.b_decode * D;
+            busy += D * kdt;
+            Cd += k * bD;
             ndec += (int)k;
         }
     }

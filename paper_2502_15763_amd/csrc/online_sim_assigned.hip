@@ -209,11 +209,13 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             npre++;
         } else {
             const int64_t D = nR;
-            const int64_t dt = p.b_decode * D + p.c_decode;
+            const int64_t bD = p.b_decode * D;              // decode time of the D tokens of one iteration
+            const int64_t dt = bD + p.c_decode;
             int64_t k = 1;                                   // nothing to pick: straight to the next finish
             if (nA == 0) k = (int64_t)wave_min_u32(rem > 0 ? (uint32_t)rem : 0xFFFFFFFFu);
             tr.decode(t, D, (uint32_t)k, lane);
-            t += k * dt;
+            const int64_t kdt = k * dt;
+            t += kdt;
             const bool active = rem > 0;
             if (active) rem -= (int32_t)k;
             const bool fin = active && rem == 0;
@@ -221,8 +223,8 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             const int nf = __popcll(__ballot(fin));
             done += nf;
             nR -= nf;
-            busy += k * D * dt;
-            Cd += k * p.b_decode * D;
+            busy += D * kdt;
+            Cd += k * bD;
             ndec += (int)k;
         }
     }
