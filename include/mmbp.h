@@ -32,7 +32,7 @@ extern "C" {
 #define MMBP_EINFEASIBLE  -2  /* N > M * cap: no assignment satisfies the cardinality limit */
 #define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 64,
                                  assigned simulator N <= 8192) */
-#define MMBP_EWORKSPACE   -4  /* workspace missing or smaller than mmbp_workspace_bytes() */
+#define MMBP_EWORKSPACE   -4  /* workspace missing, smaller than mmbp_workspace_bytes(), or not 256-byte aligned */
 #define MMBP_EHIP         -5  /* a HIP call or kernel launch failed; see mmbp_strerror() */
 
 /* per-scenario status */
@@ -60,8 +60,8 @@ int mmbp_version(void);
 const char *mmbp_strerror(int code);
 
 /*
- * Scratch needed by mmbp_local_search for these shapes (bytes of device memory, 256-byte
- * aligned base expected).  Returns 0 when every scenario is searched entirely out of the
+ * Scratch needed by mmbp_local_search for these shapes (bytes of device memory; the base
+ * must be 256-byte aligned).  Returns 0 when every scenario is searched entirely out of the
  * LDS of one workgroup; larger N uses the multi-workgroup path whose layout, per-row minima
  * and global argmin slots live in the workspace.
  */

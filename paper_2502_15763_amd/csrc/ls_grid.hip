@@ -1,15 +1,18 @@
 // Multi-workgroup MMBP local search for scenarios that do not fit the LDS of one workgroup
 // (e.g. one scenario with N = 65536, M = 64).  Same model, candidates, ids and tie-break as the
-// LDS-resident kernel (ls_lds.hip); the state lives in the caller's workspace and a pass is two
+// LDS-resident kernel (ls_lds.hip); the state lives in the caller's workspace and a pass is three
 // launches on the caller's stream:
 //   grid_eval_kernel    every workgroup takes tasks (row block of client X x column chunk of client
 //                       Y, Y staged in LDS) from a table and min-combines the best makespan into
 //                       the control block, and per non-critical job its best makespan against the
 //                       critical client (global argmin = atomic min of values, ids resolved later);
-//   grid_select_kernel  one workgroup: picks the lowest-id candidate of the best value exactly
-//                       (see ls_lds.hip), applies it, and prepares the next pass (top-3 loads,
-//                       task table with the critical client always on the column side).
-// The host enqueues min(max_passes, kMaxPassLaunches) such pairs; once a scenario has stopped the
+//   grid_flag_kernel    many workgroups: when a swap wins, the flagged job of lowest index and the
+//                       lowest partners of the four critical jobs of lowest index (one pass over
+//                       the layout); resets the row minima buffer of the next pass;
+//   grid_select_kernel  one workgroup: picks the lowest-id candidate of the best value exactly,
+//                       applies it, and prepares the next pass (top-3 loads, task table with the
+//                       critical client always on the column side).
+// The host enqueues min(max_passes, kMaxPassLaunches) such triples; once a scenario has stopped the
 // remaining launches return at once.
 #include "mmbp_dev.hpp"
 #include "ls_tile.hpp"
@@ -24,16 +27,28 @@ constexpr int kEvalBlock = 256;          // 4 waves, each up to kRMax row segmen
 constexpr int kEvalGrid = MMBP_GRID_EVAL_BLOCKS;   // workgroups of the evaluation kernel (stride loop over tasks)
 constexpr int kSelBlock = 1024;
 constexpr int kSelWaves = kSelBlock / kWave;
+constexpr int kFlagBlock = 256;          // grid_flag_kernel: kFlagGrid workgroups per scenario
+#ifndef MMBP_GRID_FLAG_BLOCKS
+#define MMBP_GRID_FLAG_BLOCKS 64
+#endif
+constexpr int kFlagGrid = MMBP_GRID_FLAG_BLOCKS;
+static_assert(kFlagGrid <= 64, "one wave of the selection kernel combines the workgroups of grid_flag_kernel");
 constexpr int kColChunk = 1024;          // columns staged in LDS per task
 constexpr int kRowBlockSegs = (kEvalBlock / kWave) * kRMax;   // 16 segments = 1024 rows per task
 constexpr int kMaxPassLaunches = 4096;
 constexpr uint32_t kNoJob32 = 0xFFFFFFFFu;
+#ifndef MMBP_GRID_FLAG_CAP
+#define MMBP_GRID_FLAG_CAP 256
+#endif
+constexpr int kFlagCap = MMBP_GRID_FLAG_CAP;   // flagged jobs listed in LDS when the first batch of a swap selection fails
+static_assert(kSelWaves * 4 == kWave, "one candidate per lane in the selection of a batch");
 
 struct GCtrl {
-    unsigned long long evals, pairs_per_scan, k0, pair, mv;
+    unsigned long long evals, pairs_per_scan;
     uint32_t vswap, vmove;
+    uint32_t bjob[4];                          // first batch of a swap selection (grid_flag_kernel)
     Top3 top;
-    int P, nfeas, ntask, passes, status, stop, iters, prune;
+    int P, nfeas, ntask, passes, status, stop, iters, prune, rk;
 };
 
 struct GTask {
@@ -43,17 +58,26 @@ struct GTask {
     uint32_t yncols;    // columns (multiple of 8)
 };
 
+// what one workgroup of grid_flag_kernel found in its share of the layout
+struct FlagPart {
+    uint32_t part[4];   // lowest partner of each job of the first batch
+    uint32_t k0job;     // lowest flagged job
+    uint32_t nflag;     // flagged jobs
+    uint32_t spare[2];
+};
+
 __host__ __device__ inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct GLayout {        // byte offsets inside one scenario's workspace slice
-    size_t ctrl, load, cnt, gstart, feas, cu, job, rowkey, list, seg_grp, tasks, total;
-    int pmax, tmax;
+    size_t ctrl, load, cnt, gstart, feas, cu, job, rowkey, pos, seg_grp, tasks, fpart, total;
+    int pmax, pstride, tmax;
 };
 
 __host__ __device__ inline GLayout grid_layout(int N, int M)
 {
     GLayout g;
     g.pmax = N + 64 * M;
+    g.pstride = (g.pmax + 63) & ~63;
     g.tmax = (g.pmax / 1024 + M) * (N / 1024 + M);
     size_t o = 0;
     g.ctrl = o; o += up256(sizeof(GCtrl));
@@ -63,10 +87,11 @@ __host__ __device__ inline GLayout grid_layout(int N, int M)
     g.feas = o; o += up256(4 * (size_t)(M + 1));
     g.cu = o; o += up256(4 * (size_t)g.pmax);
     g.job = o; o += up256(4 * (size_t)g.pmax);
-    g.rowkey = o; o += up256(4 * (size_t)g.pmax);
-    g.list = o; o += up256(4 * (size_t)g.pmax);
+    g.rowkey = o; o += up256(2 * 4 * (size_t)g.pstride);   // two buffers, used by alternate passes
+    g.pos = o; o += up256(4 * (size_t)N);
     g.seg_grp = o; o += up256((size_t)g.pmax / 64 + 1);
     g.tasks = o; o += up256(sizeof(GTask) * (size_t)g.tmax);
+    g.fpart = o; o += up256(sizeof(FlagPart) * (size_t)kFlagGrid);
     g.total = o;
     return g;
 }
@@ -75,10 +100,12 @@ struct GWs {
     GCtrl *ctrl;
     long long *load;
     int *cnt, *gstart, *feas;
-    uint32_t *cu, *job, *rowkey, *list;
+    uint32_t *cu, *job, *pos;            // pos: job -> position in the layout
+    uint32_t *rowkey, *rowkey_other;     // per-row minima of this pass; the buffer of the next pass
     uint8_t *seg_grp;
     GTask *tasks;
-    int pmax, tmax;
+    FlagPart *fpart;
+    int pmax, pstride, tmax;
 };
 
 __device__ inline GWs grid_ws(void *workspace, int s, int N, int M)
@@ -93,12 +120,15 @@ __device__ inline GWs grid_ws(void *workspace, int s, int N, int M)
     w.feas = (int *)(b + g.feas);
     w.cu = (uint32_t *)(b + g.cu);
     w.job = (uint32_t *)(b + g.job);
-    w.rowkey = (uint32_t *)(b + g.rowkey);
-    w.list = (uint32_t *)(b + g.list);
+    w.rowkey = (uint32_t *)(b + g.rowkey) + (size_t)(w.ctrl->rk & 1) * g.pstride;
+    w.rowkey_other = (uint32_t *)(b + g.rowkey) + (size_t)((w.ctrl->rk & 1) ^ 1) * g.pstride;
+    w.pos = (uint32_t *)(b + g.pos);
     w.seg_grp = (uint8_t *)(b + g.seg_grp);
     w.tasks = (GTask *)(b + g.tasks);
+    w.fpart = (FlagPart *)(b + g.fpart);
     w.pmax = g.pmax;
     w.tmax = g.tmax;
+    w.pstride = g.pstride;
     return w;
 }
 
@@ -142,6 +172,7 @@ __device__ void g_build_layout(const GWs &w, const CostT *__restrict__ c, const 
         const int a = asg[i];
         const int p = w.gstart[a] + atomicAdd(&s_cursor[a], 1);
         if (p < P) { w.cu[p] = 2u * (uint32_t)c[i] + kBias; w.job[p] = (uint32_t)i; }
+        w.pos[i] = (uint32_t)min(p, P - 1);
     }
     __syncthreads();
 }
@@ -164,19 +195,21 @@ __device__ void g_finish(const GWs &w, const OutPtrs &o, int s, int M)
 // Opens a pass: accounting, top-3, reset of the row minima, task table.  Returns false (after
 // writing the outputs) when the scenario stops here.
 __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M, int max_passes, bool last_launch,
-                            int *s_ntask)
+                            bool toggle, int *s_ntask)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     GCtrl *ctrl = w.ctrl;
     if (wave == 0) {
         if (lane == 0) {
-            ctrl->iters += 1;
-            if ((long long)ctrl->iters > (long long)max_passes + 1) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
-            else if (ctrl->stop) { }
-            else if (ctrl->passes == max_passes || last_launch) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
-            else ctrl->evals += (unsigned long long)N * (unsigned long long)(M - 1) + ctrl->pairs_per_scan;
+            const int iters = ctrl->iters + 1, stop = ctrl->stop, passes = ctrl->passes, rk = ctrl->rk;
+            const unsigned long long evals = ctrl->evals, pairs = ctrl->pairs_per_scan;
+            ctrl->iters = iters;
+            if ((long long)iters > (long long)max_passes + 1) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
+            else if (stop) { }
+            else if (passes == max_passes || last_launch) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
+            else ctrl->evals = evals + (unsigned long long)N * (unsigned long long)(M - 1) + pairs;
             ctrl->vswap = kInf; ctrl->vmove = kInf;
-            ctrl->k0 = ~0ull; ctrl->pair = ~0ull; ctrl->mv = ~0ull;
+            if (toggle) ctrl->rk = (rk & 1) ^ 1;         // the other buffer was reset by grid_flag_kernel
             *s_ntask = 0;
         }
         const Top3 t = wave_top3(w.load, M, lane);
@@ -184,32 +217,51 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
     }
     __syncthreads();
     if (ctrl->stop) { g_finish(w, o, s, M); return false; }
-    const int P = min(ctrl->P, w.pmax);
-    for (int p = tid; p < P; p += kSelBlock) w.rowkey[p] = kInf;
+    __shared__ int s_cn[MMBP_MAX_M], s_gs[MMBP_MAX_M];
+    for (int j = tid; j < M; j += kSelBlock) { s_cn[j] = w.cnt[j]; s_gs[j] = w.gstart[j]; }
+    const int prune = ctrl->prune;
+    __syncthreads();
     // task table: every unordered pair of non-empty clients once, the critical client as columns
     const int astar = min(max(ctrl->top.j0, 0), M - 1);
-    for (int q = tid; q < M * M; q += kSelBlock) {
-        const int g = q / M, b = q - g * M;
-        if (g >= b) continue;
-        if (ctrl->prune && g != astar && b != astar) continue;      // pruned scan: pairs with the critical client only
-        const int X = (g == astar) ? b : g, Y = (g == astar) ? g : b;
-        const int nx = w.cnt[X], ny = w.cnt[Y];
-        if (nx <= 0 || ny <= 0) continue;
-        const int segx = (nx + 63) >> 6;
-        const int nrb = (segx + kRowBlockSegs - 1) / kRowBlockSegs;
-        const int ncols = (ny + 7) & ~7;
-        const int ncc = (ncols + kColChunk - 1) / kColChunk;
-        const int base = atomicAdd(s_ntask, nrb * ncc);
-        if (base + nrb * ncc > w.tmax) continue;          // cannot happen (tmax bounds the table)
-        for (int rb = 0; rb < nrb; rb++)
-            for (int cc = 0; cc < ncc; cc++) {
-                GTask e;
-                e.xy = (uint32_t)X | ((uint32_t)Y << 8) | ((uint32_t)min(kRowBlockSegs, segx - rb * kRowBlockSegs) << 16);
-                e.xrow0 = (uint32_t)(w.gstart[X] + rb * kRowBlockSegs * 64);
-                e.ycol0 = (uint32_t)(w.gstart[Y] + cc * kColChunk);
-                e.yncols = (uint32_t)min(kColChunk, ncols - cc * kColChunk);
-                w.tasks[base + rb * ncc + cc] = e;
+    // Two rounds: the first task of every pair (a full row block x a full column chunk unless the
+    // pair is smaller), then the remainders, so that the stride loop of the evaluation gives every
+    // workgroup the same number of large tasks.
+    for (int round = 0; round < 2; round++) {
+        for (int q0 = 0; q0 < M * M; q0 += kSelBlock) {  // uniform trip count: the waves cooperate below
+            const int q = q0 + tid;
+            const int g = q / M, b = q - g * M;
+            const bool pair = q < M * M && g < b && !(prune && g != astar && b != astar);   // pruned scan: pairs
+            const int X = (g == astar) ? b : g, Y = (g == astar) ? g : b;                      // with the critical client only
+            const int nx = pair ? s_cn[X] : 0, ny = pair ? s_cn[Y] : 0;
+            const int segx = (nx + 63) >> 6;
+            const int nrb = (segx + kRowBlockSegs - 1) / kRowBlockSegs;
+            const int ncols = (ny + 7) & ~7;
+            const int ncc = (ncols + kColChunk - 1) / kColChunk;
+            const int all = (nx > 0 && ny > 0) ? nrb * ncc : 0;
+            const int mine = round == 0 ? min(all, 1) : max(all - 1, 0);
+            int incl = mine;                              // one slot reservation per wave
+            for (int off = 1; off < kWave; off <<= 1) {
+                const int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
             }
+            const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+            int wbase = 0;
+            if (lane == 0 && total > 0) wbase = atomicAdd(s_ntask, total);
+            wbase = __builtin_amdgcn_readfirstlane(wbase);
+            int slot = wbase + incl - mine;
+            if (mine == 0 || slot + mine > w.tmax) continue;   // (the second cannot happen: tmax bounds the table)
+            for (int rb = 0; rb < nrb; rb++)
+                for (int cc = 0; cc < ncc; cc++) {
+                    if ((rb == 0 && cc == 0) != (round == 0)) continue;
+                    GTask e;
+                    e.xy = (uint32_t)X | ((uint32_t)Y << 8) | ((uint32_t)min(kRowBlockSegs, segx - rb * kRowBlockSegs) << 16);
+                    e.xrow0 = (uint32_t)(s_gs[X] + rb * kRowBlockSegs * 64);
+                    e.ycol0 = (uint32_t)(s_gs[Y] + cc * kColChunk);
+                    e.yncols = (uint32_t)min(kColChunk, ncols - cc * kColChunk);
+                    w.tasks[slot++] = e;
+                }
+        }
+        __syncthreads();                                  // all first tasks are placed before any remainder
     }
     __syncthreads();
     if (tid == 0) ctrl->ntask = min(*s_ntask, w.tmax);
@@ -238,7 +290,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
     if (tid == 0) {
         s_bad_cost = 0; s_bad_assign = 0;
         ctrl->passes = 0; ctrl->status = MMBP_ST_OK; ctrl->stop = 0; ctrl->evals = 0; ctrl->iters = 0; ctrl->ntask = 0;
-        ctrl->prune = prune;
+        ctrl->prune = prune; ctrl->rk = 0;
     }
     __syncthreads();
     {
@@ -292,7 +344,11 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
     for (int j = tid; j < M; j += kSelBlock) { w.load[j] = s_load[j]; w.cnt[j] = s_cnt[j]; }
     __syncthreads();
     g_build_layout<CostT>(w, c, asg, N, M, cap, s_cnt /* reused as cursors */);
-    g_prep_pass(w, o, s, N, M, max_passes, false, &s_ntask);
+    {
+        uint4 *rk4 = (uint4 *)(w.rowkey < w.rowkey_other ? w.rowkey : w.rowkey_other);   // both buffers
+        for (int q = tid; q < (w.pstride >> 1); q += kSelBlock) rk4[q] = make_uint4(kInf, kInf, kInf, kInf);
+    }
+    g_prep_pass(w, o, s, N, M, max_passes, false, false, &s_ntask);
 }
 
 // ---- kernel 1: evaluation of all candidates of a pass ----
@@ -315,7 +371,7 @@ __device__ __forceinline__ void eval_rows(const GWs &w, const uint32_t *cols, in
     }
 }
 
-__global__ __launch_bounds__(kEvalBlock) void grid_eval_kernel(int N, int M, void *workspace)
+__global__ __launch_bounds__(kEvalBlock, 8) void grid_eval_kernel(int N, int M, void *workspace)
 {
     const int s = blockIdx.y;
     const GWs w = grid_ws(workspace, s, N, M);
@@ -323,14 +379,22 @@ __global__ __launch_bounds__(kEvalBlock) void grid_eval_kernel(int N, int M, voi
     if (ctrl->stop) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __shared__ __align__(16) uint32_t cols[kColChunk];
+    __shared__ uint32_t s_ld[MMBP_MAX_M];
+    __shared__ int s_feas[MMBP_MAX_M];
     Top3 top;
     top.v0 = uniu(ctrl->top.v0); top.v1 = uniu(ctrl->top.v1); top.v2 = uniu(ctrl->top.v2);
     top.j0 = uni(ctrl->top.j0); top.j1 = uni(ctrl->top.j1); top.j2 = uni(ctrl->top.j2);
     const int astar = min(max(top.j0, 0), M - 1);
     const int ntask = min(ctrl->ntask, w.tmax);
     const int P = min(ctrl->P, w.pmax);
+    const int nfeas = min(ctrl->nfeas, M);
     uint32_t sbest = kInf, mbest = kInf;
+    for (int j = tid; j < M; j += kEvalBlock) { s_ld[j] = (uint32_t)w.load[j]; s_feas[j] = j < nfeas ? w.feas[j] : 0; }
+    __syncthreads();
 
+    // (a shared counter dealing the tasks out on demand was measured slower: thousands of atomics
+    // on one address take longer than the imbalance they remove; the table lists the full-size
+    // tasks first instead, so the stride gives every workgroup the same number of them)
     for (int t = blockIdx.x; t < ntask; t += gridDim.x) {
         const GTask e = w.tasks[t];
         const int X = (int)(e.xy & 0xFFu), Y = (int)((e.xy >> 8) & 0xFFu), nseg = min((int)(e.xy >> 16), kRowBlockSegs);
@@ -338,11 +402,12 @@ __global__ __launch_bounds__(kEvalBlock) void grid_eval_kernel(int N, int M, voi
         const int ycol0 = max(min((int)e.ycol0, w.pmax - ncols), 0);
         for (int i = tid; i < ncols; i += kEvalBlock) cols[i] = w.cu[ycol0 + i];
         __syncthreads();
-        const int rowbase = (int)e.xrow0 + wave * kRMax * 64;
-        int R = min(max(nseg - wave * kRMax, 0), kRMax);
+        const int role = (wave + t) & (kEvalBlock / kWave - 1);   // short row blocks: not always the same SIMD
+        const int rowbase = (int)e.xrow0 + role * kRMax * 64;
+        int R = min(max(nseg - role * kRMax, 0), kRMax);
         if (rowbase < 0 || rowbase + 64 * R > w.pmax) R = 0;      // cannot happen: rows lie inside the layout
         if (R > 0 && ncols > 0) {
-            const uint32_t lx = (uint32_t)w.load[X], ly = (uint32_t)w.load[Y];
+            const uint32_t lx = s_ld[X], ly = s_ld[Y];
             const uint32_t oth = others_max(top, X, Y);
             const bool star = Y == astar;
             switch (R) {
@@ -355,7 +420,6 @@ __global__ __launch_bounds__(kEvalBlock) void grid_eval_kernel(int N, int M, voi
         __syncthreads();
     }
     // moves: value only
-    const int nfeas = min(ctrl->nfeas, M);
     if (nfeas > 0) {
         const int nseg = P >> 6;
         for (int seg = blockIdx.x * (kEvalBlock / kWave) + wave; seg < nseg; seg += gridDim.x * (kEvalBlock / kWave)) {
@@ -363,25 +427,183 @@ __global__ __launch_bounds__(kEvalBlock) void grid_eval_kernel(int N, int M, voi
             if (ctrl->prune && g != astar) continue;                 // an improving move leaves the critical client
             const uint32_t x = w.cu[seg * 64 + lane];
             const uint32_t ci = (x - kBias) >> 1;
-            const uint32_t la = (uint32_t)w.load[g];
+            const uint32_t la = s_ld[g];
             uint32_t m = kInf;
             for (int q = 0; q < nfeas; q++) {
-                const int b = w.feas[q];
+                const int b = s_feas[q];
                 if (b == g) continue;
-                m = min(m, max(max(la - ci, (uint32_t)w.load[b] + ci), others_max(top, g, b)));
+                m = min(m, max(max(la - ci, s_ld[b] + ci), others_max(top, g, b)));
             }
             if (x != kPad) mbest = min(mbest, m);
         }
     }
+    // One atomic per workgroup and kind at most, and none when the control block already holds a
+    // value as low (the plain read may be stale, i.e. too high: then the atomic is merely redundant).
+    // Atomics of thousands of waves on one address would cost more than the evaluation's tail.
     mbest = wave_min_u32(mbest);
     sbest = wave_min_u32(sbest);
-    if (lane == 0) {
-        if (mbest != kInf) atomicMin(&ctrl->vmove, mbest);
-        if (sbest != kInf) atomicMin(&ctrl->vswap, sbest);
+    __shared__ uint32_t s_wm[kEvalBlock / kWave], s_ws[kEvalBlock / kWave];
+    if (lane == 0) { s_wm[wave] = mbest; s_ws[wave] = sbest; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int q = 1; q < kEvalBlock / kWave; q++) { mbest = min(mbest, s_wm[q]); sbest = min(sbest, s_ws[q]); }
+        if (mbest < __hip_atomic_load(&ctrl->vmove, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMin(&ctrl->vmove, mbest);
+        if (sbest < __hip_atomic_load(&ctrl->vswap, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMin(&ctrl->vswap, sbest);
     }
 }
 
-// ---- kernel 2: exact selection, apply, preparation of the next pass ----
+// ---- exact selection of a swap: pieces shared by grid_flag_kernel and grid_select_kernel ----
+// Every swap of the best value V pairs a job of the critical client with a flagged job (row
+// minimum == V) of another client.  With k0 the flagged job of lowest index, the lowest
+// (min(i,k), max(i,k)) is either (e, f) for the lowest critical job e < k0 that has a partner (f its
+// lowest partner), or (k0, c) with c the lowest critical partner of k0.  Ties at V are the rule on
+// large instances (V is often the load of the second client), so the flagged jobs are not listed:
+// one pass over the layout finds k0 and, for the four critical jobs of lowest index, their lowest
+// partners (grid_flag_kernel, many workgroups).  When that does not settle it, a short list of
+// flagged jobs is tried against all early critical jobs; with a long list, batches of four go on.
+struct SwapCtx {
+    const uint32_t *ld;        // loads of the clients (LDS copy)
+    Top3 top;
+    uint32_t V, lstar;
+    int astar, sbase, send, sslots, P;   // critical client: its jobs [sbase, send), its slots up to sslots
+};
+
+__device__ __forceinline__ SwapCtx swap_ctx(const GWs &w, const uint32_t *ld, const Top3 &top, uint32_t V, int astar, int P)
+{
+    SwapCtx c;
+    c.ld = ld; c.top = top; c.V = V; c.astar = astar; c.P = P;
+    c.lstar = ld[astar];
+    c.sbase = min(max(w.gstart[astar], 0), P);
+    const int scnt = min(max(w.cnt[astar], 0), P - c.sbase);
+    c.send = c.sbase + scnt;
+    c.sslots = c.sbase + ((scnt + 63) & ~63);
+    return c;
+}
+
+// A pair (critical job e, job f of client g) reaches V exactly when its key |cu_e - (cu_f - sh)|
+// lies in [klo, klo + span], i.e. max(others, (l_g + l_star + key) >> 1) == V.  False: no key does.
+__device__ __forceinline__ bool key_range(const SwapCtx &c, int g, uint32_t &sh, uint32_t &klo, uint32_t &span)
+{
+    const uint32_t lg = c.ld[g], lsum = lg + c.lstar, oth = others_max(c.top, g, c.astar);
+    sh = lg - c.lstar;
+    klo = 0; span = 0;
+    if (oth > c.V || lsum > 2u * c.V + 1u) return false;
+    const uint32_t khi = min(2u * c.V + 1u - lsum, kKeyLimit - 1u);
+    klo = (oth == c.V || lsum > 2u * c.V) ? 0u : 2u * c.V - lsum;
+    span = khi - klo;
+    return klo <= khi;
+}
+
+// The four critical jobs of lowest index (above `last` when `after`), ascending, kNoJob32 for
+// none.  All threads of the workgroup call; s_cand holds 4 entries per wave (at most 16 waves);
+// contains one barrier, and the caller separates two calls by another.
+__device__ void lowest_four(const GWs &w, const SwapCtx &c, bool after, uint32_t last, uint32_t *s_cand, uint32_t bjob[4])
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwave = (int)(blockDim.x >> 6);
+    uint32_t m0 = kNoJob32, m1 = kNoJob32, m2 = kNoJob32, m3 = kNoJob32;
+    for (int p = c.sbase + tid; p < c.send; p += (int)blockDim.x) {
+        const uint32_t jb = w.job[p];
+        if ((after && jb <= last) || jb >= m3) continue;
+        m3 = jb;
+        if (m3 < m2) { const uint32_t t = m2; m2 = m3; m3 = t; }
+        if (m2 < m1) { const uint32_t t = m1; m1 = m2; m2 = t; }
+        if (m1 < m0) { const uint32_t t = m0; m0 = m1; m1 = t; }
+    }
+    uint32_t mine = kNoJob32;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        const uint32_t mw = wave_min_u32(m0);
+        if (lane == r) mine = mw;
+        if (m0 == mw && m0 != kNoJob32) { m0 = m1; m1 = m2; m2 = m3; m3 = kNoJob32; }
+    }
+    if (lane < 4) s_cand[wave * 4 + lane] = mine;
+    __syncthreads();
+    uint32_t v = lane < nwave * 4 ? s_cand[lane] : kNoJob32;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        bjob[r] = wave_min_u32(v);
+        if (v == bjob[r]) v = kNoJob32;
+    }
+}
+
+// Layout positions outside the critical client, four per step from quad q0 with stride qstride:
+// per batch job r the lowest partner pm[r]; from the row minima (rowkey != nullptr) the lowest
+// flagged job k0 and the number of flagged jobs.  Results are per lane (the caller reduces).
+__device__ __forceinline__ void scan_partners(const GWs &w, const SwapCtx &c, const uint32_t *rowkey, const uint32_t bx[4],
+                                              int q0, int qstride, uint32_t pm[4], uint32_t &k0, uint32_t &nflag)
+{
+    const uint4 *rk4 = (const uint4 *)rowkey, *cu4 = (const uint4 *)w.cu, *jb4 = (const uint4 *)w.job;
+    const int nquad = c.P >> 2;
+    for (int q = q0; q < nquad; q += qstride) {
+        const int p = q << 2;
+        if (p >= c.sbase && p < c.sslots) continue;
+        uint4 r4 = make_uint4(kInf, kInf, kInf, kInf);
+        if (rowkey) r4 = rk4[q];
+        uint32_t sh, klo, span;
+        const bool reach = key_range(c, w.seg_grp[p >> 6], sh, klo, span);
+        if (!reach && !rowkey) continue;                  // no job of this client reaches V
+        const uint4 x4 = cu4[q], j4 = jb4[q];
+        const uint32_t xs[4] = {x4.x, x4.y, x4.z, x4.w}, js[4] = {j4.x, j4.y, j4.z, j4.w};
+        const uint32_t rs[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {                      // padding slots carry kNoJob32: harmless in a min
+            const uint32_t xf = xs[e] - sh, j = reach ? js[e] : kNoJob32;
+            if (rs[e] == c.V) { k0 = min(k0, js[e]); nflag += 1; }
+#pragma unroll
+            for (int r = 0; r < 4; r++) pm[r] = min(pm[r], __usad(bx[r], xf, 0u) - klo <= span ? j : kNoJob32);
+        }
+    }
+}
+
+// ---- kernel 2: first step of the selection of a swap, and reset of the next pass's row minima ----
+__global__ __launch_bounds__(kFlagBlock) void grid_flag_kernel(int N, int M, void *workspace)
+{
+    const int s = blockIdx.y;
+    const GWs w = grid_ws(workspace, s, N, M);
+    GCtrl *ctrl = w.ctrl;
+    if (ctrl->stop) return;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int gtid = (int)blockIdx.x * kFlagBlock + tid, gthreads = (int)gridDim.x * kFlagBlock;
+    {
+        uint4 *o4 = (uint4 *)w.rowkey_other;
+        for (int q = gtid; q < (w.pstride >> 2); q += gthreads) o4[q] = make_uint4(kInf, kInf, kInf, kInf);
+    }
+    Top3 top;
+    top.v0 = uniu(ctrl->top.v0); top.v1 = uniu(ctrl->top.v1); top.v2 = uniu(ctrl->top.v2);
+    top.j0 = uni(ctrl->top.j0); top.j1 = uni(ctrl->top.j1); top.j2 = uni(ctrl->top.j2);
+    const uint32_t Vm = ctrl->vmove, Vs = ctrl->vswap;
+    if (Vs >= top.v0 || Vm <= Vs) return;                // local optimum, or a move wins
+    __shared__ uint32_t s_ld[MMBP_MAX_M], s_cand[(kFlagBlock / kWave) * 4];
+    for (int j = tid; j < M; j += kFlagBlock) s_ld[j] = (uint32_t)w.load[j];
+    __syncthreads();
+    const int astar = min(max(top.j0, 0), M - 1);
+    const SwapCtx c = swap_ctx(w, s_ld, top, Vs, astar, min(ctrl->P, w.pmax));
+    uint32_t bjob[4], bx[4];
+    lowest_four(w, c, false, 0u, s_cand, bjob);
+#pragma unroll
+    for (int r = 0; r < 4; r++) bx[r] = bjob[r] < (uint32_t)N ? w.cu[min((int)w.pos[bjob[r]], c.P - 1)] : kPad;
+    uint32_t pm[4] = {kNoJob32, kNoJob32, kNoJob32, kNoJob32}, k0 = kNoJob32, nflag = 0;
+    scan_partners(w, c, w.rowkey, bx, gtid, gthreads, pm, k0, nflag);
+#pragma unroll
+    for (int r = 0; r < 4; r++) pm[r] = wave_min_u32(pm[r]);
+    k0 = wave_min_u32(k0);
+    for (int off = 32; off >= 1; off >>= 1) nflag += __shfl_xor(nflag, off);
+    __shared__ uint32_t s_red[kFlagBlock / kWave][6];
+    if (lane == 0) {
+        uint32_t *row = s_red[tid >> 6];
+        row[0] = pm[0]; row[1] = pm[1]; row[2] = pm[2]; row[3] = pm[3]; row[4] = k0; row[5] = nflag;
+    }
+    __syncthreads();
+    if (tid < 6) {                                       // plain stores: the selection kernel combines the workgroups
+        uint32_t v = s_red[0][tid];
+        for (int q = 1; q < kFlagBlock / kWave; q++) v = tid < 5 ? min(v, s_red[q][tid]) : v + s_red[q][tid];
+        uint32_t *out = (uint32_t *)&w.fpart[blockIdx.x];
+        out[tid] = v;
+    }
+    if (blockIdx.x == 0 && tid < 4) ctrl->bjob[tid] = tid == 0 ? bjob[0] : tid == 1 ? bjob[1] : tid == 2 ? bjob[2] : bjob[3];
+}
+
+// ---- kernel 3: exact selection, apply, preparation of the next pass ----
 template <typename CostT>
 __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__restrict__ cost_all, int N, int M, int cap,
                                                                 int max_passes, int32_t *assign_all, OutPtrs o,
@@ -395,8 +617,14 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
     int32_t *asg = assign_all + (size_t)s * N;
     const int tid = threadIdx.x, lane = tid & 63;
     __shared__ int s_cursor[MMBP_MAX_M];
-    __shared__ int s_nE, s_nF, s_ntask, s_rebuild;
-    __shared__ unsigned long long s_k0, s_best;
+    __shared__ uint32_t s_ld[MMBP_MAX_M];
+    __shared__ int s_feas[MMBP_MAX_M];
+    __shared__ int s_ntask, s_rebuild;
+    __shared__ unsigned long long s_best;
+    __shared__ uint32_t s_later, s_part[4], s_cand[kSelWaves * 4];
+    __shared__ int s_nlist;
+    __shared__ FlagPart s_flag;
+    __shared__ uint32_t s_fpos[kFlagCap], s_fx[kFlagCap], s_fklo[kFlagCap], s_fspan[kFlagCap], s_fjob[kFlagCap];
 
     Top3 top;
     top.v0 = uniu(ctrl->top.v0); top.v1 = uniu(ctrl->top.v1); top.v2 = uniu(ctrl->top.v2);
@@ -407,26 +635,27 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
     const int nfeas = min(ctrl->nfeas, M);
     const uint32_t Vm = ctrl->vmove, Vs = ctrl->vswap;
     const uint32_t V = min(Vm, Vs);
-    if (tid == 0) { s_nE = 0; s_nF = 0; s_rebuild = 0; s_k0 = ~0ull; s_best = ~0ull; }
+    if (tid == 0) { s_rebuild = 0; s_later = kNoJob32; s_nlist = 0; s_best = ~0ull; }
+    for (int j = tid; j < M; j += kSelBlock) { s_ld[j] = (uint32_t)w.load[j]; s_feas[j] = j < nfeas ? w.feas[j] : 0; }
     __syncthreads();
     if (V >= T) {                                        // local optimum
         g_finish(w, o, s, M);
         return;
     }
     if (Vm <= Vs) {
-        // a move wins: lowest id among the moves of value V
+        // A move wins: the lowest id among the moves of value V.  V is below the makespan, so the
+        // job leaves the critical client: only its jobs are scanned.
+        const int sbase = min(max(w.gstart[astar], 0), P), send = sbase + min(max(w.cnt[astar], 0), P - sbase);
+        const uint32_t la = s_ld[astar];
         unsigned long long best = ~0ull;
-        for (int p = tid; p < P; p += kSelBlock) {
-            const uint32_t x = w.cu[p];
+        for (int p = sbase + tid; p < send; p += kSelBlock) {
+            const uint32_t x = w.cu[p], jb = w.job[p];
             if (x == kPad) continue;
-            const int g = w.seg_grp[p >> 6];
             const uint32_t ci = (x - kBias) >> 1;
-            const uint32_t la = (uint32_t)w.load[g];
-            const uint32_t jb = w.job[p];
             for (int q = 0; q < nfeas; q++) {
-                const int b = w.feas[q];
-                if (b == g) continue;
-                const uint32_t v = max(max(la - ci, (uint32_t)w.load[b] + ci), others_max(top, g, b));
+                const int b = s_feas[q];
+                if (b == astar) continue;
+                const uint32_t v = max(max(la - ci, s_ld[b] + ci), others_max(top, astar, b));
                 if (v == V)
                     best = min(best, (((unsigned long long)jb * (unsigned long long)M + (unsigned long long)b) << 32) |
                                          (unsigned long long)p);
@@ -440,96 +669,166 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
             const uint32_t id = (uint32_t)(mv >> 32);
             const int p = (int)(uint32_t)mv;
             const int i = (int)(id / (uint32_t)M), b = (int)(id % (uint32_t)M);
-            if (mv == ~0ull || i >= N || p >= P) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
+            if (mv == ~0ull || i >= N || p < sbase || p >= send) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
             else {
-                const int a = w.seg_grp[p >> 6];
-                const long long ci = (long long)((w.cu[p] - kBias) >> 1);
+                const int a = astar, na = w.cnt[a], nb = w.cnt[b];
+                const uint32_t x = w.cu[p];
+                const long long ci = (long long)((x - kBias) >> 1);
                 w.load[a] -= ci; w.load[b] += ci;
-                w.cnt[a] -= 1; w.cnt[b] += 1;
+                w.cnt[a] = na - 1; w.cnt[b] = nb + 1;
                 asg[i] = b;
                 if (o.applied_log) o.applied_log[(size_t)s * max_passes + ctrl->passes] = (uint64_t)id;
                 ctrl->passes += 1;
-                s_rebuild = 1;
+                // Layout: the last job of the source client fills the hole; the job goes to the first
+                // free slot of the target client.  Only a target whose slots are all taken needs the
+                // layout rebuilt.  (The order of the jobs inside a client decides nothing.)
+                const int slot = w.gstart[b] + nb;
+                if (slot >= w.gstart[b + 1]) s_rebuild = 1;
+                else {
+                    const int last = sbase + na - 1;
+                    if (p != last) {
+                        const uint32_t jl = w.job[last];
+                        w.cu[p] = w.cu[last]; w.job[p] = jl;
+                        if (jl < (uint32_t)N) w.pos[jl] = (uint32_t)p;
+                    }
+                    w.cu[last] = kPad; w.job[last] = kNoJob32;
+                    w.cu[slot] = x; w.job[slot] = (uint32_t)i; w.pos[i] = (uint32_t)slot;
+                    // unordered pairs on different clients: N^2 - sum n^2 over 2
+                    ctrl->pairs_per_scan -= (unsigned long long)((long long)nb - (long long)na + 1);
+                }
             }
         }
         __syncthreads();
         if (s_rebuild) g_build_layout<CostT>(w, c, asg, N, M, cap, s_cursor);
-    } else {
-        // a swap wins: lowest (min(i,k), max(i,k)) among the swaps of value V (see ls_lds.hip)
-        const uint32_t lstar = (uint32_t)w.load[astar];
-        const int sbase = min(max(w.gstart[astar], 0), P), scnt = min(max(w.cnt[astar], 0), P - sbase);
-        const int send = sbase + scnt, sslots = sbase + ((scnt + 63) & ~63);
-        {
-            unsigned long long k0 = ~0ull;
-            for (int p = tid; p < P; p += kSelBlock) {
-                if (p >= sbase && p < sslots) continue;
-                if (w.rowkey[p] == V) {
-                    const int idx = atomicAdd(&s_nF, 1);
-                    w.list[idx] = (uint32_t)p;
-                    k0 = min(k0, ((unsigned long long)w.job[p] << 32) | (unsigned long long)p);
-                }
+        else if (tid < kWave) {                          // move targets: clients below the cap, ascending
+            int nf = 0;
+            for (int j0 = 0; j0 < M; j0 += kWave) {
+                const int j = j0 + lane;
+                const bool ok = j < M && w.cnt[j] < cap;
+                const unsigned long long m = __ballot(ok);
+                if (ok) w.feas[nf + __popcll(m & ((1ull << lane) - 1ull))] = j;
+                nf += __popcll(m);
             }
-            k0 = wave_min_u64(k0);
-            if (lane == 0 && k0 != ~0ull) atomicMin(&s_k0, k0);
+            if (lane == 0) ctrl->nfeas = nf;
+        }
+    } else {
+        // a swap wins (see above); grid_flag_kernel has taken the first batch
+        const SwapCtx sc = swap_ctx(w, s_ld, top, V, astar, P);
+        if (tid < kWave) {                               // combine what the workgroups of grid_flag_kernel found
+            FlagPart f;
+            f.part[0] = f.part[1] = f.part[2] = f.part[3] = f.k0job = kNoJob32; f.nflag = 0;
+            if (lane < kFlagGrid) f = w.fpart[lane];
+#pragma unroll
+            for (int r = 0; r < 4; r++) f.part[r] = wave_min_u32(f.part[r]);
+            f.k0job = wave_min_u32(f.k0job);
+            for (int off = 32; off >= 1; off >>= 1) f.nflag += __shfl_xor(f.nflag, off);
+            if (lane == 0) s_flag = f;
         }
         __syncthreads();
-        if (s_k0 == ~0ull) {                             // cannot happen: a best swap has a flagged job
+        const uint32_t k0job = s_flag.k0job, nflag = s_flag.nflag;
+        if (k0job >= (uint32_t)N) {                      // cannot happen: a best swap has a flagged job
             if (tid == 0) ctrl->status = MMBP_ST_INTERNAL;
             __syncthreads();
             g_finish(w, o, s, M);
             return;
         }
-        const uint32_t k0job = (uint32_t)(s_k0 >> 32);
-        const int k0pos = min((int)(uint32_t)s_k0, P - 1);
-        for (int p = sbase + tid; p < send; p += kSelBlock) {
-            if (w.job[p] < k0job) {
-                const int idx = atomicAdd(&s_nE, 1);
-                w.list[P - 1 - idx] = (uint32_t)p;
+        uint32_t bjob[4], part[4], ji = kNoJob32, jk = kNoJob32;
+#pragma unroll
+        for (int r = 0; r < 4; r++) { bjob[r] = ctrl->bjob[r]; part[r] = s_flag.part[r]; }
+        bool found = false, early_done = false;
+        auto decide = [&]() {
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                if (found || early_done) continue;
+                if (bjob[r] >= (uint32_t)N || bjob[r] > k0job) { early_done = true; continue; }
+                if (part[r] < (uint32_t)N) { found = true; ji = bjob[r]; jk = part[r]; }
             }
+        };
+        decide();
+        while (!found && !early_done && nflag > (uint32_t)kFlagCap) {
+            // many flagged jobs and no partner yet: the next four early critical jobs
+            const uint32_t last = bjob[3];
+            if (tid < 4) s_part[tid] = kNoJob32;
+            lowest_four(w, sc, true, last, s_cand, bjob);
+            uint32_t bx[4];
+#pragma unroll
+            for (int r = 0; r < 4; r++) bx[r] = bjob[r] < (uint32_t)N ? w.cu[min((int)w.pos[bjob[r]], P - 1)] : kPad;
+            uint32_t pm[4] = {kNoJob32, kNoJob32, kNoJob32, kNoJob32}, k0 = kNoJob32, nf = 0;
+            scan_partners(w, sc, nullptr, bx, tid, kSelBlock, pm, k0, nf);
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                pm[r] = wave_min_u32(pm[r]);
+                if (lane == 0 && pm[r] != kNoJob32) atomicMin(&s_part[r], pm[r]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 4; r++) part[r] = s_part[r];
+            decide();
+            __syncthreads();                             // s_cand, s_part are rewritten by the next batch
         }
-        __syncthreads();
-        {
-            // pairs (early critical job, flagged job) and (k0, later critical job); the packed
-            // candidate (i << 44 | k << 24, job indices below 2^20) keeps the lowest (i, k)
-            const int nE = min(s_nE, scnt), nF = min(s_nF, P);
-            unsigned long long best = ~0ull;
-            const long long npair = (long long)nE * (long long)nF;
-            for (long long q = tid; q < npair; q += kSelBlock) {
-                const int e = (int)(q / nF), f = (int)(q - (long long)e * nF);
-                const int pe = (int)w.list[P - 1 - e], pf = (int)w.list[f];
-                const int g = w.seg_grp[pf >> 6];
-                const uint32_t lg = (uint32_t)w.load[g];
-                const uint32_t key = absdiff_u32(w.cu[pe], w.cu[pf] - (lg - lstar));
-                if (swap_value(key, lg + lstar, others_max(top, g, astar)) == V)
-                    best = min(best, ((unsigned long long)w.job[pe] << 44) | ((unsigned long long)w.job[pf] << 24));
+        if (!found && !early_done) {
+            // few flagged jobs: list them and try all of them against every early critical job
+            const uint4 *rk4 = (const uint4 *)w.rowkey;
+            for (int q = tid; q < (P >> 2); q += kSelBlock) {
+                const int p = q << 2;
+                if (p >= sc.sbase && p < sc.sslots) continue;
+                const uint4 r4 = rk4[q];
+                const uint32_t rs[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+                for (int e = 0; e < 4; e++)
+                    if (rs[e] == V) {
+                        const int idx = atomicAdd(&s_nlist, 1);
+                        if (idx < kFlagCap) s_fpos[idx] = (uint32_t)(p + e);
+                    }
             }
-            const int g = w.seg_grp[k0pos >> 6];
-            const uint32_t lg = (uint32_t)w.load[g];
-            const uint32_t xk = w.cu[k0pos] - (lg - lstar);
-            const uint32_t oth = others_max(top, g, astar);
-            for (int p = sbase + tid; p < send; p += kSelBlock) {
+            __syncthreads();
+            const int nl = min(s_nlist, kFlagCap);
+            if (tid < nl) {
+                const int p = min((int)s_fpos[tid], P - 1);
+                uint32_t sh, klo, span;
+                const bool ok = key_range(sc, w.seg_grp[p >> 6], sh, klo, span);
+                s_fx[tid] = w.cu[p] - sh;
+                s_fklo[tid] = ok ? klo : 1u;               // not ok: empty range
+                s_fspan[tid] = ok ? span : 0u;
+                s_fjob[tid] = ok ? w.job[p] : kNoJob32;
+            }
+            __syncthreads();
+            unsigned long long best = ~0ull;
+            for (int p = sc.sbase + tid; p < sc.send; p += kSelBlock) {
                 const uint32_t jb = w.job[p];
-                if (jb > k0job && swap_value(absdiff_u32(w.cu[p], xk), lg + lstar, oth) == V)
-                    best = min(best, ((unsigned long long)k0job << 44) | ((unsigned long long)jb << 24));
+                if (jb >= k0job) continue;
+                const uint32_t x = w.cu[p];
+                uint32_t pm = kNoJob32;
+                for (int f = 0; f < nl; f++)
+                    pm = min(pm, __usad(x, s_fx[f], 0u) - s_fklo[f] <= s_fspan[f] ? s_fjob[f] : kNoJob32);
+                if (pm != kNoJob32) best = min(best, ((unsigned long long)jb << 32) | (unsigned long long)pm);
             }
             best = wave_min_u64(best);
             if (lane == 0 && best != ~0ull) atomicMin(&s_best, best);
+            __syncthreads();
+            const unsigned long long b = s_best;
+            if (b != ~0ull) { found = true; ji = (uint32_t)(b >> 32); jk = (uint32_t)b; }
         }
-        __syncthreads();
-        // the winning jobs (i < k); their positions are looked up
-        const unsigned long long pr = s_best;
-        const uint32_t ji = (uint32_t)(pr >> 44), jk = (uint32_t)(pr >> 24) & 0xFFFFFu;
-        if (tid == 0) { s_nE = -1; s_nF = -1; }
-        __syncthreads();
-        for (int p = tid; p < P; p += kSelBlock) {
-            const uint32_t jb = w.job[p];
-            if (jb == ji) s_nE = p;
-            if (jb == jk) s_nF = p;
+        if (!found) {
+            // (k0, the lowest later critical job that reaches V with it)
+            const int k0pos = min((int)w.pos[k0job], P - 1);
+            uint32_t sh, klo, span;
+            const bool ok = key_range(sc, w.seg_grp[k0pos >> 6], sh, klo, span);
+            const uint32_t xk = w.cu[k0pos] - sh;
+            uint32_t best = kNoJob32;
+            for (int p = sc.sbase + tid; p < sc.send; p += kSelBlock) {
+                const uint32_t jb = w.job[p];
+                if (ok && jb != kNoJob32 && jb > k0job && __usad(w.cu[p], xk, 0u) - klo <= span) best = min(best, jb);
+            }
+            best = wave_min_u32(best);
+            if (lane == 0 && best != kNoJob32) atomicMin(&s_later, best);
+            __syncthreads();
+            ji = k0job;
+            jk = s_later;
         }
-        __syncthreads();
         if (tid == 0) {
-            const int pi = s_nE, pk = s_nF;
-            if (pr == ~0ull || ji >= (uint32_t)N || jk >= (uint32_t)N || pi < 0 || pk < 0) {
+            const int pi = ji < (uint32_t)N ? min((int)w.pos[ji], P - 1) : 0, pk = jk < (uint32_t)N ? min((int)w.pos[jk], P - 1) : 0;
+            if (ji >= (uint32_t)N || jk >= (uint32_t)N || ji >= jk || w.job[pi] != ji || w.job[pk] != jk) {
                 ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1;
             } else {
                 const int ga = w.seg_grp[pi >> 6], gb = w.seg_grp[pk >> 6];
@@ -538,6 +837,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
                 w.load[ga] -= d; w.load[gb] += d;
                 w.cu[pi] = xk; w.cu[pk] = xi;
                 w.job[pi] = jk; w.job[pk] = ji;
+                w.pos[ji] = (uint32_t)pk; w.pos[jk] = (uint32_t)pi;
                 asg[ji] = gb; asg[jk] = ga;
                 if (o.applied_log)
                     o.applied_log[(size_t)s * max_passes + ctrl->passes] =
@@ -547,7 +847,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
         }
     }
     __syncthreads();
-    g_prep_pass(w, o, s, N, M, max_passes, last_launch != 0, &s_ntask);
+    g_prep_pass(w, o, s, N, M, max_passes, last_launch != 0, true, &s_ntask);
 }
 
 }  // namespace
@@ -571,6 +871,7 @@ hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int 
     const int launches = max_passes < kMaxPassLaunches ? max_passes : kMaxPassLaunches;
     for (int i = 0; i < launches; i++) {
         grid_eval_kernel<<<dim3(kEvalGrid, S), dim3(kEvalBlock), 0, st>>>(N, M, workspace);
+        grid_flag_kernel<<<dim3(kFlagGrid, S), dim3(kFlagBlock), 0, st>>>(N, M, workspace);
         const int last = (i == launches - 1 && launches < max_passes) ? 1 : 0;
         if (dtype == MMBP_I32)
             grid_select_kernel<int32_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int32_t *)cost, N, M, cap, max_passes,

@@ -25,7 +25,7 @@ const char *mmbp_strerror(int code)
     case MMBP_EINVAL: return "invalid argument (null pointer, non-positive size, bad dtype, negative max_passes or unknown policy)";
     case MMBP_EINFEASIBLE: return "infeasible: N > M * cap";
     case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64, assigned simulator N <= 8192)";
-    case MMBP_EWORKSPACE: return "workspace missing or too small (see mmbp_workspace_bytes)";
+    case MMBP_EWORKSPACE: return "workspace missing, too small or not 256-byte aligned (see mmbp_workspace_bytes)";
     case MMBP_EHIP: return g_hip_err;
     default: return "unknown error code";
     }
@@ -63,6 +63,7 @@ static int local_search_impl(int prune, const void *cost, int dtype, int S, int 
     if ((int64_t)N > (int64_t)M * (int64_t)cap) return MMBP_EINFEASIBLE;
     const size_t need = mmbp_workspace_bytes(S, N, M);
     if (need > 0 && (!workspace || workspace_bytes < need)) return MMBP_EWORKSPACE;
+    if (need > 0 && ((uintptr_t)workspace & 255u) != 0) return MMBP_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
 
     // The first path writes a status for every scenario: final where it can search the scenario
