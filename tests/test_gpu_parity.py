@@ -204,6 +204,32 @@ def test_ls_multi_workgroup_path_batch(oracle):
     compare_ls(g, o, label="multi-workgroup batch")
 
 
+def test_ls_multi_workgroup_moves_in_place(oracle):
+    """Multi-workgroup path, uneven client sizes and slack capacity: a run of moves (the layout is
+    updated in place, rebuilt only when the target client's slots are full) mixed with swaps."""
+    rng = np.random.default_rng(78)
+    S, N, M, cap = 2, 14000, 6, 2600
+    cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=30000, dtype=np.int32)
+    say(f"ls multi-workgroup moves S={S} N={N} M={M}")
+    o = oracle.local_search(cost, assign, M, cap, 30, want_log=True)
+    g = gpu_local_search(cost, assign, M, cap, 30)
+    compare_ls(g, o, label="multi-workgroup moves")
+    moves = int((o["log"][o["log"] >= 0] < N * M).sum())
+    assert moves >= 10, moves                      # the case must exercise the move path
+
+
+def test_ls_multi_workgroup_heavy_ties(oracle):
+    """Multi-workgroup path with costs from a tiny range: almost every candidate ties, so the
+    lowest-id rule decides every pass (full scan and pruned scan)."""
+    rng = np.random.default_rng(79)
+    S, N, M, cap = 2, 14000, 7, 2100
+    cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=4, dtype=np.int32)
+    say(f"ls multi-workgroup ties S={S} N={N} M={M}")
+    o = oracle.local_search(cost, assign, M, cap, 10, want_log=True)
+    compare_ls(gpu_local_search(cost, assign, M, cap, 10), o, label="multi-workgroup ties")
+    compare_ls(gpu_local_search(cost, assign, M, cap, 10, pruned=True), o, label="multi-workgroup ties, pruned")
+
+
 # ------------------------------------------------------------------ pruned scan (identical results)
 def test_ls_pruned_small_random(oracle):
     """The pruned scan must return exactly what the full search returns (the oracle is the full
