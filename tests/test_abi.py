@@ -57,6 +57,8 @@ def test_host_side_argument_validation():
     if need:
         assert ls(one, 1, 1, 65536, 64, 1024, 1, one, one, one, one, None, None, one, None, 0, None) == api.EWORKSPACE
         assert ls(one, 1, 1, 65536, 64, 1024, 1, one, one, one, one, None, None, one, one, need - 1, None) == api.EWORKSPACE
+        odd = C.c_void_p(256 + 16)                 # the base must be 256-byte aligned
+        assert ls(one, 1, 1, 65536, 64, 1024, 1, one, one, one, one, None, None, one, odd, need, None) == api.EWORKSPACE
     lb = lib.mmbp_lower_bound
     assert lb(None, 0, 1, 4, 2, None, 0, 0, one, one, None) == api.EINVAL
     assert lb(one, 0, 1, 4, 0, None, 0, 0, one, one, None) == api.EINVAL
