@@ -481,17 +481,22 @@ __device__ __forceinline__ SwapCtx swap_ctx(const GWs &w, const uint32_t *ld, co
 }
 
 // A pair (critical job e, job f of client g) reaches V exactly when its key |cu_e - (cu_f - sh)|
-// lies in [klo, klo + span], i.e. max(others, (l_g + l_star + key) >> 1) == V.  False: no key does.
+// lies in [klo, klo + span], i.e. max(others, (l_g + l_star + key) >> 1) == V.  False: no key does
+// (the range returned then is meaningless).
 __device__ __forceinline__ bool key_range(const SwapCtx &c, int g, uint32_t &sh, uint32_t &klo, uint32_t &span)
 {
     const uint32_t lg = c.ld[g], lsum = lg + c.lstar, oth = others_max(c.top, g, c.astar);
     sh = lg - c.lstar;
-    klo = 0; span = 0;
-    if (oth > c.V || lsum > 2u * c.V + 1u) return false;
-    const uint32_t khi = min(2u * c.V + 1u - lsum, kKeyLimit - 1u);
-    klo = (oth == c.V || lsum > 2u * c.V) ? 0u : 2u * c.V - lsum;
-    span = khi - klo;
-    return klo <= khi;
+    // (lsum + key) >> 1 <= V  <=>  key <= 2V + 1 - lsum; compared in 64 bits: the difference can be
+    // negative (a client too loaded for any swap with the critical one to reach V)
+    const long long room = 2ll * (long long)c.V + 1ll - (long long)lsum;
+    const bool reach = oth <= c.V && room >= 0;
+    const uint32_t khi = (uint32_t)min(max(room, 0ll), (long long)(kKeyLimit - 1u));
+    klo = (oth == c.V || room < 1) ? 0u : (uint32_t)(room - 1);     // below V the value must be exactly V
+    const bool some = reach && klo <= khi;
+    klo = some ? klo : 0u;                                          // none: the caller masks on the result
+    span = some ? khi - klo : 0u;
+    return some;
 }
 
 // The four critical jobs of lowest index (above `last` when `after`), ascending, kNoJob32 for
@@ -788,8 +793,8 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
                 uint32_t sh, klo, span;
                 const bool ok = key_range(sc, w.seg_grp[p >> 6], sh, klo, span);
                 s_fx[tid] = w.cu[p] - sh;
-                s_fklo[tid] = ok ? klo : 1u;               // not ok: empty range
-                s_fspan[tid] = ok ? span : 0u;
+                s_fklo[tid] = klo;
+                s_fspan[tid] = span;                     // not ok: masked by the job below
                 s_fjob[tid] = ok ? w.job[p] : kNoJob32;
             }
             __syncthreads();

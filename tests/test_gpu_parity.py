@@ -230,6 +230,21 @@ def test_ls_multi_workgroup_heavy_ties(oracle):
     compare_ls(gpu_local_search(cost, assign, M, cap, 10, pruned=True), o, label="multi-workgroup ties, pruned")
 
 
+@pytest.mark.parametrize("seed", [1000, 1008])
+def test_ls_multi_workgroup_client_out_of_reach(oracle, seed):
+    """Multi-workgroup path, few clients, costs 0..3: loads end up within a few units of each other,
+    so for some client NO swap with the critical client can reach the best value (its load plus the
+    makespan exceeds twice that value), while thousands of rows of the other clients tie.  The
+    selection must give such a client no partners (regression: a wrapping difference once did)."""
+    rng = np.random.default_rng(seed)
+    S, N, M, cap = 3, 22000, 4, 5500
+    cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=3, dtype=np.int32)
+    say(f"ls multi-workgroup out-of-reach client seed={seed}")
+    o = oracle.local_search(cost, assign, M, cap, 30, want_log=True)
+    compare_ls(gpu_local_search(cost, assign, M, cap, 30), o, label=f"out of reach, seed {seed}")
+    compare_ls(gpu_local_search(cost, assign, M, cap, 30, pruned=True), o, label=f"out of reach, pruned, seed {seed}")
+
+
 # ------------------------------------------------------------------ pruned scan (identical results)
 def test_ls_pruned_small_random(oracle):
     """The pruned scan must return exactly what the full search returns (the oracle is the full
