@@ -3,7 +3,7 @@ modes, the FCFS simulator and the assigned-queue simulator, each against the CPU
 import numpy as np
 import pytest
 
-from paper_2502_15763_amd import workloads as W
+from paper_2502_15763_amd import api, workloads as W
 from gpu_util import (say, gpu_local_search, compare_ls, gpu_online_sim, gpu_online_sim_assigned, compare_sim)
 
 pytestmark = pytest.mark.gpu
@@ -46,6 +46,27 @@ def test_ls_random_large_shapes(oracle):
         say(f"ls random large case {t}: N={N} M={M} cap={cap} passes={mp} pruned={pruned}")
         o = oracle.local_search(cost, asg, M, cap, mp, want_log=True)
         compare_ls(gpu_local_search(cost, asg, M, cap, mp, pruned=pruned), o, label=f"large case {t}")
+
+
+def test_ls_random_multi_workgroup_shapes(oracle):
+    """Shapes of the multi-workgroup path only: many passes, slack and tight capacity, tiny cost
+    ranges (heavy ties, clients within a few units of each other), uneven client sizes."""
+    rng = np.random.default_rng(15)
+    for t in range(24):
+        N = int(rng.choice([13000, 14000, 17001, 22000, 30000]))
+        M = int(rng.integers(2, 65))
+        base = -(-N // M)
+        cap = base if rng.random() < 0.3 else int(base + rng.integers(1, 200))
+        hi = int(rng.choice([2, 3, 50, 5000, 200000]))
+        S = int(rng.integers(1, 4))
+        cost, asg = W.random_offline(rng, S, N, M, cap, cost_hi=hi, dtype=np.int64 if rng.random() < 0.3 else np.int32,
+                                     start="rr" if rng.random() < 0.4 else "random")
+        mp = int(rng.choice([3, 12, 40]))
+        pruned = bool(rng.random() < 0.4)
+        assert api.mmbp_workspace_bytes(S, N, M) > 0           # not an LDS-resident shape
+        say(f"ls random multi-workgroup case {t}: N={N} M={M} cap={cap} hi={hi} S={S} passes={mp} pruned={pruned}")
+        o = oracle.local_search(cost, asg, M, cap, mp, want_log=True)
+        compare_ls(gpu_local_search(cost, asg, M, cap, mp, pruned=pruned), o, label=f"multi-workgroup case {t}")
 
 
 def test_sim_random_parameters(oracle):
