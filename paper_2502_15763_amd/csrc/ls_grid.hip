@@ -226,7 +226,11 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
     // Two rounds: the first task of every pair (a full row block x a full column chunk unless the
     // pair is smaller), then the remainders, so that the stride loop of the evaluation gives every
     // workgroup the same number of large tasks.
+    __shared__ int s_more;                               // some pair has more than one task
+    if (tid == 0) s_more = 0;
+    __syncthreads();
     for (int round = 0; round < 2; round++) {
+        if (round == 1 && !s_more) break;                // the usual case with balanced clients: one task per pair
         for (int q0 = 0; q0 < M * M; q0 += kSelBlock) {  // uniform trip count: the waves cooperate below
             const int q = q0 + tid;
             const int g = q / M, b = q - g * M;
@@ -239,6 +243,7 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
             const int ncc = (ncols + kColChunk - 1) / kColChunk;
             const int all = (nx > 0 && ny > 0) ? nrb * ncc : 0;
             const int mine = round == 0 ? min(all, 1) : max(all - 1, 0);
+            if (round == 0 && all > 1) s_more = 1;
             int incl = mine;                              // one slot reservation per wave
             for (int off = 1; off < kWave; off <<= 1) {
                 const int up = __shfl_up(incl, off);
