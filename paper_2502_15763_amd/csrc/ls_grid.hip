@@ -141,36 +141,67 @@ struct OutPtrs {
 // ---- pieces of the one-workgroup kernels (kSelBlock threads, all call) ----
 
 // group the jobs by client: layout starts, segment -> client map, feasible move targets, pair count
+// (s_cursor: M ints, s_start: M + 1 ints of LDS; all threads of the workgroup call)
 template <typename CostT>
 __device__ void g_build_layout(const GWs &w, const CostT *__restrict__ c, const int32_t *asg, int N, int M, int cap,
-                               int *s_cursor)
+                               int *s_cursor, int *s_start)
 {
-    const int tid = threadIdx.x;
-    if (tid == 0) {
-        int pos = 0, nf = 0;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int pcap = w.pmax & ~63;                        // the blocks are 64 slots wide and end inside the layout
+    if (tid < kWave) {
+        // wave 0: exclusive prefix of the clients' slot counts, 64 clients per step
+        int running = 0, nf = 0;
         unsigned long long sq = 0;
-        for (int g = 0; g < M; g++) {
-            w.gstart[g] = pos;
-            const int n = w.cnt[g];
-            pos += min((n + 63) >> 6, (w.pmax - pos) >> 6) * 64;
-            if (n < cap) w.feas[nf++] = g;
+        for (int j0 = 0; j0 < M; j0 += kWave) {
+            const int j = j0 + lane;
+            const int n = j < M ? min(max(w.cnt[j], 0), N) : 0;
+            const int slots = ((n + 63) >> 6) * 64;
+            int incl = slots;
+            for (int off = 1; off < kWave; off <<= 1) {
+                const int up = __shfl_up(incl, off);
+                if (lane >= off) incl += up;
+            }
+            const int start = min(running + incl - slots, pcap);
+            if (j < M) { s_start[j] = start; w.gstart[j] = start; }
+            running += __builtin_amdgcn_readlane(incl, kWave - 1);
+            const bool ok = j < M && n < cap;             // move targets, ascending
+            const unsigned long long m = __ballot(ok);
+            if (ok) w.feas[nf + __popcll(m & ((1ull << lane) - 1ull))] = j;
+            nf += __popcll(m);
             sq += (unsigned long long)n * (unsigned long long)n;
         }
-        w.gstart[M] = pos;
-        w.ctrl->P = pos;
-        w.ctrl->nfeas = nf;
-        w.ctrl->pairs_per_scan = ((unsigned long long)N * (unsigned long long)N - sq) / 2ull;
+        for (int off = 32; off >= 1; off >>= 1) sq += __shfl_xor(sq, off);
+        if (lane == 0) {
+            const int P = min(running, pcap);
+            s_start[M] = P; w.gstart[M] = P;
+            w.ctrl->P = P;
+            w.ctrl->nfeas = nf;
+            w.ctrl->pairs_per_scan = ((unsigned long long)N * (unsigned long long)N - sq) / 2ull;
+        }
     }
     for (int j = tid; j < M; j += kSelBlock) s_cursor[j] = 0;
     __syncthreads();
-    const int P = min(w.ctrl->P, w.pmax);
-    for (int g = 0; g < M; g++)                       // segment -> client
-        for (int sg = (w.gstart[g] >> 6) + tid; sg < (w.gstart[g + 1] >> 6); sg += kSelBlock) w.seg_grp[sg] = (uint8_t)g;
-    for (int p = tid; p < P; p += kSelBlock) { w.cu[p] = kPad; w.job[p] = kNoJob32; }
+    const int P = s_start[M];
+    for (int sg = tid; sg < (P >> 6); sg += kSelBlock) {  // segment -> client: the last client starting at or before it
+        const int pos = sg << 6;                          // (clients without jobs share a start with their successor)
+        int lo = 0, hi = M;                               // first client whose start exceeds pos
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (s_start[mid] <= pos) lo = mid + 1; else hi = mid;
+        }
+        w.seg_grp[sg] = (uint8_t)max(lo - 1, 0);
+    }
+    {
+        uint4 *cu4 = (uint4 *)w.cu, *jb4 = (uint4 *)w.job;
+        for (int q = tid; q < (P >> 2); q += kSelBlock) {
+            cu4[q] = make_uint4(kPad, kPad, kPad, kPad);
+            jb4[q] = make_uint4(kNoJob32, kNoJob32, kNoJob32, kNoJob32);
+        }
+    }
     __syncthreads();
     for (int i = tid; i < N; i += kSelBlock) {
         const int a = asg[i];
-        const int p = w.gstart[a] + atomicAdd(&s_cursor[a], 1);
+        const int p = s_start[a] + atomicAdd(&s_cursor[a], 1);
         if (p < P) { w.cu[p] = 2u * (uint32_t)c[i] + kBias; w.job[p] = (uint32_t)i; }
         w.pos[i] = (uint32_t)min(p, P - 1);
     }
@@ -286,7 +317,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
     const int32_t *asg = assign_all + (size_t)s * N;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     __shared__ long long s_load[MMBP_MAX_M];
-    __shared__ int s_cnt[MMBP_MAX_M];
+    __shared__ int s_cnt[MMBP_MAX_M], s_start[MMBP_MAX_M + 1];
     __shared__ unsigned long long s_wsum[kSelWaves], s_wmax[kSelWaves];
     __shared__ int s_bad_cost, s_bad_assign, s_ntask;
     __shared__ long long s_T0;
@@ -348,7 +379,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
     }
     for (int j = tid; j < M; j += kSelBlock) { w.load[j] = s_load[j]; w.cnt[j] = s_cnt[j]; }
     __syncthreads();
-    g_build_layout<CostT>(w, c, asg, N, M, cap, s_cnt /* reused as cursors */);
+    g_build_layout<CostT>(w, c, asg, N, M, cap, s_cnt /* reused as cursors */, s_start);
     {
         uint4 *rk4 = (uint4 *)(w.rowkey < w.rowkey_other ? w.rowkey : w.rowkey_other);   // both buffers
         for (int q = tid; q < (w.pstride >> 1); q += kSelBlock) rk4[q] = make_uint4(kInf, kInf, kInf, kInf);
@@ -626,7 +657,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
     const CostT *c = cost_all + (size_t)s * N;
     int32_t *asg = assign_all + (size_t)s * N;
     const int tid = threadIdx.x, lane = tid & 63;
-    __shared__ int s_cursor[MMBP_MAX_M];
+    __shared__ int s_cursor[MMBP_MAX_M], s_start[MMBP_MAX_M + 1];
     __shared__ uint32_t s_ld[MMBP_MAX_M];
     __shared__ int s_feas[MMBP_MAX_M];
     __shared__ int s_ntask, s_rebuild;
@@ -709,7 +740,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
             }
         }
         __syncthreads();
-        if (s_rebuild) g_build_layout<CostT>(w, c, asg, N, M, cap, s_cursor);
+        if (s_rebuild) g_build_layout<CostT>(w, c, asg, N, M, cap, s_cursor, s_start);
         else if (tid < kWave) {                          // move targets: clients below the cap, ascending
             int nf = 0;
             for (int j0 = 0; j0 < M; j0 += kWave) {
