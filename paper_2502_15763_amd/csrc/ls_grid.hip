@@ -33,7 +33,9 @@ constexpr int kFlagBlock = 256;          // grid_flag_kernel: kFlagGrid workgrou
 #endif
 constexpr int kFlagGrid = MMBP_GRID_FLAG_BLOCKS;
 static_assert(kFlagGrid <= 64, "one wave of the selection kernel combines the workgroups of grid_flag_kernel");
-constexpr int kColChunk = 1024;          // columns staged in LDS per task
+constexpr int kColChunk = 1024;          // columns staged in LDS per task, at most
+constexpr int kMinColChunk = 128;        // the host picks the chunk (a power of two in between) so that few clients still
+                                         // give the evaluation enough tasks to fill the chip
 constexpr int kRowBlockSegs = (kEvalBlock / kWave) * kRMax;   // 16 segments = 1024 rows per task
 constexpr int kMaxPassLaunches = 4096;
 constexpr uint32_t kNoJob32 = 0xFFFFFFFFu;
@@ -48,7 +50,7 @@ struct GCtrl {
     uint32_t vswap, vmove;
     uint32_t bjob[4];                          // first batch of a swap selection (grid_flag_kernel)
     Top3 top;
-    int P, nfeas, ntask, passes, status, stop, iters, prune, rk;
+    int P, nfeas, ntask, passes, status, stop, iters, prune, rk, cchunk;
 };
 
 struct GTask {
@@ -78,7 +80,7 @@ __host__ __device__ inline GLayout grid_layout(int N, int M)
     GLayout g;
     g.pmax = N + 64 * M;
     g.pstride = (g.pmax + 63) & ~63;
-    g.tmax = (g.pmax / 1024 + M) * (N / 1024 + M);
+    g.tmax = (g.pmax / 1024 + M) * (N / kMinColChunk + M);
     size_t o = 0;
     g.ctrl = o; o += up256(sizeof(GCtrl));
     g.load = o; o += up256(8 * (size_t)M);
@@ -251,6 +253,7 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
     __shared__ int s_cn[MMBP_MAX_M], s_gs[MMBP_MAX_M];
     for (int j = tid; j < M; j += kSelBlock) { s_cn[j] = w.cnt[j]; s_gs[j] = w.gstart[j]; }
     const int prune = ctrl->prune;
+    const int cchunk = min(max(ctrl->cchunk, kMinColChunk), kColChunk) & ~7;
     __syncthreads();
     // task table: every unordered pair of non-empty clients once, the critical client as columns
     const int astar = min(max(ctrl->top.j0, 0), M - 1);
@@ -271,7 +274,7 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
             const int segx = (nx + 63) >> 6;
             const int nrb = (segx + kRowBlockSegs - 1) / kRowBlockSegs;
             const int ncols = (ny + 7) & ~7;
-            const int ncc = (ncols + kColChunk - 1) / kColChunk;
+            const int ncc = (ncols + cchunk - 1) / cchunk;
             const int all = (nx > 0 && ny > 0) ? nrb * ncc : 0;
             const int mine = round == 0 ? min(all, 1) : max(all - 1, 0);
             if (round == 0 && all > 1) s_more = 1;
@@ -292,8 +295,8 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
                     GTask e;
                     e.xy = (uint32_t)X | ((uint32_t)Y << 8) | ((uint32_t)min(kRowBlockSegs, segx - rb * kRowBlockSegs) << 16);
                     e.xrow0 = (uint32_t)(s_gs[X] + rb * kRowBlockSegs * 64);
-                    e.ycol0 = (uint32_t)(s_gs[Y] + cc * kColChunk);
-                    e.yncols = (uint32_t)min(kColChunk, ncols - cc * kColChunk);
+                    e.ycol0 = (uint32_t)(s_gs[Y] + cc * cchunk);
+                    e.yncols = (uint32_t)min(cchunk, ncols - cc * cchunk);
                     w.tasks[slot++] = e;
                 }
         }
@@ -307,7 +310,7 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
 // ---- kernel 0: validation, narrowing decision, layout, first pass preparation ----
 template <typename CostT>
 __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__restrict__ cost_all, int N, int M, int cap,
-                                                               int max_passes, int prune, int32_t *assign_all,
+                                                               int max_passes, int prune, int cchunk, int32_t *assign_all,
                                                                OutPtrs o, void *workspace)
 {
     const int s = blockIdx.x;
@@ -326,7 +329,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
     if (tid == 0) {
         s_bad_cost = 0; s_bad_assign = 0;
         ctrl->passes = 0; ctrl->status = MMBP_ST_OK; ctrl->stop = 0; ctrl->evals = 0; ctrl->iters = 0; ctrl->ntask = 0;
-        ctrl->prune = prune; ctrl->rk = 0;
+        ctrl->prune = prune; ctrl->rk = 0; ctrl->cchunk = cchunk;
     }
     __syncthreads();
     {
@@ -901,17 +904,26 @@ hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int 
                           hipStream_t st)
 {
     OutPtrs o{load_out, makespan_out, passes_out, status_out, evals_out, applied_log};
+    // Tasks are row blocks of 1024 x column chunks.  With few clients there are few client pairs:
+    // the chunk shrinks until a pass has about a thousand tasks (estimated for balanced clients),
+    // and the evaluation gets no more workgroups than it can use.
+    const long long avg = (N + M - 1) / M, pairs = prune ? (long long)(M - 1) : (long long)M * (M - 1) / 2;
+    auto est_tasks = [&](int chunk) { return pairs * ((avg + 1023) / 1024) * ((avg + chunk - 1) / chunk); };
+    int cchunk = kColChunk;
+    while (cchunk > kMinColChunk && est_tasks(cchunk) < 1024) cchunk >>= 1;
+    const long long want = est_tasks(cchunk) * 3 / 2 + M;
+    const int egrid = want < 64 ? 64 : want < kEvalGrid ? (int)want : kEvalGrid;
     if (dtype == MMBP_I32)
         grid_stage_kernel<int32_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int32_t *)cost, N, M, cap, max_passes,
-                                                                       prune, assign, o, workspace);
+                                                                       prune, cchunk, assign, o, workspace);
     else
         grid_stage_kernel<int64_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int64_t *)cost, N, M, cap, max_passes,
-                                                                       prune, assign, o, workspace);
+                                                                       prune, cchunk, assign, o, workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int launches = max_passes < kMaxPassLaunches ? max_passes : kMaxPassLaunches;
     for (int i = 0; i < launches; i++) {
-        grid_eval_kernel<<<dim3(kEvalGrid, S), dim3(kEvalBlock), 0, st>>>(N, M, workspace);
+        grid_eval_kernel<<<dim3(egrid, S), dim3(kEvalBlock), 0, st>>>(N, M, workspace);
         grid_flag_kernel<<<dim3(kFlagGrid, S), dim3(kFlagBlock), 0, st>>>(N, M, workspace);
         const int last = (i == launches - 1 && launches < max_passes) ? 1 : 0;
         if (dtype == MMBP_I32)
