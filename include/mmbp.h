@@ -60,10 +60,14 @@ int mmbp_version(void);
 const char *mmbp_strerror(int code);
 
 /*
- * Scratch needed by mmbp_local_search for these shapes (bytes of device memory; the base
- * must be 256-byte aligned).  Returns 0 when every scenario is searched entirely out of the
- * LDS of one workgroup; larger N uses the multi-workgroup path whose layout, per-row minima
- * and global argmin slots live in the workspace.
+ * Scratch for mmbp_local_search with these shapes (bytes of device memory; the base must be
+ * 256-byte aligned).  0: every scenario is searched entirely out of the LDS of one workgroup.
+ * Otherwise the call runs the multi-workgroup path, whose layout, per-row minima and task table
+ * live in the workspace.  That path is REQUIRED when a scenario does not fit the LDS (larger N:
+ * without the workspace the call returns MMBP_EWORKSPACE) and merely PREFERRED for a few large
+ * scenarios that would leave most of the chip idle (at most 128 scenarios and a predicted factor
+ * of two): there a call without workspace, or with one that is too small or misaligned, still
+ * runs, on the one-workgroup path.  Results do not depend on the path.
  */
 size_t mmbp_workspace_bytes(int S, int N, int M);
 
@@ -99,7 +103,8 @@ int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M,
  *              infeasible moves, not counting b == assign[i] nor same-client pairs
  * applied_log  [S,max_passes] uint64, nullable: id applied in each pass (rest untouched)
  * status_out   [S] int32.  For MMBP_ST_BAD_*: load/makespan/passes/evals are 0.
- * workspace    device scratch of at least mmbp_workspace_bytes(S,N,M) bytes (may be NULL if 0)
+ * workspace    device scratch of at least mmbp_workspace_bytes(S,N,M) bytes (may be NULL if that is 0, or
+ *              where the multi-workgroup path is only preferred, see mmbp_workspace_bytes)
  */
 int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
                       int32_t *assign, int64_t *load_out, int64_t *makespan_out,

@@ -217,7 +217,7 @@ def online_iter_sim_assigned(in_len, out_len, assign, params: dict, finish_us, t
 
 
 def run_local_search(cost, assign0, M, cap, max_passes, want_log=False, stream=None, raise_on_error=True,
-                     pruned=False):
+                     pruned=False, use_workspace=True):
     torch = _torch()
     dev = cost.device
     S, N = cost.shape
@@ -230,7 +230,7 @@ def run_local_search(cost, assign0, M, cap, max_passes, want_log=False, stream=N
     if want_log and max_passes > 0:
         log = torch.full((S, max_passes), -1, dtype=torch.int64, device=dev)
     ws_bytes = mmbp_workspace_bytes(S, N, M)
-    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev) if ws_bytes else None
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev) if ws_bytes and use_workspace else None
     fn = mmbp_local_search_pruned if pruned else mmbp_local_search
     rc = fn(cost, M, cap, max_passes, out["assign"], out["load"], out["makespan"], out["passes"],
             out["status"], evals_out=out["evals"], applied_log=log, workspace=ws, stream=stream,

@@ -31,10 +31,23 @@ const char *mmbp_strerror(int code)
     }
 }
 
+// A few large scenarios leave most of the chip idle on the one-workgroup-per-scenario path, where a
+// pass of a scenario costs about 4 us + 14 ns per 1000 swap candidates on its CU; the multi-workgroup
+// path costs about 19 us per pass plus 0.3 us + 0.11 ns per 1000 candidates per scenario (both
+// measured on MI355X).  It is preferred where this predicts at least a factor of two.
+static bool prefer_multi_workgroup(int S, int N, int M)
+{
+    if (S > 128) return false;
+    const double pairs = 0.5 * (double)N * (double)N * (1.0 - 1.0 / (double)M);
+    const double one_wg = 4.0 + 14e-6 * pairs;
+    const double multi_wg = 19.0 + (double)S * (0.3 + 0.11e-6 * pairs);
+    return 2.0 * multi_wg < one_wg;
+}
+
 size_t mmbp_workspace_bytes(int S, int N, int M)
 {
     if (S <= 0 || N <= 0 || M <= 0 || N > MMBP_MAX_N || M > MMBP_MAX_M) return 0;
-    if (mmbp::ls_lds_fits(N, M)) return 0;
+    if (mmbp::ls_lds_fits(N, M) && !prefer_multi_workgroup(S, N, M)) return 0;
     return mmbp::ls_grid_workspace_bytes(S, N, M);
 }
 
@@ -62,14 +75,16 @@ static int local_search_impl(int prune, const void *cost, int dtype, int S, int 
     if (N > MMBP_MAX_N || M > MMBP_MAX_M) return MMBP_EUNSUPPORTED;
     if ((int64_t)N > (int64_t)M * (int64_t)cap) return MMBP_EINFEASIBLE;
     const size_t need = mmbp_workspace_bytes(S, N, M);
-    if (need > 0 && (!workspace || workspace_bytes < need)) return MMBP_EWORKSPACE;
-    if (need > 0 && ((uintptr_t)workspace & 255u) != 0) return MMBP_EWORKSPACE;
+    const bool ws_ok = need > 0 && workspace && workspace_bytes >= need && ((uintptr_t)workspace & 255u) == 0;
+    const bool fits = mmbp::ls_lds_fits(N, M);
+    if (!fits && !ws_ok) return MMBP_EWORKSPACE;
+    const bool one_wg = fits && !ws_ok;      // also the fallback when the optional workspace is not given
     hipStream_t st = (hipStream_t)stream;
 
     // The first path writes a status for every scenario: final where it can search the scenario
     // exactly, pending otherwise; the 64-bit kernel then takes the pending ones.
     hipError_t e;
-    if (mmbp::ls_lds_fits(N, M)) {
+    if (one_wg) {
         e = mmbp::launch_ls_lds(cost, dtype, S, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out,
                                 evals_out, applied_log, status_out, st);
         if (e != hipSuccess) return fail_hip(e, "mmbp_local_search(lds)");

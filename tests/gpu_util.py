@@ -19,11 +19,13 @@ def u64(t):
     return t.cpu().numpy().view(np.uint64)
 
 
-def gpu_local_search(cost, assign0, M, cap, max_passes, want_log=True, pruned=False):
+def gpu_local_search(cost, assign0, M, cap, max_passes, want_log=True, pruned=False, use_workspace=True):
+    """use_workspace=False: no workspace is passed, which keeps a shape that fits the LDS on the
+    one-workgroup path even where the library would prefer the multi-workgroup one."""
     import torch
     from paper_2502_15763_amd import api
     r = api.run_local_search(to_dev(cost), to_dev(assign0.astype(np.int32)), M, cap, max_passes, want_log=want_log,
-                             pruned=pruned)
+                             pruned=pruned, use_workspace=use_workspace)
     torch.cuda.synchronize()
     out = dict(rc=r["rc"], assign=r["assign"].cpu().numpy(), load=r["load"].cpu().numpy(),
                makespan=r["makespan"].cpu().numpy(), passes=r["passes"].cpu().numpy(), evals=u64(r["evals"]),

@@ -42,8 +42,10 @@ def test_ls_shapes_between_64_and_156_kb_of_lds(oracle):
         cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=50000, dtype=np.int32, start="rr")
         say(f"ls large-LDS shapes S={S} N={N} M={M}")
         o = oracle.local_search(cost, assign, M, cap, passes, want_log=True)
-        g = gpu_local_search(cost, assign, M, cap, passes)
+        g = gpu_local_search(cost, assign, M, cap, passes, use_workspace=False)       # one workgroup per scenario
         compare_ls(g, o, label=f"large LDS N={N} M={M}")
+        g = gpu_local_search(cost, assign, M, cap, passes)                            # the library's choice of path
+        compare_ls(g, o, label=f"large LDS N={N} M={M}, with workspace")
 
 
 def test_ls_maximum_sizes(oracle):
@@ -179,6 +181,8 @@ def test_ls_config3_slack_converged(oracle):
     o = oracle.local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, want_log=True)
     g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes)
     compare_ls(g, o, label="c3 slack")
+    g = gpu_local_search(c.cost, c.assign0, c.M, c.cap, c.max_passes, use_workspace=False)
+    compare_ls(g, o, label="c3 slack, one workgroup per scenario")
 
 
 @pytest.mark.parametrize("slack,passes", [(0, 12), (256, 12)])
@@ -243,6 +247,38 @@ def test_ls_multi_workgroup_client_out_of_reach(oracle, seed):
     o = oracle.local_search(cost, assign, M, cap, 30, want_log=True)
     compare_ls(gpu_local_search(cost, assign, M, cap, 30), o, label=f"out of reach, seed {seed}")
     compare_ls(gpu_local_search(cost, assign, M, cap, 30, pruned=True), o, label=f"out of reach, pruned, seed {seed}")
+
+
+def test_ls_few_large_scenarios_take_either_path(oracle):
+    """Shapes that fit one workgroup's LDS but leave most of the chip idle: with the optional
+    workspace the multi-workgroup path runs, without it the one-workgroup path; both must give the
+    oracle's result, and a workspace that is too small or misaligned only selects the fallback."""
+    import torch
+    from paper_2502_15763_amd import api
+    rng = np.random.default_rng(91)
+    for (S, N, M, cap, passes) in [(1, 4096, 16, 256, 120), (3, 5000, 10, 520, 60), (12, 3500, 7, 500, 40)]:
+        assert api.mmbp_workspace_bytes(S, N, M) > 0 and api.mmbp_workspace_bytes(1024, N, M) == 0
+        cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=20000, dtype=np.int32)
+        say(f"ls either path S={S} N={N} M={M}")
+        o = oracle.local_search(cost, assign, M, cap, passes, want_log=True)
+        for pruned in (False, True):
+            compare_ls(gpu_local_search(cost, assign, M, cap, passes, pruned=pruned), o, label=f"multi-workgroup N={N} pruned={pruned}")
+            compare_ls(gpu_local_search(cost, assign, M, cap, passes, pruned=pruned, use_workspace=False), o,
+                       label=f"one workgroup N={N} pruned={pruned}")
+    # too small / misaligned workspace: not an error here, the one-workgroup path runs
+    S, N, M, cap = 1, 4096, 16, 256
+    cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=20000, dtype=np.int32)
+    o = oracle.local_search(cost, assign, M, cap, 20, want_log=True)
+    need = api.mmbp_workspace_bytes(S, N, M)
+    for ws in (torch.empty(need - 1, dtype=torch.uint8, device="cuda"), torch.empty(need + 256, dtype=torch.uint8, device="cuda")[16:]):
+        out = dict(assign=torch.from_numpy(assign).cuda(), load=torch.empty((S, M), dtype=torch.int64, device="cuda"),
+                   makespan=torch.empty(S, dtype=torch.int64, device="cuda"), passes=torch.empty(S, dtype=torch.int32, device="cuda"),
+                   status=torch.empty(S, dtype=torch.int32, device="cuda"))
+        rc = api.mmbp_local_search(torch.from_numpy(cost).cuda(), M, cap, 20, out["assign"], out["load"], out["makespan"],
+                                   out["passes"], out["status"], workspace=ws)
+        torch.cuda.synchronize()
+        assert rc == 0
+        assert np.array_equal(out["assign"].cpu().numpy(), o["assign"]) and np.array_equal(out["passes"].cpu().numpy(), o["passes"])
 
 
 # ------------------------------------------------------------------ pruned scan (identical results)

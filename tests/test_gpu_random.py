@@ -46,6 +46,9 @@ def test_ls_random_large_shapes(oracle):
         say(f"ls random large case {t}: N={N} M={M} cap={cap} passes={mp} pruned={pruned}")
         o = oracle.local_search(cost, asg, M, cap, mp, want_log=True)
         compare_ls(gpu_local_search(cost, asg, M, cap, mp, pruned=pruned), o, label=f"large case {t}")
+        if api.mmbp_workspace_bytes(1024, N, M) == 0:          # fits one workgroup's LDS: that path too
+            compare_ls(gpu_local_search(cost, asg, M, cap, mp, pruned=pruned, use_workspace=False), o,
+                       label=f"large case {t}, one workgroup per scenario")
 
 
 def test_ls_random_multi_workgroup_shapes(oracle):
