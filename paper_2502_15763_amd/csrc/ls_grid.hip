@@ -140,6 +140,13 @@ struct OutPtrs {
     uint64_t *evals_out, *applied_log;
 };
 
+// Layouts up to this many positions are scanned by the selection workgroup itself (a pass is then
+// two launches); larger ones get grid_flag_kernel.
+#ifndef MMBP_GRID_SMALL_LAYOUT
+#define MMBP_GRID_SMALL_LAYOUT 8192
+#endif
+inline bool grid_has_flag(int N, int M) { return grid_layout(N, M).pmax > MMBP_GRID_SMALL_LAYOUT; }
+
 // ---- pieces of the one-workgroup kernels (kSelBlock threads, all call) ----
 
 // group the jobs by client: layout starts, segment -> client map, feasible move targets, pair count
@@ -651,12 +658,16 @@ __global__ __launch_bounds__(kFlagBlock) void grid_flag_kernel(int N, int M, voi
 template <typename CostT>
 __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__restrict__ cost_all, int N, int M, int cap,
                                                                 int max_passes, int32_t *assign_all, OutPtrs o,
-                                                                void *workspace, int last_launch)
+                                                                void *workspace, int last_launch, int has_flag)
 {
     const int s = blockIdx.x;
     const GWs w = grid_ws(workspace, s, N, M);
     GCtrl *ctrl = w.ctrl;
     if (ctrl->stop) return;
+    if (!has_flag) {                                     // no grid_flag_kernel in this mode: its other duty
+        uint4 *o4 = (uint4 *)w.rowkey_other;
+        for (int q = threadIdx.x; q < (w.pstride >> 2); q += kSelBlock) o4[q] = make_uint4(kInf, kInf, kInf, kInf);
+    }
     const CostT *c = cost_all + (size_t)s * N;
     int32_t *asg = assign_all + (size_t)s * N;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -756,9 +767,27 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
             if (lane == 0) ctrl->nfeas = nf;
         }
     } else {
-        // a swap wins (see above); grid_flag_kernel has taken the first batch
+        // a swap wins (see above); the first batch was taken by grid_flag_kernel, or is taken here
         const SwapCtx sc = swap_ctx(w, s_ld, top, V, astar, P);
-        if (tid < kWave) {                               // combine what the workgroups of grid_flag_kernel found
+        uint32_t bjob[4], part[4], ji = kNoJob32, jk = kNoJob32;
+        if (!has_flag) {                                 // small layout: one workgroup scans it as fast as a launch takes
+            if (tid == 0) { s_flag.part[0] = s_flag.part[1] = s_flag.part[2] = s_flag.part[3] = s_flag.k0job = kNoJob32; s_flag.nflag = 0; }
+            lowest_four(w, sc, false, 0u, s_cand, bjob);  // (its barrier also publishes the reset of s_flag)
+            uint32_t bx[4];
+#pragma unroll
+            for (int r = 0; r < 4; r++) bx[r] = bjob[r] < (uint32_t)N ? w.cu[min((int)w.pos[bjob[r]], P - 1)] : kPad;
+            uint32_t pm[4] = {kNoJob32, kNoJob32, kNoJob32, kNoJob32}, k0 = kNoJob32, nf = 0;
+            scan_partners(w, sc, w.rowkey, bx, tid, kSelBlock, pm, k0, nf);
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                pm[r] = wave_min_u32(pm[r]);
+                if (lane == 0 && pm[r] != kNoJob32) atomicMin(&s_flag.part[r], pm[r]);
+            }
+            k0 = wave_min_u32(k0);
+            for (int off = 32; off >= 1; off >>= 1) nf += __shfl_xor(nf, off);
+            if (lane == 0 && k0 != kNoJob32) atomicMin(&s_flag.k0job, k0);
+            if (lane == 0 && nf) atomicAdd(&s_flag.nflag, nf);
+        } else if (tid < kWave) {                        // combine what the workgroups of grid_flag_kernel found
             FlagPart f;
             f.part[0] = f.part[1] = f.part[2] = f.part[3] = f.k0job = kNoJob32; f.nflag = 0;
             if (lane < kFlagGrid) f = w.fpart[lane];
@@ -776,9 +805,8 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
             g_finish(w, o, s, M);
             return;
         }
-        uint32_t bjob[4], part[4], ji = kNoJob32, jk = kNoJob32;
 #pragma unroll
-        for (int r = 0; r < 4; r++) { bjob[r] = ctrl->bjob[r]; part[r] = s_flag.part[r]; }
+        for (int r = 0; r < 4; r++) { if (has_flag) bjob[r] = ctrl->bjob[r]; part[r] = s_flag.part[r]; }
         bool found = false, early_done = false;
         auto decide = [&]() {
 #pragma unroll
@@ -922,16 +950,17 @@ hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int launches = max_passes < kMaxPassLaunches ? max_passes : kMaxPassLaunches;
+    const int has_flag = grid_has_flag(N, M) ? 1 : 0;
     for (int i = 0; i < launches; i++) {
         grid_eval_kernel<<<dim3(egrid, S), dim3(kEvalBlock), 0, st>>>(N, M, workspace);
-        grid_flag_kernel<<<dim3(kFlagGrid, S), dim3(kFlagBlock), 0, st>>>(N, M, workspace);
+        if (has_flag) grid_flag_kernel<<<dim3(kFlagGrid, S), dim3(kFlagBlock), 0, st>>>(N, M, workspace);
         const int last = (i == launches - 1 && launches < max_passes) ? 1 : 0;
         if (dtype == MMBP_I32)
             grid_select_kernel<int32_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int32_t *)cost, N, M, cap, max_passes,
-                                                                            assign, o, workspace, last);
+                                                                            assign, o, workspace, last, has_flag);
         else
             grid_select_kernel<int64_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int64_t *)cost, N, M, cap, max_passes,
-                                                                            assign, o, workspace, last);
+                                                                            assign, o, workspace, last, has_flag);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
