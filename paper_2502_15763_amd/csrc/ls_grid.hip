@@ -12,8 +12,10 @@
 //   grid_select_kernel  one workgroup: picks the lowest-id candidate of the best value exactly,
 //                       applies it, and prepares the next pass (top-3 loads, task table with the
 //                       critical client always on the column side).
-// The host enqueues min(max_passes, kMaxPassLaunches) such triples; once a scenario has stopped the
-// remaining launches return at once.
+// The host enqueues min(max_passes, kMaxPassLaunches) such triples (pairs for small layouts, which
+// the selection workgroup scans itself); once a scenario has stopped the remaining launches return
+// at once.  The column chunk of the tasks and the number of evaluation workgroups follow the number
+// of client pairs, so that few clients still fill the chip.
 #include "mmbp_dev.hpp"
 #include "ls_tile.hpp"
 
