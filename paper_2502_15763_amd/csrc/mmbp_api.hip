@@ -78,7 +78,9 @@ static int local_search_impl(int prune, const void *cost, int dtype, int S, int 
     const bool ws_ok = need > 0 && workspace && workspace_bytes >= need && ((uintptr_t)workspace & 255u) == 0;
     const bool fits = mmbp::ls_lds_fits(N, M);
     if (!fits && !ws_ok) return MMBP_EWORKSPACE;
-    const bool one_wg = fits && !ws_ok;      // also the fallback when the optional workspace is not given
+    // One workgroup per scenario: the fallback when the optional workspace is not given, and always
+    // for the pruned scan of a scenario that fits (its pass is about as short as three launches)
+    const bool one_wg = fits && (!ws_ok || prune != 0);
     hipStream_t st = (hipStream_t)stream;
 
     // The first path writes a status for every scenario: final where it can search the scenario
