@@ -242,20 +242,26 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     GCtrl *ctrl = w.ctrl;
     if (wave == 0) {
+        // (the control fields are fetched before the top-3 reduction and used after it, so that
+        // their latency overlaps with the loads of the reduction)
+        int iters = 0, stop = 0, passes = 0, rk = 0;
+        unsigned long long evals = 0, pairs = 0;
         if (lane == 0) {
-            const int iters = ctrl->iters + 1, stop = ctrl->stop, passes = ctrl->passes, rk = ctrl->rk;
-            const unsigned long long evals = ctrl->evals, pairs = ctrl->pairs_per_scan;
+            iters = ctrl->iters + 1; stop = ctrl->stop; passes = ctrl->passes; rk = ctrl->rk;
+            evals = ctrl->evals; pairs = ctrl->pairs_per_scan;
+        }
+        const Top3 t = wave_top3(w.load, M, lane);
+        if (lane == 0) {
             ctrl->iters = iters;
             if ((long long)iters > (long long)max_passes + 1) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
             else if (stop) { }
             else if (passes == max_passes || last_launch) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
             else ctrl->evals = evals + (unsigned long long)N * (unsigned long long)(M - 1) + pairs;
             ctrl->vswap = kInf; ctrl->vmove = kInf;
-            if (toggle) ctrl->rk = (rk & 1) ^ 1;         // the other buffer was reset by grid_flag_kernel
+            if (toggle) ctrl->rk = (rk & 1) ^ 1;         // the other buffer has been reset for the next pass
             *s_ntask = 0;
+            ctrl->top = t;
         }
-        const Top3 t = wave_top3(w.load, M, lane);
-        if (lane == 0) ctrl->top = t;
     }
     __syncthreads();
     if (ctrl->stop) { g_finish(w, o, s, M); return false; }
@@ -901,22 +907,26 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
             jk = s_later;
         }
         if (tid == 0) {
-            const int pi = ji < (uint32_t)N ? min((int)w.pos[ji], P - 1) : 0, pk = jk < (uint32_t)N ? min((int)w.pos[jk], P - 1) : 0;
-            if (ji >= (uint32_t)N || jk >= (uint32_t)N || ji >= jk || w.job[pi] != ji || w.job[pk] != jk) {
+            // (independent loads first: one thread, every dependent round trip to memory counts)
+            const bool valid = ji < (uint32_t)N && jk < (uint32_t)N && ji < jk;
+            const int passes = ctrl->passes;
+            const int pi = valid ? min((int)w.pos[ji], P - 1) : 0, pk = valid ? min((int)w.pos[jk], P - 1) : 0;
+            const uint32_t at_pi = w.job[pi], at_pk = w.job[pk], xi = w.cu[pi], xk = w.cu[pk];
+            const int ga = w.seg_grp[pi >> 6], gb = w.seg_grp[pk >> 6];
+            if (!valid || at_pi != ji || at_pk != jk) {
                 ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1;
             } else {
-                const int ga = w.seg_grp[pi >> 6], gb = w.seg_grp[pk >> 6];
-                const uint32_t xi = w.cu[pi], xk = w.cu[pk];
                 const long long d = (long long)((xi - kBias) >> 1) - (long long)((xk - kBias) >> 1);
-                w.load[ga] -= d; w.load[gb] += d;
+                w.load[ga] = (long long)s_ld[ga] - d;     // the loads of this path fit 32 bits: s_ld holds them exactly
+                w.load[gb] = (long long)s_ld[gb] + d;
                 w.cu[pi] = xk; w.cu[pk] = xi;
                 w.job[pi] = jk; w.job[pk] = ji;
                 w.pos[ji] = (uint32_t)pk; w.pos[jk] = (uint32_t)pi;
                 asg[ji] = gb; asg[jk] = ga;
                 if (o.applied_log)
-                    o.applied_log[(size_t)s * max_passes + ctrl->passes] =
+                    o.applied_log[(size_t)s * max_passes + passes] =
                         (uint64_t)N * (uint64_t)M + (uint64_t)ji * (uint64_t)N + (uint64_t)jk;
-                ctrl->passes += 1;
+                ctrl->passes = passes + 1;
             }
         }
     }
