@@ -67,7 +67,8 @@ const char *mmbp_strerror(int code);
  * without the workspace the call returns MMBP_EWORKSPACE) and merely PREFERRED for a few large
  * scenarios that would leave most of the chip idle (at most 128 scenarios and a predicted factor
  * of two): there a call without workspace, or with one that is too small or misaligned, still
- * runs, on the one-workgroup path (as does mmbp_local_search_pruned for every scenario that fits).
+ * runs, on the one-workgroup path (as do mmbp_local_search_pruned and a call with max_passes above
+ * 4096 for every scenario that fits).
  * Results do not depend on the path.
  */
 size_t mmbp_workspace_bytes(int S, int N, int M);

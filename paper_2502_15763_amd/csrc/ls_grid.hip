@@ -938,6 +938,8 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
 
 size_t ls_grid_workspace_bytes(int S, int N, int M) { return (size_t)S * grid_layout(N, M).total; }
 
+int ls_grid_pass_limit() { return kMaxPassLaunches; }
+
 hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                           int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                           uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, void *workspace,

@@ -79,8 +79,9 @@ static int local_search_impl(int prune, const void *cost, int dtype, int S, int 
     const bool fits = mmbp::ls_lds_fits(N, M);
     if (!fits && !ws_ok) return MMBP_EWORKSPACE;
     // One workgroup per scenario: the fallback when the optional workspace is not given, and always
-    // for the pruned scan of a scenario that fits (its pass is about as short as three launches)
-    const bool one_wg = fits && (!ws_ok || prune != 0);
+    // for the pruned scan of a scenario that fits (its pass is about as short as three launches),
+    // and for a pass limit the multi-workgroup path cannot honour in one call.
+    const bool one_wg = fits && (!ws_ok || prune != 0 || max_passes > mmbp::ls_grid_pass_limit());
     hipStream_t st = (hipStream_t)stream;
 
     // The first path writes a status for every scenario: final where it can search the scenario

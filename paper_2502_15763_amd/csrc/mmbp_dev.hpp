@@ -25,6 +25,7 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
 
 // multi-workgroup path (large N): state in the caller's workspace
 size_t ls_grid_workspace_bytes(int S, int N, int M);
+int ls_grid_pass_limit();     // passes one call of the multi-workgroup path can apply (it then reports TRUNCATED)
 hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                           int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                           uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, void *workspace,
