@@ -31,7 +31,8 @@ extern "C" {
 #define MMBP_EINVAL       -1  /* null pointer, non-positive size, bad dtype, negative max_passes, unknown policy */
 #define MMBP_EINFEASIBLE  -2  /* N > M * cap: no assignment satisfies the cardinality limit */
 #define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 64,
-                                 assigned simulator N <= 8192) */
+                                 assigned simulator N <= 8192, max_passes <= MMBP_GRID_MAX_PASSES for a
+                                 scenario that does not fit one workgroup's LDS) */
 #define MMBP_EWORKSPACE   -4  /* workspace missing, smaller than mmbp_workspace_bytes(), or not 256-byte aligned */
 #define MMBP_EHIP         -5  /* a HIP call or kernel launch failed; see mmbp_strerror() */
 
@@ -39,7 +40,7 @@ extern "C" {
 #define MMBP_ST_OK            0  /* converged: a full scan found no improving candidate */
 #define MMBP_ST_TRUNCATED     1  /* max_passes reached before a scan proved local optimality */
 #define MMBP_ST_BAD_ASSIGN    2  /* assign entry outside [0,M) or more than cap jobs on a client */
-#define MMBP_ST_BAD_COST      3  /* negative cost, or sum of costs >= 2^62 */
+#define MMBP_ST_BAD_COST      3  /* negative cost, sum of costs >= 2^62, or (lower bound) a negative token count */
 #define MMBP_ST_BAD_SIM_INPUT 4  /* arrival negative or decreasing, in_len < 1, out_len < 1 */
 #define MMBP_ST_INTERNAL      5  /* a consistency check inside a kernel failed (a bug): the scenario's
                                     outputs are not valid */
@@ -50,6 +51,7 @@ extern "C" {
 
 #define MMBP_MAX_N (1 << 20)
 #define MMBP_MAX_M 256
+#define MMBP_GRID_MAX_PASSES 4096   /* candidates one call can apply on the multi-workgroup path */
 #define MMBP_SIM_MAX_CAP 64
 #define MMBP_SIM_ASSIGNED_MAX_N 8192
 
@@ -81,7 +83,8 @@ size_t mmbp_workspace_bytes(int S, int N, int M);
  *   t^p* = tp_L * floor(sum_i prefill_tokens_i / ncap_L)  (the paper's floor form with the
  *        largest level L), added only when prefill_tokens != NULL and ncap_L > 0.
  * cost            [S,N] int32 or int64 per `dtype`, T_i >= 0
- * prefill_tokens  [S,N] int32 N^p_i, nullable
+ * prefill_tokens  [S,N] int32 N^p_i >= 0, nullable (a negative entry, when the term is enabled, makes the
+ *                 scenario MMBP_ST_BAD_COST)
  * lb_out          [S] int64
  * status_out      [S] int32: MMBP_ST_OK or MMBP_ST_BAD_COST (then lb_out = 0)
  */
@@ -97,7 +100,12 @@ int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M,
  *   swap  (i <-> k), i < k, assign[i] != assign[k],                      id = N*M + i*N + k
  * takes the candidate with the smallest (makespan, id) and applies it if it lowers the
  * makespan; otherwise the search stops (MMBP_ST_OK).  It also stops after max_passes applied
- * candidates (MMBP_ST_TRUNCATED; max_passes = 0 only reports the loads of the start).
+ * candidates (MMBP_ST_TRUNCATED; max_passes = 0 only reports the loads of the start).  `assign`
+ * is in/out, so a truncated search is resumed by calling again: k passes followed by k more give
+ * exactly what 2k passes give.  A scenario too large for one workgroup's LDS (mmbp_workspace_bytes)
+ * is searched with a fixed number of launches per pass, enqueued up front; for such shapes
+ * max_passes above MMBP_GRID_MAX_PASSES returns MMBP_EUNSUPPORTED (nothing is enqueued) and the
+ * caller resumes in calls of at most that many passes.
  * cost         [S,N] int32 / int64 per `dtype`
  * assign       [S,N] int32, in: feasible start, out: result (untouched for bad scenarios)
  * load_out     [S,M] int64 t_j of the result;  makespan_out [S] int64;  passes_out [S] int32

@@ -124,42 +124,31 @@ static void ls_one(const int64_t *cost, int N, int M, int cap, int max_passes, i
                 best_take(&best, v, (uint64_t)i * (uint64_t)M + (uint64_t)b);
             }
         }
-        /* swaps */
+        /* swaps: one loop for both ways of running it.  With inner_parallel the rows i are
+         * dealt to the threads of a team and the per-thread bests are merged with the same
+         * (value, id) order, which is total, so the result does not depend on the split; without
+         * it the team has one thread and the loop runs as written. */
         uint64_t swap_evals = 0;
-        if (inner_parallel) {
-#pragma omp parallel
-            {
-                best_t mine = {0, 0, 0};
-                uint64_t my_evals = 0;
+#pragma omp parallel if (inner_parallel)
+        {
+            best_t mine = {0, 0, 0};
+            uint64_t my_evals = 0;
 #pragma omp for schedule(dynamic, 64) nowait
-                for (int i = 0; i < N; i++) {
-                    int a = assign[i];
-                    for (int k = i + 1; k < N; k++) {
-                        int b = assign[k];
-                        if (a == b) continue;
-                        my_evals++;
-                        int64_t d = cost[i] - cost[k];
-                        int64_t v = max2(max2(load[a] - d, load[b] + d), others[(size_t)a * M + b]);
-                        best_take(&mine, v, (uint64_t)N * M + (uint64_t)i * N + (uint64_t)k);
-                    }
-                }
-#pragma omp critical
-                {
-                    swap_evals += my_evals;
-                    if (mine.valid) best_take(&best, mine.value, mine.id);
-                }
-            }
-        } else {
             for (int i = 0; i < N; i++) {
                 int a = assign[i];
                 for (int k = i + 1; k < N; k++) {
                     int b = assign[k];
                     if (a == b) continue;
-                    swap_evals++;
+                    my_evals++;
                     int64_t d = cost[i] - cost[k];
                     int64_t v = max2(max2(load[a] - d, load[b] + d), others[(size_t)a * M + b]);
-                    best_take(&best, v, (uint64_t)N * M + (uint64_t)i * N + (uint64_t)k);
+                    best_take(&mine, v, (uint64_t)N * M + (uint64_t)i * N + (uint64_t)k);
                 }
+            }
+#pragma omp critical
+            {
+                swap_evals += my_evals;
+                if (mine.valid) best_take(&best, mine.value, mine.id);
             }
         }
         evals += swap_evals;
@@ -192,30 +181,35 @@ static void ls_one(const int64_t *cost, int N, int M, int cap, int max_passes, i
     free(cnt); free(others);
 }
 
+/* mode: 0 = threads over scenarios (each scenario's scan serial), 1 = scenarios one after the
+ * other, threads inside the swap scan, -1 = pick by batch size.  Results do not depend on it. */
+int oracle_local_search_mode(const int64_t *cost, int S, int N, int M, int cap, int max_passes,
+                             int32_t *assign, int64_t *load_out, int64_t *makespan_out,
+                             int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
+                             int32_t *status_out, int mode)
+{
+    if (!cost || !assign || !load_out || !makespan_out || !passes_out || !status_out) return -1;
+    if (S <= 0 || N <= 0 || M <= 0 || cap <= 0 || max_passes < 0) return -1;
+    if (mode < -1 || mode > 1) return -1;
+    if ((int64_t)N > (int64_t)M * cap) return -2;
+    int threads = oracle_num_threads();
+    int inner = mode >= 0 ? mode : !(S >= threads || threads == 1);
+#pragma omp parallel for schedule(dynamic, 1) if (!inner)
+    for (int s = 0; s < S; s++)
+        ls_one(cost + (size_t)s * N, N, M, cap, max_passes, assign + (size_t)s * N,
+               load_out + (size_t)s * M, makespan_out + s, passes_out + s,
+               evals_out ? evals_out + s : 0,
+               applied_log ? applied_log + (size_t)s * max_passes : 0, status_out + s, inner);
+    return 0;
+}
+
 int oracle_local_search(const int64_t *cost, int S, int N, int M, int cap, int max_passes,
                         int32_t *assign, int64_t *load_out, int64_t *makespan_out,
                         int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
                         int32_t *status_out)
 {
-    if (!cost || !assign || !load_out || !makespan_out || !passes_out || !status_out) return -1;
-    if (S <= 0 || N <= 0 || M <= 0 || cap <= 0 || max_passes < 0) return -1;
-    if ((int64_t)N > (int64_t)M * cap) return -2;
-    int threads = oracle_num_threads();
-    if (S >= threads || threads == 1) {
-#pragma omp parallel for schedule(dynamic, 1)
-        for (int s = 0; s < S; s++)
-            ls_one(cost + (size_t)s * N, N, M, cap, max_passes, assign + (size_t)s * N,
-                   load_out + (size_t)s * M, makespan_out + s, passes_out + s,
-                   evals_out ? evals_out + s : 0,
-                   applied_log ? applied_log + (size_t)s * max_passes : 0, status_out + s, 0);
-    } else {
-        for (int s = 0; s < S; s++)
-            ls_one(cost + (size_t)s * N, N, M, cap, max_passes, assign + (size_t)s * N,
-                   load_out + (size_t)s * M, makespan_out + s, passes_out + s,
-                   evals_out ? evals_out + s : 0,
-                   applied_log ? applied_log + (size_t)s * max_passes : 0, status_out + s, 1);
-    }
-    return 0;
+    return oracle_local_search_mode(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out,
+                                    passes_out, evals_out, applied_log, status_out, -1);
 }
 
 /* ------------------------------------------------------------------------------------------
@@ -277,6 +271,9 @@ int oracle_lower_bound(const int64_t *cost, int S, int N, int M, const int32_t *
             if (c[i] < 0 || c[i] >= COST_SUM_LIMIT || sum + c[i] >= COST_SUM_LIMIT) { bad = 1; break; }
             sum += c[i];
         }
+        /* N^p_i is a token count: a negative entry makes the scenario's input invalid */
+        if (prefill_tokens && ncap_L > 0)
+            for (int i = 0; i < N; i++) if (prefill_tokens[(size_t)s * N + i] < 0) bad = 1;
         if (bad) { lb_out[s] = 0; status_out[s] = ST_BAD_COST; free(sorted); continue; }
         memcpy(sorted, c, (size_t)N * sizeof(int64_t));
         qsort(sorted, (size_t)N, sizeof(int64_t), cmp_desc);

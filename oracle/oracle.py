@@ -45,7 +45,9 @@ def num_threads() -> int:
     return int(lib().oracle_num_threads())
 
 
-def local_search(cost, assign0, M, cap, max_passes, want_log=False):
+def local_search(cost, assign0, M, cap, max_passes, want_log=False, mode=-1):
+    """mode: -1 = the library picks, 0 = threads over scenarios, 1 = threads inside one scenario's
+    swap scan (same results; tests pin both)."""
     cost = np.ascontiguousarray(cost, dtype=np.int64)
     S, N = cost.shape
     assign = np.ascontiguousarray(assign0, dtype=np.int32).copy()
@@ -55,9 +57,9 @@ def local_search(cost, assign0, M, cap, max_passes, want_log=False):
     evals = np.zeros(S, np.uint64)
     status = np.zeros(S, np.int32)
     log = np.full((S, max(max_passes, 1)), np.iinfo(np.uint64).max, np.uint64) if want_log else None
-    rc = lib().oracle_local_search(_p(cost), S, N, M, cap, max_passes, _p(assign), _p(load), _p(mk),
-                                   _p(passes), _p(evals), _p(log) if (want_log and max_passes > 0) else None,
-                                   _p(status))
+    rc = lib().oracle_local_search_mode(_p(cost), S, N, M, cap, max_passes, _p(assign), _p(load), _p(mk),
+                                        _p(passes), _p(evals), _p(log) if (want_log and max_passes > 0) else None,
+                                        _p(status), int(mode))
     out = dict(rc=rc, assign=assign, load=load, makespan=mk, passes=passes, evals=evals, status=status)
     if want_log:
         out["log"] = log

@@ -18,8 +18,11 @@ POLICY_RULE, POLICY_PREFILL_FIRST, POLICY_PREFILL_FIRST_SINGLE = 0, 1, 2
 ST_OK, ST_TRUNCATED, ST_BAD_ASSIGN, ST_BAD_COST, ST_BAD_SIM_INPUT = 0, 1, 2, 3, 4
 EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 
+GRID_MAX_PASSES = 4096
+
 EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_lower_bound",
-           "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim", "online_iter_sim_assigned")
+           "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim",
+           "online_iter_sim_assigned")
 
 
 class SimParams(C.Structure):

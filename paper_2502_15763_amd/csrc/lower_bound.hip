@@ -97,7 +97,11 @@ __global__ __launch_bounds__(kBlock) void lower_bound_kernel(const CostT *__rest
         }
     }
     if (prefill_tokens && ncap_L > 0)
-        for (int i = tid; i < N; i += kBlock) tok += (uint64_t)(int64_t)prefill_tokens[(size_t)s * N + i];
+        for (int i = tid; i < N; i += kBlock) {
+            const int32_t np = prefill_tokens[(size_t)s * N + i];
+            if (np < 0) bad = 1;                       // a token count cannot be negative
+            tok += (uint64_t)(np < 0 ? 0 : np);
+        }
     for (int off = 32; off >= 1; off >>= 1) {
         part = sat_add62(part, __shfl_xor((unsigned long long)part, off));
         mx = max(mx, (uint64_t)__shfl_xor((unsigned long long)mx, off));

@@ -7,19 +7,6 @@
 
 namespace mmbp {
 
-__global__ void fill_i32_kernel(int32_t *p, int32_t v, size_t n)
-{
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
-hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st)
-{
-    if (n == 0) return hipSuccess;
-    fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(p, v, n);
-    return hipGetLastError();
-}
-
 namespace {
 
 constexpr int kBlock = 256;

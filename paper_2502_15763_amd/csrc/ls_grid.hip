@@ -12,7 +12,8 @@
 //   grid_select_kernel  one workgroup: picks the lowest-id candidate of the best value exactly,
 //                       applies it, and prepares the next pass (top-3 loads, task table with the
 //                       critical client always on the column side).
-// The host enqueues min(max_passes, kMaxPassLaunches) such triples (pairs for small layouts, which
+// The host enqueues max_passes (at most kMaxPassLaunches; callers of larger limits that could run on
+// one workgroup are routed there, others are refused) such triples (pairs for small layouts, which
 // the selection workgroup scans itself); once a scenario has stopped the remaining launches return
 // at once.  The column chunk of the tasks and the number of evaluation workgroups follow the number
 // of client pairs, so that few clients still fill the chip.
@@ -39,7 +40,7 @@ constexpr int kColChunk = 1024;          // columns staged in LDS per task, at m
 constexpr int kMinColChunk = 128;        // the host picks the chunk (a power of two in between) so that few clients still
                                          // give the evaluation enough tasks to fill the chip
 constexpr int kRowBlockSegs = (kEvalBlock / kWave) * kRMax;   // 16 segments = 1024 rows per task
-constexpr int kMaxPassLaunches = 4096;
+constexpr int kMaxPassLaunches = MMBP_GRID_MAX_PASSES;   // the host refuses larger pass limits for this path
 constexpr uint32_t kNoJob32 = 0xFFFFFFFFu;
 #ifndef MMBP_GRID_FLAG_CAP
 #define MMBP_GRID_FLAG_CAP 256

@@ -24,7 +24,8 @@ const char *mmbp_strerror(int code)
     case MMBP_OK: return "ok";
     case MMBP_EINVAL: return "invalid argument (null pointer, non-positive size, bad dtype, negative max_passes or unknown policy)";
     case MMBP_EINFEASIBLE: return "infeasible: N > M * cap";
-    case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64, assigned simulator N <= 8192)";
+    case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64, assigned simulator N <= 8192, "
+                                   "max_passes <= 4096 per call for scenarios that need the multi-workgroup path)";
     case MMBP_EWORKSPACE: return "workspace missing, too small or not 256-byte aligned (see mmbp_workspace_bytes)";
     case MMBP_EHIP: return g_hip_err;
     default: return "unknown error code";
@@ -78,6 +79,10 @@ static int local_search_impl(int prune, const void *cost, int dtype, int S, int 
     const bool ws_ok = need > 0 && workspace && workspace_bytes >= need && ((uintptr_t)workspace & 255u) == 0;
     const bool fits = mmbp::ls_lds_fits(N, M);
     if (!fits && !ws_ok) return MMBP_EWORKSPACE;
+    // The multi-workgroup path enqueues its launches pass by pass and cannot see convergence from the
+    // host: a call applies at most MMBP_GRID_MAX_PASSES candidates.  A larger limit on a shape that
+    // needs this path is refused rather than silently cut (the caller resumes with further calls).
+    if (!fits && max_passes > MMBP_GRID_MAX_PASSES) return MMBP_EUNSUPPORTED;
     // One workgroup per scenario: the fallback when the optional workspace is not given, and always
     // for the pruned scan of a scenario that fits (its pass is about as short as three launches),
     // and for a pass limit the multi-workgroup path cannot honour in one call.

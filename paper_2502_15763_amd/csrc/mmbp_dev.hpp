@@ -11,8 +11,6 @@ constexpr int32_t kPending = -1;          // status_out value while no path has 
 constexpr int64_t kCostSumLimit = (int64_t)1 << 62;
 
 // ---- host-side launchers, one per translation unit (all enqueue on `st`, return hipError_t) ----
-hipError_t launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t st);
-
 hipError_t launch_ls_generic(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
                              int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                              uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st);

@@ -59,6 +59,9 @@ def test_host_side_argument_validation():
         assert ls(one, 1, 1, 65536, 64, 1024, 1, one, one, one, one, None, None, one, one, need - 1, None) == api.EWORKSPACE
         odd = C.c_void_p(256 + 16)                 # the base must be 256-byte aligned
         assert ls(one, 1, 1, 65536, 64, 1024, 1, one, one, one, one, None, None, one, odd, need, None) == api.EWORKSPACE
+        # a pass limit above what one call of the multi-workgroup path can apply is refused, not cut
+        assert ls(one, 1, 1, 65536, 64, 1024, api.GRID_MAX_PASSES + 1, one, one, one, one, None, None, one, one, need,
+                  None) == api.EUNSUPPORTED
     lb = lib.mmbp_lower_bound
     assert lb(None, 0, 1, 4, 2, None, 0, 0, one, one, None) == api.EINVAL
     assert lb(one, 0, 1, 4, 0, None, 0, 0, one, one, None) == api.EINVAL

@@ -65,6 +65,17 @@ def test_lb_bad_cost(oracle):
     assert r["status"].tolist() == [3, 0] and r["lb"].tolist() == [0, 2]
 
 
+def test_lb_negative_token_count_is_bad_input(oracle):
+    # N^p_i is a token count; a negative entry invalidates the scenario when the prefill term is on,
+    # and is not looked at when the term is off
+    c = np.array([[10, 10], [10, 10]], np.int64)
+    tok = np.array([[100, -1], [100, 7000]], np.int32)
+    r = oracle.lower_bound(c, 2, prefill_tokens=tok, ncap_L=5000, tp_L=675000)
+    assert r["status"].tolist() == [3, 0] and r["lb"].tolist() == [0, 10 + 675000]
+    r = oracle.lower_bound(c, 2, prefill_tokens=tok, ncap_L=0, tp_L=675000)
+    assert r["status"].tolist() == [0, 0] and r["lb"].tolist() == [10, 10]
+
+
 # ------------------------------------------------------------------ simulator
 def test_time_model_worked_examples(oracle):
     with open(GOLD) as f:

@@ -53,13 +53,32 @@ def test_hand_worked_examples(oracle, case):
     assert d["assign"] == case["assign"] and d["log"] == case["log"] and d["evals"] == case["evals"]
 
 
+@pytest.mark.parametrize("mode", [0, 1], ids=["threads_over_scenarios", "threads_inside_scan"])
+@pytest.mark.parametrize("case", _golden_cases(), ids=lambda c: c["name"])
+def test_hand_worked_examples_both_threadings(oracle, case, mode):
+    """The oracle runs its swap scan either serially (threads over scenarios) or split over threads
+    (one scenario at a time); each way is held to the hand-worked numbers, whatever the host's core
+    count would have picked."""
+    cost = np.array([case["cost"]], np.int64)
+    a0 = np.array([case["assign0"]], np.int32)
+    r = oracle.local_search(cost, a0, case["M"], case["cap"], case["max_passes"], want_log=True, mode=mode)
+    assert r["rc"] == 0
+    assert r["assign"][0].tolist() == case["assign"]
+    assert r["load"][0].tolist() == case["load"]
+    assert int(r["passes"][0]) == case["passes"]
+    assert int(r["evals"][0]) == case["evals"]
+    assert int(r["status"][0]) == case["status"]
+    assert r["log"][0][: case["passes"]].tolist() == case["log"]
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["threads_over_scenarios", "threads_inside_scan"])
 @pytest.mark.parametrize("N,M,cap", [(6, 2, 3), (7, 3, 3), (9, 3, 4), (8, 4, 2), (10, 4, 10), (5, 5, 1),
                                      (12, 3, 6), (16, 4, 5)])
-def test_delta_formula_equals_recomputation(oracle, N, M, cap):
+def test_delta_formula_equals_recomputation(oracle, N, M, cap, mode):
     rng = np.random.default_rng(100 + N * 10 + M)
     for trial in range(12):
         cost, assign = W.random_offline(rng, 1, N, M, cap, cost_hi=[30, 1000, 3][trial % 3])
-        r = oracle.local_search(cost, assign, M, cap, 50, want_log=True)
+        r = oracle.local_search(cost, assign, M, cap, 50, want_log=True, mode=mode)
         d = D.local_search(cost[0], assign[0], M, cap, 50)
         p = int(r["passes"][0])
         assert p == d["passes"]
@@ -203,3 +222,27 @@ def test_config1_shape_and_tight_capacity(oracle):
     assert int(r["evals"][0]) == per_scan * (p + 1)
     lb = int(oracle.lower_bound(c.cost, c.M)["lb"][0])
     assert lb <= int(r["makespan"][0])
+
+
+@pytest.mark.parametrize("mode", [0, 1], ids=["threads_over_scenarios", "threads_inside_scan"])
+def test_batch_of_scenarios_both_threadings(oracle, mode):
+    """A batch larger than any host's thread count (so neither threading is chosen by accident),
+    with rows long enough that the split scan really hands rows to several threads (its chunks are
+    64 rows): every scenario against the definition-level search, pass by pass."""
+    rng = np.random.default_rng(4242)
+    S, N, M, cap = 40, 130, 4, 40
+    cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=60)
+    r = oracle.local_search(cost, assign, M, cap, 4, want_log=True, mode=mode)
+    assert r["rc"] == 0
+    for s in range(0, S, 8):
+        d = D.local_search(cost[s], assign[s], M, cap, 4)
+        p = int(r["passes"][s])
+        assert p == d["passes"] and r["log"][s][:p].tolist() == d["log"]
+        assert r["assign"][s].tolist() == d["assign"] and r["load"][s].tolist() == d["load"]
+        assert int(r["evals"][s]) == d["evals"] and int(r["status"][s]) == d["status"]
+
+
+def test_bad_mode_is_rejected(oracle):
+    cost = np.array([[5, 3, 2, 1]], np.int64)
+    assign = np.array([[0, 0, 1, 1]], np.int32)
+    assert oracle.local_search(cost, assign, 2, 2, 10, mode=2)["rc"] == -1
