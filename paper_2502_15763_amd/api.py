@@ -47,6 +47,9 @@ def load_library() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2502_15763_amd.build`")
+    # PyTorch brings its own copy of the HIP runtime; the library must bind to that copy (one runtime
+    # per process: a second one sees no device), so torch is loaded before the library, always.
+    _torch()
     lib = C.CDLL(LIB_PATH)
     vp, i, i64, sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
     lib.mmbp_version.restype = i
