@@ -135,6 +135,28 @@ int mmbp_local_search_pruned(const void *cost, int dtype, int S, int N, int M, i
                              int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
                              int32_t *status_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * mmbp_local_search for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results,
+ * status codes and path selection as mmbp_local_search, without the workspace pair: where that call
+ * would use a workspace, this one uses a scratch array that is part of the library's device code
+ * (MMBP_STATIC_SCRATCH_BYTES per GPU, held from the moment the library is loaded on that GPU until
+ * the process ends).  The call allocates and frees nothing, on the host side of the GPU or through
+ * any library; its first call on a device looks the array's device address up once (not an
+ * allocation; make that first call outside a graph capture).
+ *   - mmbp_workspace_bytes(S,N,M) above MMBP_STATIC_SCRATCH_BYTES: MMBP_EWORKSPACE (nothing is
+ *     enqueued) when the shape needs the multi-workgroup path; where that path is only preferred the
+ *     one-workgroup path runs instead.
+ *   - All calls on one GPU share that GPU's array (it keeps the last call's contents; the kernels
+ *     initialise what they read).  Two calls that overlap in time on one GPU (different streams, or
+ *     different host threads without stream order between them) race on it: keep them in stream order.
+ */
+#define MMBP_STATIC_SCRATCH_BYTES (16u << 20)
+int mmbp_local_search_static(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
+                             int32_t *assign, int64_t *load_out, int64_t *makespan_out,
+                             int32_t *passes_out, uint64_t *evals_out, uint64_t *applied_log,
+                             int32_t *status_out, void *stream);
+
 /* Iteration-scheduling policy of the simulator.
  * MMBP_POLICY_RULE: the paper's rule (section "Online requests and iteration scheduling"):
  *     C_p >= C_d keeps decoding, otherwise the prefill is dispatched.

@@ -19,9 +19,10 @@ ST_OK, ST_TRUNCATED, ST_BAD_ASSIGN, ST_BAD_COST, ST_BAD_SIM_INPUT = 0, 1, 2, 3, 
 EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 
 GRID_MAX_PASSES = 4096
+STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_lower_bound",
-           "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim",
+           "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
            "online_iter_sim_assigned")
 
 
@@ -63,6 +64,8 @@ def load_library() -> C.CDLL:
     lib.mmbp_local_search.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mmbp_local_search_pruned.restype = i
     lib.mmbp_local_search_pruned.argtypes = lib.mmbp_local_search.argtypes
+    lib.mmbp_local_search_static.restype = i
+    lib.mmbp_local_search_static.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.online_iter_sim.restype = i
     lib.online_iter_sim.argtypes = [vp, vp, vp, i, i, C.POINTER(SimParams), vp, vp, vp, vp, vp, vp, vp, vp, i, i,
                                     vp, vp]
@@ -162,6 +165,21 @@ def mmbp_local_search_pruned(cost, M, cap, max_passes, assign, load_out, makespa
     return mmbp_local_search(cost, M, cap, max_passes, assign, load_out, makespan_out, passes_out, status_out,
                              evals_out=evals_out, applied_log=applied_log, workspace=workspace, stream=stream,
                              raise_on_error=raise_on_error, _entry="mmbp_local_search_pruned")
+
+
+def mmbp_local_search_static(cost, M, cap, max_passes, assign, load_out, makespan_out, passes_out, status_out,
+                             evals_out=None, applied_log=None, stream=None, raise_on_error=True) -> int:
+    """The entry point that allocates nothing: scratch comes from the library's own device array."""
+    torch = _torch()
+    S, N = cost.shape
+    rc = load_library().mmbp_local_search_static(
+        _ptr(cost, name="cost"), _cost_dtype(cost), S, N, int(M), int(cap), int(max_passes),
+        _ptr(assign, torch.int32, (S, N), "assign"), _ptr(load_out, torch.int64, (S, M), "load_out"),
+        _ptr(makespan_out, torch.int64, (S,), "makespan_out"), _ptr(passes_out, torch.int32, (S,), "passes_out"),
+        _ptr(evals_out, torch.int64, (S,), "evals_out"),
+        _ptr(applied_log, torch.int64, (S, max(int(max_passes), 0)), "applied_log") if applied_log is not None else None,
+        _ptr(status_out, torch.int32, (S,), "status_out"), _stream(stream))
+    return _check(rc, raise_on_error)
 
 
 def online_iter_sim(arrival_us, in_len, out_len, params: dict, finish_us, total_us, busy_slot_us,

@@ -2,6 +2,7 @@
 // stream.  No allocation, no synchronisation.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include "mmbp_dev.hpp"
 
 namespace {
@@ -11,6 +12,38 @@ int fail_hip(hipError_t e, const char *where)
 {
     snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", where, hipGetErrorString(e));
     return MMBP_EHIP;
+}
+}  // namespace
+
+// ---- the entry point that allocates nothing ----
+// Scratch of the multi-workgroup path for callers that cannot bring a workspace: one array per GPU
+// (each device that loads this code object holds its own copy at its own address until the process
+// ends).  In host code the array's name is only a handle; the device address is looked up once per
+// device and that pointer is what the kernels get.
+constexpr size_t kStaticScratchBytes = MMBP_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up on the first call per device)
+int static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "mmbp_local_search_static(hipGetDevice)");
+    if (dev < 0 || dev >= kMaxDevices) return MMBP_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail_hip(e, "mmbp_local_search_static(hipGetSymbolAddress)");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MMBP_OK;
 }
 }  // namespace
 
@@ -26,7 +59,8 @@ const char *mmbp_strerror(int code)
     case MMBP_EINFEASIBLE: return "infeasible: N > M * cap";
     case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64, assigned simulator N <= 8192, "
                                    "max_passes <= 4096 per call for scenarios that need the multi-workgroup path)";
-    case MMBP_EWORKSPACE: return "workspace missing, too small or not 256-byte aligned (see mmbp_workspace_bytes)";
+    case MMBP_EWORKSPACE: return "workspace missing, too small or not 256-byte aligned (see mmbp_workspace_bytes), or the "
+                                 "shape needs more scratch than mmbp_local_search_static holds (MMBP_STATIC_SCRATCH_BYTES)";
     case MMBP_EHIP: return g_hip_err;
     default: return "unknown error code";
     }
@@ -122,6 +156,30 @@ int mmbp_local_search_pruned(const void *cost, int dtype, int S, int N, int M, i
 {
     return local_search_impl(1, cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
                              evals_out, applied_log, status_out, workspace, workspace_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing (its scratch is declared above) ----
+int mmbp_local_search_static(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int32_t *assign,
+                             int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
+                             uint64_t *applied_log, int32_t *status_out, void *stream)
+{
+    // argument errors first, exactly as mmbp_local_search reports them
+    if (!cost || !assign || !load_out || !makespan_out || !passes_out || !status_out) return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || M <= 0 || cap <= 0 || max_passes < 0) return MMBP_EINVAL;
+    if (dtype != MMBP_I32 && dtype != MMBP_I64) return MMBP_EINVAL;
+    if (N > MMBP_MAX_N || M > MMBP_MAX_M) return MMBP_EUNSUPPORTED;
+    if ((int64_t)N > (int64_t)M * (int64_t)cap) return MMBP_EINFEASIBLE;
+    const size_t need = mmbp_workspace_bytes(S, N, M);
+    void *ws = nullptr;
+    if (need > kStaticScratchBytes) {
+        // where the multi-workgroup path is only preferred the one-workgroup path still runs
+        if (!mmbp::ls_lds_fits(N, M)) return MMBP_EWORKSPACE;
+    } else if (need > 0) {
+        const int rc = static_scratch(&ws);
+        if (rc != MMBP_OK) return rc;
+    }
+    return local_search_impl(0, cost, dtype, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out,
+                             evals_out, applied_log, status_out, ws, ws ? kStaticScratchBytes : 0, stream);
 }
 
 int online_iter_sim(const int64_t *arrival_us, const int32_t *in_len, const int32_t *out_len, int S, int N,

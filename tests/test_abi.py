@@ -21,7 +21,7 @@ def _declared_functions():
 
 def test_header_declares_expected_entry_points():
     names = _declared_functions()
-    for n in ("mmbp_lower_bound", "mmbp_local_search", "mmbp_local_search_pruned", "online_iter_sim",
+    for n in ("mmbp_lower_bound", "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
               "online_iter_sim_assigned", "mmbp_workspace_bytes",
               "mmbp_strerror", "mmbp_version"):
         assert n in names
@@ -62,6 +62,12 @@ def test_host_side_argument_validation():
         # a pass limit above what one call of the multi-workgroup path can apply is refused, not cut
         assert ls(one, 1, 1, 65536, 64, 1024, api.GRID_MAX_PASSES + 1, one, one, one, one, None, None, one, one, need,
                   None) == api.EUNSUPPORTED
+    st = lib.mmbp_local_search_static
+    assert st(None, 0, 1, 4, 2, 2, 1, one, one, one, one, None, None, one, None) == api.EINVAL
+    assert st(one, 0, 1, 5, 2, 2, 1, one, one, one, one, None, None, one, None) == api.EINFEASIBLE
+    assert st(one, 0, 1, 4, 257, 2, 1, one, one, one, one, None, None, one, None) == api.EUNSUPPORTED
+    assert api.mmbp_workspace_bytes(8, 65536, 64) > api.STATIC_SCRATCH_BYTES      # more than the static scratch holds
+    assert st(one, 1, 8, 65536, 64, 1024, 1, one, one, one, one, None, None, one, None) == api.EWORKSPACE
     lb = lib.mmbp_lower_bound
     assert lb(None, 0, 1, 4, 2, None, 0, 0, one, one, None) == api.EINVAL
     assert lb(one, 0, 1, 4, 0, None, 0, 0, one, one, None) == api.EINVAL
