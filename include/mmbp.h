@@ -76,6 +76,17 @@ const char *mmbp_strerror(int code);
 size_t mmbp_workspace_bytes(int S, int N, int M);
 
 /*
+ * Measurement aid, no part of the method: runs the instruction mix of the local search's swap
+ * evaluation (one 32-bit subtract per candidate, one three-way min and one three-way max per two
+ * candidates) on registers only, so that a caller can time the vector-ALU issue rate the device
+ * sustains and set the search's throughput against it.
+ * out       device [blocks * 256] uint32 (receives one word per thread; its content means nothing)
+ * blocks    workgroups of 256 threads, 1 .. 2^20;  trips: loop trips per thread, 1 .. 2^24
+ * lane_ops  HOST pointer, nullable: receives the number of 32-bit lane operations the launch issues
+ */
+int mmbp_valu_probe(uint32_t *out, int blocks, int trips, uint64_t *lane_ops /* host */, void *stream);
+
+/*
  * Theoretical lower bound, paper section "Offline requests scheduling & theoretical lower
  * bound": T^LB = t^p* + t^d*.
  *   t^d* (optimum of the MMBP model) is replaced by the largest of three relaxation bounds,

@@ -21,7 +21,7 @@ EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 GRID_MAX_PASSES = 4096
 STATIC_SCRATCH_BYTES = 16 << 20
 
-EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_lower_bound",
+EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_valu_probe", "mmbp_lower_bound",
            "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
            "online_iter_sim_assigned")
 
@@ -58,6 +58,8 @@ def load_library() -> C.CDLL:
     lib.mmbp_strerror.argtypes = [i]
     lib.mmbp_workspace_bytes.restype = sz
     lib.mmbp_workspace_bytes.argtypes = [i, i, i]
+    lib.mmbp_valu_probe.restype = i
+    lib.mmbp_valu_probe.argtypes = [vp, i, i, C.POINTER(C.c_uint64), vp]
     lib.mmbp_lower_bound.restype = i
     lib.mmbp_lower_bound.argtypes = [vp, i, i, i, i, vp, i64, i64, vp, vp, vp]
     lib.mmbp_local_search.restype = i
@@ -119,6 +121,16 @@ def mmbp_strerror(code: int) -> str:
 
 def mmbp_workspace_bytes(S: int, N: int, M: int) -> int:
     return int(load_library().mmbp_workspace_bytes(int(S), int(N), int(M)))
+
+
+def mmbp_valu_probe(out, blocks, trips, stream=None, raise_on_error=True) -> int:
+    """Enqueues the vector-ALU calibration loop; returns the 32-bit lane operations it issues."""
+    torch = _torch()
+    ops = C.c_uint64(0)
+    rc = load_library().mmbp_valu_probe(_ptr(out, torch.int32, (int(blocks) * 256,), "out"), int(blocks), int(trips),
+                                        C.byref(ops), _stream(stream))
+    _check(rc, raise_on_error)
+    return int(ops.value)
 
 
 def _cost_dtype(cost):

@@ -86,6 +86,15 @@ size_t mmbp_workspace_bytes(int S, int N, int M)
     return mmbp::ls_grid_workspace_bytes(S, N, M);
 }
 
+int mmbp_valu_probe(uint32_t *out, int blocks, int trips, uint64_t *lane_ops, void *stream)
+{
+    if (!out || blocks <= 0 || trips <= 0) return MMBP_EINVAL;
+    if (blocks > (1 << 20) || trips > (1 << 24)) return MMBP_EUNSUPPORTED;
+    if (lane_ops) *lane_ops = (uint64_t)blocks * 256ull * (uint64_t)trips * (uint64_t)mmbp::valu_probe_ops_per_trip();
+    hipError_t e = mmbp::launch_valu_probe(out, blocks, trips, (hipStream_t)stream);
+    return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_valu_probe");
+}
+
 int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M, const int32_t *prefill_tokens,
                      int64_t ncap_L, int64_t tp_L, int64_t *lb_out, int32_t *status_out, void *stream)
 {

@@ -45,6 +45,10 @@ hipError_t launch_online_sim_assigned(const int32_t *in_len, const int32_t *out_
                                       mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
                                       int trace_capacity, int32_t *status_out, hipStream_t st);
 
+// calibration probe of the vector-ALU issue rate (measurement aid, see valu_probe.hip)
+int valu_probe_ops_per_trip();
+hipError_t launch_valu_probe(uint32_t *out, int blocks, int trips, hipStream_t st);
+
 #if defined(__HIPCC__)
 // ------------------------------------------------------------------------------------------
 // wave64 reductions.  DPP row shifts reduce inside each row of 16 lanes, the two row
