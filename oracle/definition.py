@@ -96,3 +96,19 @@ def brute_force_opt(cost, M, cap):
         if best is None or v < best:
             best = v
     return best
+
+
+def brute_force_opt_caps(cost, M, caps):
+    """Optimum of the MMBP model with a cardinality limit per client, by enumeration."""
+    N = len(cost)
+    best = None
+    for asg in itertools.product(range(M), repeat=N):
+        cnt = [0] * M
+        for a in asg:
+            cnt[a] += 1
+        if any(cnt[j] > caps[j] for j in range(M)):
+            continue
+        v = makespan_of(cost, asg, M)
+        if best is None or v < best:
+            best = v
+    return best

@@ -295,6 +295,139 @@ int oracle_lower_bound(const int64_t *cost, int S, int N, int M, const int32_t *
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Extended lower bound.  Same equation T^LB = t^p* + t^d*, with more relaxation bounds on t^d*
+ * and a level table for t^p* (levels l with token capacity N^cap_l and prefill time T^p_l, as in
+ * the paper's prefill-length constraints).
+ *   L1, L2 as above.
+ *   L3(k) = T_(kM+1) + T_(kM) + ... + T_(kM+1-k)   (descending order, k >= 1, kM+1 <= N):
+ *           of the kM+1 largest requests some client holds at least k+1, and those cost at least
+ *           as much as the k+1 smallest of them.  Taken over k <= kmax (kmax <= 0: no limit of the
+ *           caller's) with kM+1 <= rank_limit (the library's own limit on the ranks it looks at;
+ *           any subset of the k gives a valid bound).  L3 = max_k L3(k), k3 = the smallest k that
+ *           attains it (0 when no k qualifies).
+ *   Lcap  per-client cardinality limits cap[j] (nullable): client j holds at least
+ *           n_j = max(0, N - sum_{j' != j} cap[j']) requests, so its load is at least the sum of
+ *           the n_j smallest costs; Lcap = that sum for the largest n_j.
+ *   t^p*  tp_form 0: the paper's floor form on the level L of largest capacity (among equal
+ *           capacities the smaller time), T^p_L * floor(sum N^p_i / N^cap_L);
+ *         tp_form 1: every prefill stage of level l takes T^p_l for at most N^cap_l tokens, so
+ *           any set of stages that covers all tokens takes at least
+ *           ceil(sum N^p_i * min_l (T^p_l / N^cap_l))  (valid for every table, whereas the floor
+ *           form assumes the largest level is also the most efficient one).
+ * parts_out[s] = { L1, L2, L3, k3, Lcap, t^p* }.  lb = max(L1, L2, L3, Lcap) + t^p*.
+ * Returns -1 bad argument, -2 if sum cap[j] < N.  Status BAD_COST: invalid cost, negative token
+ * count, or t^p* not below 2^62.
+ * ------------------------------------------------------------------------------------------ */
+int oracle_lower_bound_ex(const int64_t *cost, int S, int N, int M, const int32_t *cap, int kmax,
+                          int rank_limit, const int32_t *prefill_tokens, int n_levels,
+                          const int64_t *ncap, const int64_t *tp, int tp_form, int64_t *lb_out,
+                          int64_t *parts_out, int32_t *status_out)
+{
+    if (!cost || !lb_out || !status_out || S <= 0 || N <= 0 || M <= 0) return -1;
+    if (n_levels < 0 || (n_levels > 0 && (!ncap || !tp)) || (tp_form != 0 && tp_form != 1)) return -1;
+    if (rank_limit < 1) return -1;
+    for (int l = 0; l < n_levels; l++)
+        if (ncap[l] < 1 || ncap[l] > INT32_MAX || tp[l] < 0 || tp[l] > INT32_MAX) return -1;
+    int nstar = 0;                                   /* largest n_j */
+    if (cap) {
+        int64_t capsum = 0;
+        for (int j = 0; j < M; j++) { if (cap[j] < 0) return -1; capsum += cap[j]; }
+        if (capsum < N) return -2;
+        for (int j = 0; j < M; j++) {
+            int64_t nj = (int64_t)N - (capsum - cap[j]);
+            if (nj > nstar) nstar = (int)nj;
+        }
+    }
+#pragma omp parallel for schedule(static)
+    for (int s = 0; s < S; s++) {
+        const int64_t *c = cost + (size_t)s * N;
+        int64_t *parts = parts_out ? parts_out + (size_t)s * 6 : 0;
+        if (parts) for (int q = 0; q < 6; q++) parts[q] = 0;
+        int bad = 0;
+        int64_t sum = 0, tok = 0;
+        for (int i = 0; i < N; i++) {
+            if (c[i] < 0 || c[i] >= COST_SUM_LIMIT || sum + c[i] >= COST_SUM_LIMIT) { bad = 1; break; }
+            sum += c[i];
+        }
+        const int with_tp = prefill_tokens && n_levels > 0;
+        if (with_tp)
+            for (int i = 0; i < N; i++) {
+                if (prefill_tokens[(size_t)s * N + i] < 0) bad = 1;
+                else tok += prefill_tokens[(size_t)s * N + i];
+            }
+        /* t^p* */
+        int64_t tps = 0;
+        if (!bad && with_tp) {
+            if (tp_form == 0) {
+                int L = 0;
+                for (int l = 1; l < n_levels; l++)
+                    if (ncap[l] > ncap[L] || (ncap[l] == ncap[L] && tp[l] < tp[L])) L = l;
+                int64_t q = tok / ncap[L];
+                if (tp[L] > 0 && q > (COST_SUM_LIMIT - 1) / tp[L]) bad = 1;
+                else tps = tp[L] * q;
+            } else {
+                /* min over levels of ceil(tok * tp / ncap), each as q*tp + ceil(r*tp/ncap) */
+                for (int l = 0; l < n_levels; l++) {
+                    int64_t q = tok / ncap[l], r = tok % ncap[l];
+                    if (tp[l] > 0 && q > (COST_SUM_LIMIT - 1) / tp[l] - 1) { bad = 1; break; }
+                    int64_t v = q * tp[l] + (r * tp[l] + ncap[l] - 1) / ncap[l];
+                    if (l == 0 || v < tps) tps = v;
+                }
+            }
+        }
+        if (bad) { lb_out[s] = 0; status_out[s] = ST_BAD_COST; continue; }
+        int64_t *sorted = (int64_t *)malloc((size_t)N * sizeof(int64_t));
+        memcpy(sorted, c, (size_t)N * sizeof(int64_t));
+        qsort(sorted, (size_t)N, sizeof(int64_t), cmp_desc);
+        int64_t L1 = (sum + M - 1) / M;
+        int64_t L2 = sorted[0];
+        int64_t L3 = 0; int k3 = 0;
+        for (int k = 1; (int64_t)k * M + 1 <= N && (int64_t)k * M + 1 <= rank_limit; k++) {
+            if (kmax > 0 && k > kmax) break;
+            int64_t v = 0;
+            for (int h = 0; h <= k; h++) v += sorted[(size_t)k * M + 1 - h - 1];   /* rank r is sorted[r-1] */
+            if (v > L3) { L3 = v; k3 = k; }
+        }
+        int64_t Lcap = 0;
+        for (int q = 0; q < nstar; q++) Lcap += sorted[N - 1 - q];                   /* the nstar smallest */
+        int64_t lbd = max2(max2(L1, L2), max2(L3, Lcap));
+        lb_out[s] = lbd + tps;
+        status_out[s] = ST_OK;
+        if (parts) { parts[0] = L1; parts[1] = L2; parts[2] = L3; parts[3] = k3; parts[4] = Lcap; parts[5] = tps; }
+        free(sorted);
+    }
+    return 0;
+}
+
+/* brute force with per-client cardinality limits cap[j] */
+static void bf_rec_caps(const int64_t *cost, int N, int M, const int32_t *cap, int i, int64_t *load, int32_t *cnt,
+                        int64_t *best)
+{
+    if (i == N) {
+        int64_t T = 0;
+        for (int j = 0; j < M; j++) T = max2(T, load[j]);
+        if (*best < 0 || T < *best) *best = T;
+        return;
+    }
+    for (int j = 0; j < M; j++) {
+        if (cnt[j] + 1 > cap[j]) continue;
+        cnt[j]++; load[j] += cost[i];
+        bf_rec_caps(cost, N, M, cap, i + 1, load, cnt, best);
+        cnt[j]--; load[j] -= cost[i];
+    }
+}
+
+int64_t oracle_brute_force_opt_caps(const int64_t *cost, int N, int M, const int32_t *cap)
+{
+    int64_t *load = (int64_t *)calloc((size_t)M, sizeof(int64_t));
+    int32_t *cnt = (int32_t *)calloc((size_t)M, sizeof(int32_t));
+    int64_t best = -1;
+    bf_rec_caps(cost, N, M, cap, 0, load, cnt, &best);
+    free(load); free(cnt);
+    return best;
+}
+
+/* ------------------------------------------------------------------------------------------
  * FNV-1a, 64 bit (published constants: offset basis 0xcbf29ce484222325, prime 0x100000001b3).
  * ------------------------------------------------------------------------------------------ */
 uint64_t oracle_fnv1a64(const uint8_t *bytes, size_t n, uint64_t h)

@@ -27,6 +27,7 @@ def lib():
         path = _build.build(force=False)
         _lib = C.CDLL(path)
         _lib.oracle_brute_force_opt.restype = C.c_int64
+        _lib.oracle_brute_force_opt_caps.restype = C.c_int64
         _lib.oracle_fnv1a64.restype = C.c_uint64
         _lib.oracle_fnv1a64.argtypes = [C.c_void_p, C.c_size_t, C.c_uint64]
         _lib.oracle_fnv1a64_init.restype = C.c_uint64
@@ -80,6 +81,32 @@ def lower_bound(cost, M, prefill_tokens=None, ncap_L=0, tp_L=0):
     rc = lib().oracle_lower_bound(_p(cost), S, N, M, _p(pt), C.c_int64(ncap_L), C.c_int64(tp_L),
                                   _p(lb), _p(status))
     return dict(rc=rc, lb=lb, status=status)
+
+
+LB_RANK_LIMIT = 16384     # ranks the library's extended bound looks at (its documented limit, see include/mmbp.h)
+
+
+def lower_bound_ex(cost, M, cap=None, kmax=0, prefill_tokens=None, ncap=None, tp=None, tp_form=0,
+                   rank_limit=LB_RANK_LIMIT):
+    cost = np.ascontiguousarray(cost, dtype=np.int64)
+    S, N = cost.shape
+    lb = np.zeros(S, np.int64)
+    parts = np.zeros((S, 6), np.int64)
+    status = np.zeros(S, np.int32)
+    capa = None if cap is None else np.ascontiguousarray(cap, dtype=np.int32)
+    pt = None if prefill_tokens is None else np.ascontiguousarray(prefill_tokens, dtype=np.int32)
+    nc = None if ncap is None else np.ascontiguousarray(ncap, dtype=np.int64)
+    tpa = None if tp is None else np.ascontiguousarray(tp, dtype=np.int64)
+    nl = 0 if nc is None else int(nc.shape[0])
+    rc = lib().oracle_lower_bound_ex(_p(cost), S, N, int(M), _p(capa), int(kmax), int(rank_limit), _p(pt), nl, _p(nc),
+                                     _p(tpa), int(tp_form), _p(lb), _p(parts), _p(status))
+    return dict(rc=rc, lb=lb, parts=parts, status=status)
+
+
+def brute_force_opt_caps(cost_row, M, caps) -> int:
+    c = np.ascontiguousarray(cost_row, dtype=np.int64)
+    k = np.ascontiguousarray(caps, dtype=np.int32)
+    return int(lib().oracle_brute_force_opt_caps(_p(c), int(c.shape[0]), int(M), _p(k)))
 
 
 def make_params(cap, a_prefill, b_decode, c_prefill, c_decode, max_prefill_tokens=0, policy=0):

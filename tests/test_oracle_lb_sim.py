@@ -76,6 +76,124 @@ def test_lb_negative_token_count_is_bad_input(oracle):
     assert r["status"].tolist() == [0, 0] and r["lb"].tolist() == [10, 10]
 
 
+# ------------------------------------------------------------------ extended lower bound
+LB_EX_GOLD = os.path.join(os.path.dirname(__file__), "golden", "lb_ex_hand_worked.txt")
+
+
+def _lb_ex_cases():
+    cases = []
+    ints = lambda t: None if t.strip() == "-" else [int(x) for x in t.split()]
+    for line in open(LB_EX_GOLD):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        p = [x.strip() for x in line.split("|")]
+        lv = None if p[6] == "-" else [tuple(int(v) for v in t.split(":")) for t in p[6].split()]
+        cases.append(dict(name=p[0], M=int(p[1]), cost=ints(p[2]), caps=ints(p[3]), kmax=int(p[4]), tokens=ints(p[5]),
+                          levels=lv, tp_form=int(p[7]), parts=[int(x) for x in p[8:14]], lb=int(p[14])))
+    return cases
+
+
+def _lb_ex(oracle, c):
+    kw = {}
+    if c["levels"]:
+        kw = dict(prefill_tokens=np.array([c["tokens"]], np.int32), ncap=[l[0] for l in c["levels"]],
+                  tp=[l[1] for l in c["levels"]], tp_form=c["tp_form"])
+    return oracle.lower_bound_ex(np.array([c["cost"]], np.int64), c["M"], cap=c["caps"], kmax=c["kmax"], **kw)
+
+
+@pytest.mark.parametrize("case", _lb_ex_cases(), ids=lambda c: c["name"])
+def test_lb_ex_hand_worked(oracle, case):
+    r = _lb_ex(oracle, case)
+    assert r["rc"] == 0 and int(r["status"][0]) == 0
+    assert r["parts"][0].tolist() == case["parts"]
+    assert int(r["lb"][0]) == case["lb"]
+
+
+def test_lb_ex_reduces_to_the_basic_bound(oracle):
+    """With kmax = 1, no caps and a one-level table the extended bound is the basic one."""
+    rng = np.random.default_rng(41)
+    for N, M in [(1, 1), (3, 5), (9, 4), (64, 4), (200, 7), (33, 32)]:
+        c = rng.integers(0, 1000, size=(6, N)).astype(np.int64)
+        tok = rng.integers(1, 3000, size=(6, N)).astype(np.int32)
+        a = oracle.lower_bound(c, M, prefill_tokens=tok, ncap_L=5000, tp_L=675000)
+        b = oracle.lower_bound_ex(c, M, kmax=1, prefill_tokens=tok, ncap=[5000], tp=[675000], tp_form=0)
+        assert a["lb"].tolist() == b["lb"].tolist()
+        more = oracle.lower_bound_ex(c, M, prefill_tokens=tok, ncap=[5000], tp=[675000], tp_form=0)
+        assert (more["lb"] >= a["lb"]).all()
+
+
+def test_lb_ex_closed_forms(oracle):
+    # N = kM + 1 equal costs c: some client holds k+1 of them; LB = OPT = (k+1) c, reached by L3(k) alone
+    for k, M, cst in [(1, 3, 7), (2, 3, 7), (3, 2, 11), (2, 4, 5)]:
+        N = k * M + 1
+        c = np.full((1, N), cst, np.int64)
+        r = oracle.lower_bound_ex(c, M)
+        assert int(r["lb"][0]) == (k + 1) * cst and int(r["parts"][0][3]) == k
+        if N <= 9:
+            assert oracle.brute_force_opt(c[0], M, N) == (k + 1) * cst
+    # N = kM + 1 with one small job and kM equal large ones: L3(k) = k large + the small one, the earlier
+    # terms are (k'+1) large for k' < k, so the maximum is at k - 1 unless the small job is large enough
+    c = np.array([[20] * 8 + [1]], np.int64)                             # M = 4, k = 2: L3(1) = 40, L3(2) = 41
+    assert oracle.lower_bound_ex(c, 4)["parts"][0][2:4].tolist() == [41, 2]
+    c = np.array([[20] * 8 + [0]], np.int64)                             # L3(2) = 40 = L3(1): the smaller k is reported
+    assert oracle.lower_bound_ex(c, 4)["parts"][0][2:4].tolist() == [40, 1]
+    rng = np.random.default_rng(43)
+    # caps: uniform cap C -> every client holds at least N - (M-1)C jobs; tight caps (M*C == N) force C each
+    c = rng.integers(1, 50, size=(1, 12)).astype(np.int64)
+    r = oracle.lower_bound_ex(c, 3, cap=[4, 4, 4])
+    assert int(r["parts"][0][4]) == int(np.sort(c[0])[:4].sum())
+    r = oracle.lower_bound_ex(c, 3, cap=[12, 12, 12])
+    assert int(r["parts"][0][4]) == 0
+    # the rank limit only removes terms: a valid bound either way, never larger than with all ranks
+    c = rng.integers(1, 50, size=(4, 40)).astype(np.int64)
+    full = oracle.lower_bound_ex(c, 3)
+    cut = oracle.lower_bound_ex(c, 3, rank_limit=10)                      # k <= 3
+    lim = oracle.lower_bound_ex(c, 3, kmax=3)
+    assert cut["parts"].tolist() == lim["parts"].tolist() and (cut["lb"] <= full["lb"]).all()
+
+
+def test_lb_ex_below_bruteforce_opt_with_caps(oracle):
+    """LB <= OPT by enumeration, per-client caps included; the brute force itself is checked
+    against the definition-level enumeration."""
+    from oracle import definition as D
+    rng = np.random.default_rng(47)
+    seen_cap_decides = seen_l3k_decides = False
+    for N, M in [(6, 2), (7, 3), (8, 3), (9, 4), (7, 2), (9, 2)]:
+        for trial in range(10):
+            c = rng.integers(0, 30, size=(1, N)).astype(np.int64)
+            if trial % 2 == 0:
+                c[:] = rng.integers(10, 13)                # near-equal costs: the counting bounds decide
+                c[0, : N // 3] += rng.integers(0, 3, size=N // 3)
+            caps = rng.integers(1, N + 1, size=M)
+            while caps.sum() < N:
+                caps[rng.integers(M)] += 1
+            r = oracle.lower_bound_ex(c, M, cap=caps)
+            opt = oracle.brute_force_opt_caps(c[0], M, caps)
+            if N <= 7:
+                assert opt == D.brute_force_opt_caps(c[0].tolist(), M, caps.tolist())
+            assert int(r["lb"][0]) <= opt, (c, caps, r["parts"])
+            L1, L2, L3, k3, Lcap, _ = r["parts"][0].tolist()
+            seen_cap_decides |= Lcap > max(L1, L2, L3)
+            seen_l3k_decides |= L3 > max(L1, L2) and k3 >= 2
+            free = oracle.lower_bound_ex(c, M)
+            assert int(free["lb"][0]) <= oracle.brute_force_opt(c[0], M, N)
+    assert seen_cap_decides and seen_l3k_decides        # the cases must exercise the new terms
+
+
+def test_lb_ex_status_and_return_codes(oracle):
+    c = np.array([[5, 3, 2, 1], [5, -3, 2, 1]], np.int64)
+    r = oracle.lower_bound_ex(c, 2)
+    assert r["rc"] == 0 and r["status"].tolist() == [0, 3] and int(r["lb"][1]) == 0
+    assert oracle.lower_bound_ex(c, 2, cap=[1, 2])["rc"] == -2                 # caps cannot hold the requests
+    assert oracle.lower_bound_ex(c, 2, cap=[-1, 9])["rc"] == -1
+    tok = np.array([[1, 2, 3, 4], [1, 2, -3, 4]], np.int32)
+    r = oracle.lower_bound_ex(c[:1].repeat(2, 0), 2, prefill_tokens=tok, ncap=[4], tp=[10])
+    assert r["status"].tolist() == [0, 3] and int(r["lb"][0]) == 6 + 10 * 2
+    assert oracle.lower_bound_ex(c, 2, prefill_tokens=tok, ncap=[0], tp=[10])["rc"] == -1
+    assert oracle.lower_bound_ex(c, 2, prefill_tokens=tok, ncap=[4], tp=[10], tp_form=2)["rc"] == -1
+
+
 # ------------------------------------------------------------------ simulator
 def test_time_model_worked_examples(oracle):
     with open(GOLD) as f:
