@@ -104,6 +104,40 @@ int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M,
                      int64_t *lb_out, int32_t *status_out, void *stream);
 
 /*
+ * The same bound T^LB = t^p* + t^d* with stronger relaxations of t^d* and a level table for t^p*
+ * (levels l of the paper's prefill-length constraints: a prefill stage of level l holds at most
+ * N^cap_l tokens and takes T^p_l).
+ *   L1 = ceil(sum_i T_i / M), L2 = max_i T_i as in mmbp_lower_bound;
+ *   L3(k) = T_(kM+1) + T_(kM) + ... + T_(kM+1-k) (descending order): of the kM+1 largest requests
+ *           some client holds k+1.  Evaluated for every k >= 1 with kM+1 <= min(N, MMBP_LB_RANK_LIMIT)
+ *           and, if kmax > 0, k <= kmax; L3 = the largest of them (k = 1 is mmbp_lower_bound's term);
+ *   Lcap  with per-client cardinality limits cap[j]: client j holds at least
+ *           n_j = max(0, N - sum_{j' != j} cap[j']) requests, hence at least the n_j smallest costs;
+ *           Lcap = sum of the max_j n_j smallest costs;
+ *   t^p*  tp_form MMBP_TP_FLOOR_LARGEST: the paper's form T^p_L * floor(sum_i N^p_i / N^cap_L) on the
+ *           level L of largest capacity (equal capacities: the smaller time);
+ *         tp_form MMBP_TP_COVER: min_l ceil(sum_i N^p_i * T^p_l / N^cap_l), a bound for every table
+ *           (stages that cover all tokens cannot beat the most efficient level's time per token).
+ *   lb = max(L1, L2, L3, Lcap) + t^p*.
+ * cost            [S,N] int32 or int64 per `dtype`, T_i >= 0
+ * cap             HOST [M] int32, nullable (no limits); sum cap[j] < N returns MMBP_EINFEASIBLE
+ * prefill_tokens  [S,N] int32 N^p_i >= 0, nullable; the t^p* term needs it and n_levels > 0
+ * ncap, tp        HOST [n_levels] int64, 1 <= ncap[l] < 2^31, 0 <= tp[l] < 2^31; n_levels <= MMBP_LB_MAX_LEVELS
+ * lb_out          [S] int64
+ * parts_out       [S,6] int64, nullable: L1, L2, L3, the smallest k that attains L3 (0: none), Lcap, t^p*
+ * status_out      [S] int32: MMBP_ST_OK, or MMBP_ST_BAD_COST (negative cost or token count, sum of costs
+ *                 or t^p* not below 2^62): then lb_out and parts_out of the scenario are 0
+ */
+#define MMBP_TP_FLOOR_LARGEST 0
+#define MMBP_TP_COVER         1
+#define MMBP_LB_RANK_LIMIT    16384
+#define MMBP_LB_MAX_LEVELS    16
+int mmbp_lower_bound_ex(const void *cost, int dtype, int S, int N, int M, const int32_t *cap /* host */, int kmax,
+                        const int32_t *prefill_tokens, int n_levels, const int64_t *ncap /* host */,
+                        const int64_t *tp /* host */, int tp_form, int64_t *lb_out, int64_t *parts_out,
+                        int32_t *status_out, void *stream);
+
+/*
  * Best-improvement local search on the MMBP model (same section: min max_j t_j, every request
  * on exactly one client, t_j = sum of the T_i assigned to j), with at most `cap` requests per
  * client.  Each pass evaluates the makespan that EVERY candidate would give,

@@ -21,7 +21,7 @@ EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 GRID_MAX_PASSES = 4096
 STATIC_SCRATCH_BYTES = 16 << 20
 
-EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_valu_probe", "mmbp_lower_bound",
+EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_valu_probe", "mmbp_lower_bound", "mmbp_lower_bound_ex",
            "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
            "online_iter_sim_assigned")
 
@@ -62,6 +62,9 @@ def load_library() -> C.CDLL:
     lib.mmbp_valu_probe.argtypes = [vp, i, i, C.POINTER(C.c_uint64), vp]
     lib.mmbp_lower_bound.restype = i
     lib.mmbp_lower_bound.argtypes = [vp, i, i, i, i, vp, i64, i64, vp, vp, vp]
+    lib.mmbp_lower_bound_ex.restype = i
+    lib.mmbp_lower_bound_ex.argtypes = [vp, i, i, i, i, C.POINTER(C.c_int32), i, vp, i, C.POINTER(i64), C.POINTER(i64), i,
+                                        vp, vp, vp, vp]
     lib.mmbp_local_search.restype = i
     lib.mmbp_local_search.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mmbp_local_search_pruned.restype = i
@@ -151,6 +154,27 @@ def mmbp_lower_bound(cost, M, lb_out, status_out, prefill_tokens=None, ncap_L=0,
         _ptr(prefill_tokens, torch.int32, (S, N), "prefill_tokens"), int(ncap_L), int(tp_L),
         _ptr(lb_out, torch.int64, (S,), "lb_out"), _ptr(status_out, torch.int32, (S,), "status_out"),
         _stream(stream))
+    return _check(rc, raise_on_error)
+
+
+TP_FLOOR_LARGEST, TP_COVER = 0, 1
+LB_RANK_LIMIT = 16384
+
+
+def mmbp_lower_bound_ex(cost, M, lb_out, status_out, cap=None, kmax=0, prefill_tokens=None, ncap=None, tp=None,
+                        tp_form=TP_FLOOR_LARGEST, parts_out=None, stream=None, raise_on_error=True) -> int:
+    """cap: host sequence of M ints or None; ncap / tp: host sequences (the level table) or None."""
+    torch = _torch()
+    S, N = cost.shape
+    cap_arr = (C.c_int32 * int(M))(*[int(x) for x in cap]) if cap is not None else None
+    nl = len(ncap) if ncap is not None else 0
+    ncap_arr = (C.c_int64 * nl)(*[int(x) for x in ncap]) if nl else None
+    tp_arr = (C.c_int64 * nl)(*[int(x) for x in tp]) if nl else None
+    rc = load_library().mmbp_lower_bound_ex(
+        _ptr(cost, name="cost"), _cost_dtype(cost), S, N, int(M), cap_arr, int(kmax),
+        _ptr(prefill_tokens, torch.int32, (S, N), "prefill_tokens"), nl, ncap_arr, tp_arr, int(tp_form),
+        _ptr(lb_out, torch.int64, (S,), "lb_out"), _ptr(parts_out, torch.int64, (S, 6), "parts_out"),
+        _ptr(status_out, torch.int32, (S,), "status_out"), _stream(stream))
     return _check(rc, raise_on_error)
 
 
@@ -284,6 +308,18 @@ def run_lower_bound(cost, M, prefill_tokens=None, ncap_L=0, tp_L=0, stream=None,
     st = torch.empty(S, dtype=torch.int32, device=cost.device)
     rc = mmbp_lower_bound(cost, M, lb, st, prefill_tokens, ncap_L, tp_L, stream=stream, raise_on_error=raise_on_error)
     return dict(rc=rc, lb=lb, status=st)
+
+
+def run_lower_bound_ex(cost, M, cap=None, kmax=0, prefill_tokens=None, ncap=None, tp=None, tp_form=TP_FLOOR_LARGEST,
+                       stream=None, raise_on_error=True):
+    torch = _torch()
+    S = cost.shape[0]
+    lb = torch.empty(S, dtype=torch.int64, device=cost.device)
+    parts = torch.empty((S, 6), dtype=torch.int64, device=cost.device)
+    st = torch.empty(S, dtype=torch.int32, device=cost.device)
+    rc = mmbp_lower_bound_ex(cost, M, lb, st, cap=cap, kmax=kmax, prefill_tokens=prefill_tokens, ncap=ncap, tp=tp,
+                             tp_form=tp_form, parts_out=parts, stream=stream, raise_on_error=raise_on_error)
+    return dict(rc=rc, lb=lb, parts=parts, status=st)
 
 
 def run_online_sim(arrival_us, in_len, out_len, params, trace_scenarios=0, trace_capacity=0, stream=None,

@@ -1,5 +1,6 @@
 // C-ABI boundary of libmmbp: argument validation, path selection, kernel launches on the caller's
 // stream.  No allocation, no synchronisation.
+#include <climits>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -106,6 +107,39 @@ int mmbp_lower_bound(const void *cost, int dtype, int S, int N, int M, const int
     hipError_t e = mmbp::launch_lower_bound(cost, dtype, S, N, M, prefill_tokens, ncap_L, tp_L, lb_out, status_out,
                                             (hipStream_t)stream);
     return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_lower_bound");
+}
+
+int mmbp_lower_bound_ex(const void *cost, int dtype, int S, int N, int M, const int32_t *cap, int kmax,
+                        const int32_t *prefill_tokens, int n_levels, const int64_t *ncap, const int64_t *tp, int tp_form,
+                        int64_t *lb_out, int64_t *parts_out, int32_t *status_out, void *stream)
+{
+    if (!cost || !lb_out || !status_out) return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || M <= 0) return MMBP_EINVAL;
+    if (dtype != MMBP_I32 && dtype != MMBP_I64) return MMBP_EINVAL;
+    if (n_levels < 0 || (n_levels > 0 && (!ncap || !tp))) return MMBP_EINVAL;
+    if (tp_form != MMBP_TP_FLOOR_LARGEST && tp_form != MMBP_TP_COVER) return MMBP_EINVAL;
+    if (N > MMBP_MAX_N || M > MMBP_MAX_M || n_levels > MMBP_LB_MAX_LEVELS) return MMBP_EUNSUPPORTED;
+    for (int l = 0; l < n_levels; l++)
+        if (ncap[l] < 1 || ncap[l] > INT32_MAX || tp[l] < 0 || tp[l] > INT32_MAX) return MMBP_EINVAL;
+    int nstar = 0;                                       // the most requests the limits force onto one client
+    if (cap) {
+        int64_t capsum = 0;
+        for (int j = 0; j < M; j++) {
+            if (cap[j] < 0) return MMBP_EINVAL;
+            capsum += cap[j];
+        }
+        if (capsum < N) return MMBP_EINFEASIBLE;
+        for (int j = 0; j < M; j++) {
+            const int64_t nj = (int64_t)N - (capsum - cap[j]);
+            if (nj > nstar) nstar = (int)nj;
+        }
+    }
+    int K = (N - 1) / M;                                 // terms L3(k): k*M + 1 <= N, within the rank limit and the caller's
+    if (K > (MMBP_LB_RANK_LIMIT - 1) / M) K = (MMBP_LB_RANK_LIMIT - 1) / M;
+    if (kmax > 0 && K > kmax) K = kmax;
+    hipError_t e = mmbp::launch_lower_bound_ex(cost, dtype, S, N, M, K, nstar, prefill_tokens, n_levels, ncap, tp, tp_form,
+                                               lb_out, parts_out, status_out, (hipStream_t)stream);
+    return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_lower_bound_ex");
 }
 
 static int local_search_impl(int prune, const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int32_t *assign,

@@ -61,6 +61,16 @@ def gpu_lower_bound(cost, M, prefill_tokens=None, ncap_L=0, tp_L=0):
     return dict(rc=r["rc"], lb=r["lb"].cpu().numpy(), status=r["status"].cpu().numpy())
 
 
+def gpu_lower_bound_ex(cost, M, cap=None, kmax=0, prefill_tokens=None, ncap=None, tp=None, tp_form=0):
+    import torch
+    from paper_2502_15763_amd import api
+    pt = to_dev(prefill_tokens.astype(np.int32)) if prefill_tokens is not None else None
+    r = api.run_lower_bound_ex(to_dev(cost), M, cap=cap, kmax=kmax, prefill_tokens=pt, ncap=ncap, tp=tp, tp_form=tp_form,
+                               raise_on_error=False)
+    torch.cuda.synchronize()
+    return dict(rc=r["rc"], lb=r["lb"].cpu().numpy(), parts=r["parts"].cpu().numpy(), status=r["status"].cpu().numpy())
+
+
 def gpu_online_sim(arrival, in_len, out_len, params, trace_scenarios=0, trace_capacity=0):
     import torch
     from paper_2502_15763_amd import api

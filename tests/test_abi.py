@@ -21,7 +21,7 @@ def _declared_functions():
 
 def test_header_declares_expected_entry_points():
     names = _declared_functions()
-    for n in ("mmbp_lower_bound", "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
+    for n in ("mmbp_lower_bound", "mmbp_lower_bound_ex", "mmbp_valu_probe", "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
               "online_iter_sim_assigned", "mmbp_workspace_bytes",
               "mmbp_strerror", "mmbp_version"):
         assert n in names
@@ -72,6 +72,18 @@ def test_host_side_argument_validation():
     assert lb(None, 0, 1, 4, 2, None, 0, 0, one, one, None) == api.EINVAL
     assert lb(one, 0, 1, 4, 0, None, 0, 0, one, one, None) == api.EINVAL
     assert lb(one, 3, 1, 4, 2, None, 0, 0, one, one, None) == api.EINVAL
+    lbx = lib.mmbp_lower_bound_ex
+    i32a = lambda *v: (C.c_int32 * len(v))(*v)
+    i64a = lambda *v: (C.c_int64 * len(v))(*v)
+    assert lbx(None, 0, 1, 4, 2, None, 0, None, 0, None, None, 0, one, None, one, None) == api.EINVAL
+    assert lbx(one, 0, 1, 4, 2, None, 0, None, 0, None, None, 2, one, None, one, None) == api.EINVAL           # tp_form
+    assert lbx(one, 0, 1, 4, 2, None, 0, one, 1, None, None, 0, one, None, one, None) == api.EINVAL            # levels missing
+    assert lbx(one, 0, 1, 4, 2, None, 0, one, 1, i64a(0), i64a(5), 0, one, None, one, None) == api.EINVAL      # ncap < 1
+    assert lbx(one, 0, 1, 4, 2, None, 0, one, 1, i64a(5), i64a(1 << 31), 0, one, None, one, None) == api.EINVAL
+    assert lbx(one, 0, 1, 4, 2, i32a(1, 2), 0, None, 0, None, None, 0, one, None, one, None) == api.EINFEASIBLE
+    assert lbx(one, 0, 1, 4, 2, i32a(-1, 9), 0, None, 0, None, None, 0, one, None, one, None) == api.EINVAL
+    assert lbx(one, 0, 1, 4, 2, None, 0, one, 17, i64a(*[5] * 17), i64a(*[5] * 17), 0, one, None, one, None) == api.EUNSUPPORTED
+    assert lbx(one, 0, 1, 4, 257, None, 0, None, 0, None, None, 0, one, None, one, None) == api.EUNSUPPORTED
     sim = lib.online_iter_sim
     p = api.SimParams(65, 0, 1, 1, 1, 1, 0)
     args = lambda pp: (one, one, one, 1, 4, C.byref(pp), one, one, one, one, one, one, None, None, 0, 0, one, None)

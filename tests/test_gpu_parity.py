@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from paper_2502_15763_amd import workloads as W
-from gpu_util import (say, gpu_local_search, compare_ls, gpu_lower_bound, gpu_online_sim, compare_sim,
+from gpu_util import (say, gpu_local_search, compare_ls, gpu_lower_bound, gpu_lower_bound_ex, gpu_online_sim, compare_sim,
                       gpu_online_sim_assigned)
 
 pytestmark = pytest.mark.gpu
@@ -491,6 +491,60 @@ def test_sim_config5_full(oracle):
     say("sim config5 oracle, all scenarios")
     o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, w.params, trace_scenarios=4, trace_capacity=8192)
     compare_sim(g, o, label="c5")
+
+
+def _same_lb_ex(g, o, label):
+    assert g["rc"] == o["rc"], (label, g["rc"], o["rc"])
+    if o["rc"] != 0:
+        return
+    for k in ("status", "lb", "parts"):
+        assert np.array_equal(g[k], o[k]), f"{label}: {k} differs: gpu {g[k][:3]} oracle {o[k][:3]}"
+
+
+def test_lb_ex_parity(oracle):
+    """Extended bound: every term (L1, L2, L3 and its k, Lcap, t^p*) and the total, bit for bit."""
+    rng = np.random.default_rng(53)
+    levels = dict(ncap=[1000, 5000, 2048], tp=[155000, 675000, 300000])
+    for (N, M, hi, dtype) in [(1, 1, 10, np.int32), (3, 5, 10, np.int64), (5, 4, 100, np.int32), (9, 8, 3, np.int32),
+                              (13, 4, 50, np.int64), (64, 4, 40000, np.int32), (1000, 7, 1 << 20, np.int64),
+                              (4097, 16, 1 << 40, np.int64), (5000, 256, 1000, np.int32), (300, 255, 7, np.int32),
+                              (16385, 1, 1000, np.int32), (40000, 3, 100000, np.int32), (2000, 2, 0, np.int32)]:
+        say(f"lb_ex N={N} M={M}")
+        S = 5
+        cost = rng.integers(0, hi + 1, size=(S, N)).astype(dtype)
+        tok = rng.integers(0, 3000, size=(S, N)).astype(np.int32)
+        caps = rng.integers(0, 2 * (N // M + 1) + 1, size=M)
+        while caps.sum() < N:
+            caps[rng.integers(M)] += N // M + 1
+        for kw in (dict(), dict(kmax=1), dict(kmax=3, cap=caps.tolist()), dict(cap=caps.tolist(), prefill_tokens=tok, tp_form=0, **levels),
+                   dict(prefill_tokens=tok, tp_form=1, **levels), dict(cap=[N] + [0] * (M - 1))):
+            _same_lb_ex(gpu_lower_bound_ex(cost, M, **kw), oracle.lower_bound_ex(cost, M, **kw), f"N={N} M={M} {sorted(kw)}")
+    # bad scenarios, bad arguments
+    cost = np.array([[3, -1, 4, 2], [1, 2, 3, 4], [5, 5, 5, 5]], np.int64)
+    tok = np.array([[1, 1, 1, 1], [1, -1, 1, 1], [2 ** 31 - 1] * 4], np.int32)
+    for kw in (dict(), dict(prefill_tokens=tok, ncap=[4], tp=[10]), dict(prefill_tokens=tok, ncap=[1], tp=[2 ** 31 - 1], tp_form=1),
+               dict(cap=[1, 2]), dict(cap=[-1, 9])):
+        _same_lb_ex(gpu_lower_bound_ex(cost, 2, **kw), oracle.lower_bound_ex(cost, 2, **kw), f"bad inputs {sorted(kw)}")
+    o = oracle.lower_bound_ex(cost, 2, prefill_tokens=tok, ncap=[4], tp=[10])
+    assert o["status"].tolist() == [3, 3, 0]
+
+
+def test_lb_ex_hand_worked_and_configs(oracle):
+    from test_oracle_lb_sim import _lb_ex_cases
+    for c in _lb_ex_cases():
+        kw = {}
+        if c["levels"]:
+            kw = dict(prefill_tokens=np.array([c["tokens"]], np.int32), ncap=[l[0] for l in c["levels"]],
+                      tp=[l[1] for l in c["levels"]], tp_form=c["tp_form"])
+        g = gpu_lower_bound_ex(np.array([c["cost"]], np.int64), c["M"], cap=c["caps"], kmax=c["kmax"], **kw)
+        assert g["rc"] == 0 and g["parts"][0].tolist() == c["parts"] and int(g["lb"][0]) == c["lb"], c["name"]
+    for c in (W.config1(), W.config2(), W.config3(S=256), W.config4()):
+        say(f"lb_ex config {c.name}")
+        caps = [c.cap] * c.M
+        o = oracle.lower_bound_ex(c.cost, c.M, cap=caps)
+        _same_lb_ex(gpu_lower_bound_ex(c.cost, c.M, cap=caps), o, c.name)
+        basic = oracle.lower_bound(c.cost, c.M)
+        assert (o["lb"] >= basic["lb"]).all()
 
 
 # ------------------------------------------------------------------ simulator fed by an offline assignment
