@@ -295,6 +295,67 @@ int oracle_lower_bound(const int64_t *cost, int S, int N, int M, const int32_t *
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Longest-processing-time start for the MMBP model (min max_j t_j with at most cap requests per
+ * client): take the requests by decreasing cost T_i (equal costs: lower index first) and give
+ * each to the client with the smallest load t_j among those that still have room (equal loads:
+ * lower client index).  The classical list-scheduling rule; with cap >= N its makespan is at
+ * most (4/3 - 1/(3M)) times the optimum.
+ * order_out (nullable) receives the request indices in the order they were taken.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct { int64_t cost; int32_t idx; } lpt_item;
+
+static int cmp_lpt(const void *x, const void *y)
+{
+    const lpt_item *a = (const lpt_item *)x, *b = (const lpt_item *)y;
+    if (a->cost != b->cost) return a->cost < b->cost ? 1 : -1;
+    return a->idx < b->idx ? -1 : (a->idx > b->idx ? 1 : 0);
+}
+
+int oracle_lpt_start(const int64_t *cost, int S, int N, int M, int cap, int32_t *assign_out,
+                     int64_t *load_out, int32_t *order_out, int32_t *status_out)
+{
+    if (!cost || !assign_out || !load_out || !status_out || S <= 0 || N <= 0 || M <= 0 || cap <= 0) return -1;
+    if ((int64_t)N > (int64_t)M * cap) return -2;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < S; s++) {
+        const int64_t *c = cost + (size_t)s * N;
+        int32_t *asg = assign_out + (size_t)s * N;
+        int64_t *load = load_out + (size_t)s * M;
+        for (int j = 0; j < M; j++) load[j] = 0;
+        int bad = 0;
+        int64_t sum = 0;
+        for (int i = 0; i < N; i++) {
+            if (c[i] < 0 || c[i] >= COST_SUM_LIMIT || sum + c[i] >= COST_SUM_LIMIT) { bad = 1; break; }
+            sum += c[i];
+        }
+        if (bad) {
+            status_out[s] = ST_BAD_COST;
+            for (int i = 0; i < N; i++) { asg[i] = -1; if (order_out) order_out[(size_t)s * N + i] = -1; }
+            continue;
+        }
+        lpt_item *it = (lpt_item *)malloc((size_t)N * sizeof(lpt_item));
+        int32_t *cnt = (int32_t *)calloc((size_t)M, sizeof(int32_t));
+        for (int i = 0; i < N; i++) { it[i].cost = c[i]; it[i].idx = i; }
+        qsort(it, (size_t)N, sizeof(lpt_item), cmp_lpt);
+        for (int q = 0; q < N; q++) {
+            int best = -1;
+            for (int j = 0; j < M; j++) {
+                if (cnt[j] >= cap) continue;
+                if (best < 0 || load[j] < load[best]) best = j;
+            }
+            /* N <= M*cap: some client has room */
+            asg[it[q].idx] = best;
+            load[best] += it[q].cost;
+            cnt[best]++;
+            if (order_out) order_out[(size_t)s * N + q] = it[q].idx;
+        }
+        status_out[s] = ST_OK;
+        free(it); free(cnt);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
  * Extended lower bound.  Same equation T^LB = t^p* + t^d*, with more relaxation bounds on t^d*
  * and a level table for t^p* (levels l with token capacity N^cap_l and prefill time T^p_l, as in
  * the paper's prefill-length constraints).

@@ -109,6 +109,17 @@ def brute_force_opt_caps(cost_row, M, caps) -> int:
     return int(lib().oracle_brute_force_opt_caps(_p(c), int(c.shape[0]), int(M), _p(k)))
 
 
+def lpt_start(cost, M, cap):
+    cost = np.ascontiguousarray(cost, dtype=np.int64)
+    S, N = cost.shape
+    assign = np.zeros((S, N), np.int32)
+    load = np.zeros((S, M), np.int64)
+    order = np.zeros((S, N), np.int32)
+    status = np.zeros(S, np.int32)
+    rc = lib().oracle_lpt_start(_p(cost), S, N, int(M), int(cap), _p(assign), _p(load), _p(order), _p(status))
+    return dict(rc=rc, assign=assign, load=load, order=order, status=status)
+
+
 def make_params(cap, a_prefill, b_decode, c_prefill, c_decode, max_prefill_tokens=0, policy=0):
     return SimParams(cap, policy, a_prefill, b_decode, c_prefill, c_decode, max_prefill_tokens)
 
