@@ -138,6 +138,24 @@ int mmbp_lower_bound_ex(const void *cost, int dtype, int S, int N, int M, const 
                         int32_t *status_out, void *stream);
 
 /*
+ * A start for the local search: the longest-processing-time rule on the MMBP model (same section;
+ * objective min max_j t_j) with at most `cap` requests per client.  The requests are taken by
+ * decreasing T_i (equal costs: lower index first) and each goes to the client with the smallest load
+ * among those that still have room (equal loads: lower client index).  With cap >= N the makespan is
+ * at most (4/3 - 1/(3M)) times the optimum of the model.
+ * cost        [S,N] int32 / int64 per `dtype`, T_i >= 0;  N <= MMBP_LPT_MAX_N
+ * assign_out  [S,N] int32: the client of every request (a feasible start for mmbp_local_search)
+ * load_out    [S,M] int64 t_j of that assignment
+ * order_out   [S,N] int32: the request indices in the order they were taken (required: the kernel
+ *             also uses it to hand the order from its sorting phase to its assignment phase)
+ * status_out  [S] int32: MMBP_ST_OK, or MMBP_ST_BAD_COST (then assign_out and order_out are -1, loads 0)
+ * Returns MMBP_EINFEASIBLE when N > M * cap.
+ */
+#define MMBP_LPT_MAX_N 16384
+int mmbp_lpt_start(const void *cost, int dtype, int S, int N, int M, int cap, int32_t *assign_out,
+                   int64_t *load_out, int32_t *order_out, int32_t *status_out, void *stream);
+
+/*
  * Best-improvement local search on the MMBP model (same section: min max_j t_j, every request
  * on exactly one client, t_j = sum of the T_i assigned to j), with at most `cap` requests per
  * client.  Each pass evaluates the makespan that EVERY candidate would give,

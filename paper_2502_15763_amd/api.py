@@ -21,7 +21,7 @@ EINVAL, EINFEASIBLE, EUNSUPPORTED, EWORKSPACE, EHIP = -1, -2, -3, -4, -5
 GRID_MAX_PASSES = 4096
 STATIC_SCRATCH_BYTES = 16 << 20
 
-EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_valu_probe", "mmbp_lower_bound", "mmbp_lower_bound_ex",
+EXPORTS = ("mmbp_version", "mmbp_strerror", "mmbp_workspace_bytes", "mmbp_valu_probe", "mmbp_lower_bound", "mmbp_lower_bound_ex", "mmbp_lpt_start",
            "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
            "online_iter_sim_assigned")
 
@@ -65,6 +65,8 @@ def load_library() -> C.CDLL:
     lib.mmbp_lower_bound_ex.restype = i
     lib.mmbp_lower_bound_ex.argtypes = [vp, i, i, i, i, C.POINTER(C.c_int32), i, vp, i, C.POINTER(i64), C.POINTER(i64), i,
                                         vp, vp, vp, vp]
+    lib.mmbp_lpt_start.restype = i
+    lib.mmbp_lpt_start.argtypes = [vp, i, i, i, i, i, vp, vp, vp, vp, vp]
     lib.mmbp_local_search.restype = i
     lib.mmbp_local_search.argtypes = [vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.mmbp_local_search_pruned.restype = i
@@ -175,6 +177,20 @@ def mmbp_lower_bound_ex(cost, M, lb_out, status_out, cap=None, kmax=0, prefill_t
         _ptr(prefill_tokens, torch.int32, (S, N), "prefill_tokens"), nl, ncap_arr, tp_arr, int(tp_form),
         _ptr(lb_out, torch.int64, (S,), "lb_out"), _ptr(parts_out, torch.int64, (S, 6), "parts_out"),
         _ptr(status_out, torch.int32, (S,), "status_out"), _stream(stream))
+    return _check(rc, raise_on_error)
+
+
+LPT_MAX_N = 16384
+
+
+def mmbp_lpt_start(cost, M, cap, assign_out, load_out, order_out, status_out, stream=None, raise_on_error=True) -> int:
+    torch = _torch()
+    S, N = cost.shape
+    rc = load_library().mmbp_lpt_start(
+        _ptr(cost, name="cost"), _cost_dtype(cost), S, N, int(M), int(cap),
+        _ptr(assign_out, torch.int32, (S, N), "assign_out"), _ptr(load_out, torch.int64, (S, M), "load_out"),
+        _ptr(order_out, torch.int32, (S, N), "order_out"), _ptr(status_out, torch.int32, (S,), "status_out"),
+        _stream(stream))
     return _check(rc, raise_on_error)
 
 
@@ -308,6 +324,17 @@ def run_lower_bound(cost, M, prefill_tokens=None, ncap_L=0, tp_L=0, stream=None,
     st = torch.empty(S, dtype=torch.int32, device=cost.device)
     rc = mmbp_lower_bound(cost, M, lb, st, prefill_tokens, ncap_L, tp_L, stream=stream, raise_on_error=raise_on_error)
     return dict(rc=rc, lb=lb, status=st)
+
+
+def run_lpt_start(cost, M, cap, stream=None, raise_on_error=True):
+    torch = _torch()
+    S, N = cost.shape
+    dev = cost.device
+    out = dict(assign=torch.empty((S, N), dtype=torch.int32, device=dev), load=torch.empty((S, M), dtype=torch.int64, device=dev),
+               order=torch.empty((S, N), dtype=torch.int32, device=dev), status=torch.empty(S, dtype=torch.int32, device=dev))
+    out["rc"] = mmbp_lpt_start(cost, M, cap, out["assign"], out["load"], out["order"], out["status"], stream=stream,
+                               raise_on_error=raise_on_error)
+    return out
 
 
 def run_lower_bound_ex(cost, M, cap=None, kmax=0, prefill_tokens=None, ncap=None, tp=None, tp_form=TP_FLOOR_LARGEST,

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmmbp.so")
-SOURCES = ["mmbp_api.hip", "ls_generic.hip", "ls_lds.hip", "ls_grid.hip", "lower_bound.hip", "lower_bound_ex.hip", "online_sim.hip",
+SOURCES = ["mmbp_api.hip", "ls_generic.hip", "ls_lds.hip", "ls_grid.hip", "lower_bound.hip", "lower_bound_ex.hip", "lpt_start.hip", "online_sim.hip",
            "online_sim_assigned.hip", "valu_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -142,6 +142,19 @@ int mmbp_lower_bound_ex(const void *cost, int dtype, int S, int N, int M, const 
     return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_lower_bound_ex");
 }
 
+int mmbp_lpt_start(const void *cost, int dtype, int S, int N, int M, int cap, int32_t *assign_out, int64_t *load_out,
+                   int32_t *order_out, int32_t *status_out, void *stream)
+{
+    if (!cost || !assign_out || !load_out || !order_out || !status_out) return MMBP_EINVAL;
+    if (S <= 0 || N <= 0 || M <= 0 || cap <= 0) return MMBP_EINVAL;
+    if (dtype != MMBP_I32 && dtype != MMBP_I64) return MMBP_EINVAL;
+    if (N > MMBP_LPT_MAX_N || M > MMBP_MAX_M) return MMBP_EUNSUPPORTED;
+    if ((int64_t)N > (int64_t)M * (int64_t)cap) return MMBP_EINFEASIBLE;
+    hipError_t e = mmbp::launch_lpt_start(cost, dtype, S, N, M, cap, assign_out, load_out, order_out, status_out,
+                                          (hipStream_t)stream);
+    return e == hipSuccess ? MMBP_OK : fail_hip(e, "mmbp_lpt_start");
+}
+
 static int local_search_impl(int prune, const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int32_t *assign,
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, void *workspace, size_t workspace_bytes,

@@ -36,6 +36,9 @@ hipError_t launch_lower_bound_ex(const void *cost, int dtype, int S, int N, int 
                                  const int32_t *prefill_tokens, int n_levels, const int64_t *ncap, const int64_t *tp,
                                  int tp_form, int64_t *lb_out, int64_t *parts_out, int32_t *status_out, hipStream_t st);
 
+hipError_t launch_lpt_start(const void *cost, int dtype, int S, int N, int M, int cap, int32_t *assign_out,
+                            int64_t *load_out, int32_t *order_out, int32_t *status_out, hipStream_t st);
+
 hipError_t launch_online_sim(const int64_t *arrival_us, const int32_t *in_len, const int32_t *out_len, int S, int N,
                              const mmbp_sim_params &p, int64_t *finish_us, int64_t *total_us, int64_t *busy_slot_us,
                              int32_t *n_prefill_iter, int32_t *n_decode_iter, uint64_t *trace_hash,

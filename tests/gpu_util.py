@@ -71,6 +71,15 @@ def gpu_lower_bound_ex(cost, M, cap=None, kmax=0, prefill_tokens=None, ncap=None
     return dict(rc=r["rc"], lb=r["lb"].cpu().numpy(), parts=r["parts"].cpu().numpy(), status=r["status"].cpu().numpy())
 
 
+def gpu_lpt_start(cost, M, cap):
+    import torch
+    from paper_2502_15763_amd import api
+    r = api.run_lpt_start(to_dev(cost), M, cap, raise_on_error=False)
+    torch.cuda.synchronize()
+    return dict(rc=r["rc"], assign=r["assign"].cpu().numpy(), load=r["load"].cpu().numpy(), order=r["order"].cpu().numpy(),
+                status=r["status"].cpu().numpy())
+
+
 def gpu_online_sim(arrival, in_len, out_len, params, trace_scenarios=0, trace_capacity=0):
     import torch
     from paper_2502_15763_amd import api

@@ -21,7 +21,7 @@ def _declared_functions():
 
 def test_header_declares_expected_entry_points():
     names = _declared_functions()
-    for n in ("mmbp_lower_bound", "mmbp_lower_bound_ex", "mmbp_valu_probe", "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
+    for n in ("mmbp_lower_bound", "mmbp_lower_bound_ex", "mmbp_lpt_start", "mmbp_valu_probe", "mmbp_local_search", "mmbp_local_search_pruned", "mmbp_local_search_static", "online_iter_sim",
               "online_iter_sim_assigned", "mmbp_workspace_bytes",
               "mmbp_strerror", "mmbp_version"):
         assert n in names
@@ -84,6 +84,12 @@ def test_host_side_argument_validation():
     assert lbx(one, 0, 1, 4, 2, i32a(-1, 9), 0, None, 0, None, None, 0, one, None, one, None) == api.EINVAL
     assert lbx(one, 0, 1, 4, 2, None, 0, one, 17, i64a(*[5] * 17), i64a(*[5] * 17), 0, one, None, one, None) == api.EUNSUPPORTED
     assert lbx(one, 0, 1, 4, 257, None, 0, None, 0, None, None, 0, one, None, one, None) == api.EUNSUPPORTED
+    lpt = lib.mmbp_lpt_start
+    assert lpt(None, 0, 1, 4, 2, 2, one, one, one, one, None) == api.EINVAL
+    assert lpt(one, 0, 1, 4, 2, 2, one, one, None, one, None) == api.EINVAL                  # order_out is required
+    assert lpt(one, 0, 1, 4, 2, 0, one, one, one, one, None) == api.EINVAL
+    assert lpt(one, 0, 1, 5, 2, 2, one, one, one, one, None) == api.EINFEASIBLE
+    assert lpt(one, 0, 1, api.LPT_MAX_N + 1, 2, 1 << 20, one, one, one, one, None) == api.EUNSUPPORTED
     sim = lib.online_iter_sim
     p = api.SimParams(65, 0, 1, 1, 1, 1, 0)
     args = lambda pp: (one, one, one, 1, 4, C.byref(pp), one, one, one, one, one, one, None, None, 0, 0, one, None)

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 from paper_2502_15763_amd import workloads as W
-from gpu_util import (say, gpu_local_search, compare_ls, gpu_lower_bound, gpu_lower_bound_ex, gpu_online_sim, compare_sim,
+from gpu_util import (say, gpu_local_search, compare_ls, gpu_lower_bound, gpu_lower_bound_ex, gpu_lpt_start, gpu_online_sim, compare_sim,
                       gpu_online_sim_assigned)
 
 pytestmark = pytest.mark.gpu
@@ -545,6 +545,54 @@ def test_lb_ex_hand_worked_and_configs(oracle):
         _same_lb_ex(gpu_lower_bound_ex(c.cost, c.M, cap=caps), o, c.name)
         basic = oracle.lower_bound(c.cost, c.M)
         assert (o["lb"] >= basic["lb"]).all()
+
+
+# ------------------------------------------------------------------ longest-processing-time start
+def _same_lpt(g, o, label):
+    assert g["rc"] == o["rc"], (label, g["rc"], o["rc"])
+    if o["rc"] == 0:
+        for k in ("status", "order", "assign", "load"):
+            assert np.array_equal(g[k], o[k]), f"{label}: {k} differs"
+
+
+def test_lpt_start_parity(oracle):
+    from test_oracle_lpt import _cases
+    for c in _cases():
+        g = gpu_lpt_start(np.array([c["cost"]], np.int64), c["M"], c["cap"])
+        assert g["rc"] == 0 and g["order"][0].tolist() == c["order"] and g["assign"][0].tolist() == c["assign"] \
+            and g["load"][0].tolist() == c["load"], c["name"]
+    rng = np.random.default_rng(71)
+    for (N, M, cap, hi, dtype) in [(1, 1, 1, 10, np.int32), (2, 3, 1, 10, np.int64), (5, 5, 1, 50, np.int32), (64, 4, 16, 40000, np.int32),
+                                   (65, 3, 30, 3, np.int32), (100, 7, 15, 2000, np.int64), (257, 9, 33, 700, np.int32),
+                                   (1319, 200, 7, 60000, np.int32), (4096, 16, 256, 700000, np.int64), (3000, 256, 12, 40000, np.int32),
+                                   (1000, 70, 1000, 0, np.int32), (16384, 64, 256, 1 << 20, np.int32), (9000, 5, 1800, 1 << 30, np.int64),
+                                   (700, 6, 200, 1 << 50, np.int64), (513, 130, 4, 1 << 50, np.int64)]:
+        say(f"lpt N={N} M={M} cap={cap} hi={hi}")
+        S = 3
+        cost = rng.integers(0, hi + 1, size=(S, N)).astype(dtype)
+        if hi >= 1 << 50:
+            # a few costs too large to pack beside an index (the ranking path), some of them equal: the index decides
+            cost[:, 5:13] = (1 << 57) + rng.integers(0, 3, size=(S, 8))
+            cost[:, 100:120] = cost[:, 300:320]
+        _same_lpt(gpu_lpt_start(cost, M, cap), oracle.lpt_start(cost, M, cap), f"N={N} M={M}")
+    cost = np.array([[5, 3, 2, 1], [5, -3, 2, 1], [1 << 61, 1 << 61, 1, 1]], np.int64)
+    _same_lpt(gpu_lpt_start(cost, 2, 2), oracle.lpt_start(cost, 2, 2), "bad cost")
+    assert gpu_lpt_start(cost, 2, 1)["rc"] == -2
+
+
+def test_lpt_start_feeds_the_local_search(oracle):
+    """The start is feasible for mmbp_local_search, and the search from it ends no worse than it started."""
+    for c in (W.config2(S=32), W.config3(S=8)):
+        say(f"lpt -> local search {c.name}")
+        o = oracle.lpt_start(c.cost, c.M, c.cap)
+        g = gpu_lpt_start(c.cost, c.M, c.cap)
+        _same_lpt(g, o, c.name)
+        ol = oracle.local_search(c.cost, o["assign"], c.M, c.cap, 50, want_log=True)
+        gl = gpu_local_search(c.cost, g["assign"], c.M, c.cap, 50)
+        compare_ls(gl, ol, label=f"search from the LPT start, {c.name}")
+        assert (gl["makespan"] <= g["load"].max(axis=1)).all()
+        rr = oracle.local_search(c.cost, c.assign0, c.M, c.cap, 0)
+        assert (g["load"].max(axis=1) <= rr["makespan"]).all()      # on these inputs LPT starts below round-robin
 
 
 # ------------------------------------------------------------------ simulator fed by an offline assignment
