@@ -40,6 +40,13 @@
 // are scanned; the packed minimum (i, k, pos_i, pos_k) is applied.  Moves are value-only in phase A
 // and rescanned for the id when a move wins.
 //
+// Pruned scan (PRUNE): only the candidates that involve the critical client are looked at (the others
+// cannot lower max_j t_j).  The positions of every client are then kept in ascending order of cu
+// (a bitonic network after each regrouping; a swap removes one entry and inserts the other in place),
+// and a row's best partner in the critical client is found by binary search: the nearest column at or
+// above x and the nearest below it, i.e. the same key min |y - x| the tile computes, in O(log n)
+// per row instead of one subtraction per column.  Selection, tie-break and apply are shared.
+//
 // Exactness: all loads stay at or below the initial makespan T0; with T0 + 2*max T_i < 2^29 every
 // quantity above is exact in 32 bits: x lies in (2^29, 3*2^29), a real |y - x| is below 2^29, a
 // wrapped difference is above 7*2^29, and an empty column (cu = 6*2^29) gives d in (3*2^29, 5*2^29),
@@ -205,9 +212,52 @@ __device__ __forceinline__ void run_tile(const Lds &l, int rowbase, int c0, int 
     }
 }
 
+// Sorts the positions of every client by cu, ascending (all threads; barriers inside).  A bitonic
+// network whose comparators all put the smaller entry at the lower position, so positions beyond P
+// act as +infinity without being stored; entries of different clients never change order (clients
+// occupy ascending position ranges), empty positions (kPad) end up last in their client's range.
+template <int BLOCK>
+__device__ void sort_groups(const Lds &l, int P)
+{
+    const int tid = threadIdx.x;
+    int P2 = 1;
+    while (P2 < P) P2 <<= 1;
+    for (int k = 2; k <= P2; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = tid; t < (P2 >> 1); t += BLOCK) {
+                const int blk = t / j, off = t - blk * j;
+                int i, q;
+                if (j == (k >> 1)) { i = blk * k + off; q = blk * k + (k - 1 - off); }
+                else { i = blk * 2 * j + off; q = i + j; }
+                if (q < P && l.seg_grp[i >> 6] == l.seg_grp[q >> 6]) {
+                    const uint32_t a = l.cu[i], b = l.cu[q];
+                    if (a > b) {
+                        l.cu[i] = b; l.cu[q] = a;
+                        const uint16_t ja = l.job[i];
+                        l.job[i] = l.job[q]; l.job[q] = ja;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+}
+
+// min over the n sorted entries cu[sb .. sb+n) of |cu - x|: the nearest at or above x, the nearest below
+__device__ __forceinline__ uint32_t nearest_sorted(const uint32_t *cu, int sb, int n, uint32_t x)
+{
+    int lo = 0, hi = n;                                  // first entry >= x
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[sb + mid] < x) lo = mid + 1; else hi = mid;
+    }
+    const uint32_t up = lo < n ? cu[sb + lo] - x : kInf;
+    const uint32_t dn = lo > 0 ? x - cu[sb + lo - 1] : kInf;
+    return min(up, dn);
+}
+
 // Groups the jobs by client and builds the chunk and task tables (all threads; barriers inside).
 template <typename CostT, int BLOCK>
-__device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const int32_t *asg, int N, int M, int cap)
+__device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const int32_t *asg, int N, int M, int cap, bool sorted)
 {
     const int tid = threadIdx.x;
     const LdsDims d = lds_dims(N, M);
@@ -270,11 +320,12 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
         for (int q = 0; q < n; q++) l.tasks[base + q] = (unsigned long long)w0 | ((unsigned long long)l.chunks[k0 + q] << 32);
     }
     __syncthreads();
+    if (sorted) sort_groups<BLOCK>(l, min(l.ctrl->P, (int)d.P) & ~63);
 }
 
-template <typename CostT, int BLOCK, bool SMALLM>
+template <typename CostT, int BLOCK, bool SMALLM, bool PRUNE>
 __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
-    const CostT *__restrict__ cost_all, int N, int M, int cap, int max_passes, int prune, int32_t *assign_all,
+    const CostT *__restrict__ cost_all, int N, int M, int cap, int max_passes, int32_t *assign_all,
     int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
     uint64_t *applied_log, int32_t *status_out)
 {
@@ -344,7 +395,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             return;
         }
     }
-    build_layout<CostT, BLOCK>(l, c, asg, N, M, cap);
+    build_layout<CostT, BLOCK>(l, c, asg, N, M, cap, PRUNE);
 
     // loads stay below 2^29 on this path: their low words are used
     auto load32 = [&](int g) -> uint32_t { return (uint32_t)l.load[g]; };
@@ -397,7 +448,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         __syncthreads();                                 // B0: layout, loads, top-3 and flags are published
         if (ctrl->stop) break;
         if (ctrl->rebuild) {                             // a move was applied: regroup the jobs
-            build_layout<CostT, BLOCK>(l, c, asg, N, M, cap);
+            build_layout<CostT, BLOCK>(l, c, asg, N, M, cap, PRUNE);
             if (tid == 0) ctrl->rebuild = 0;             // (after the last barrier of build_layout: nobody
                                                          //  reads the flag before the next B0)
             const unsigned long long np = ctrl->pairs_per_scan;
@@ -450,7 +501,26 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         const int sega = min(max(uni(l.gstart[astar]), 0), P) >> 6, segb = min(max(uni(l.gstart[astar + 1]), 0), P) >> 6;
         if (nfeas > 0)
             for (int seg = sega + wave; seg < segb; seg += kWaves) mbest = min(mbest, segment_moves(seg, astar));
-        {
+        if constexpr (PRUNE) {
+            // every position outside the critical client against its sorted columns
+            const int sb = min(max(uni(l.gstart[astar]), 0), P), sn = min(max(uni(l.cnt[astar]), 0), P - sb);
+            const int s1 = min(max(uni(l.gstart[astar + 1]), 0), P);
+            const uint32_t lstar = wload(astar);
+            if (sn > 0)
+                for (int p = tid; p < P; p += BLOCK) {
+                    if (p >= sb && p < s1) continue;
+                    const uint32_t cx = l.cu[p];
+                    if (cx == kPad) continue;
+                    const int g = min((int)l.seg_grp[p >> 6], M - 1);
+                    const uint32_t lg = load32(g);
+                    const uint32_t v = swap_value(nearest_sorted(l.cu, sb, sn, cx - (lg - lstar)), lg + lstar, others_max(top, g, astar));
+                    sbest = min(sbest, v);
+                    if (v != kInf) {
+                        l.rowkey[p] = v;                 // one thread per row: nothing to combine
+                        kbest = min(kbest, ((unsigned long long)v << 32) | ((unsigned long long)l.job[p] << 16) | (unsigned long long)p);
+                    }
+                }
+        } else {
             const int nU = min(max(uni(l.upre[M]), 0), Umax);
             const int ua0 = min(max(uni(l.upre[astar]), 0), nU), nua = min(max(uni(l.upre[astar + 1]), 0), nU) - ua0;
             const int nCh = min(max(ctrl->nchunk, 0), Cmax);
@@ -682,7 +752,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
 
         // ---- phase C: the rest of the scan, dealt from a counter: the swap tiles of the task table
         //      that do not involve the critical client, then the move segments of the other clients ----
-        if (!prune) {
+        if constexpr (!PRUNE) {
             uint32_t rbest = kInf;
             unsigned long long knone = ~0ull;
             const int nwork = ntask + (nfeas > 0 ? nseg : 0);
@@ -718,7 +788,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
 
         // ---- wave 0: apply (its operands were read before the barrier), open the next pass ----
         uint32_t vnew = vload;
-        if (!prune && uniu(ctrl->vrest) < T) act = kActError;       // cannot happen: those candidates keep the critical load
+        if (!PRUNE && uniu(ctrl->vrest) < T) act = kActError;       // cannot happen: those candidates keep the critical load
         if (act == kActStop) {
             if (lane == 0) ctrl->stop = 1;
             continue;
@@ -748,10 +818,49 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 vnew = vload - (lane == ga ? d : 0u) + (lane == gb ? d : 0u);
                 if (lane == ga || lane == gb) l.load[lane] = (long long)vnew;
             }
+            if constexpr (PRUNE) {
+                // the clients' positions stay sorted: the entry at pr leaves, (xnew, jnew) enters where it belongs
+                auto replace_sorted = [&](int g, int pr, uint32_t xnew, uint32_t jnew) {
+                    const int gb0 = min(max(uni(l.gstart[g]), 0), P), n = min(max(uni(l.cnt[g]), 0), P - gb0);
+                    if (pr < gb0 || pr >= gb0 + n) return;              // cannot happen: the entry is one of the client's
+                    int less = 0;
+                    for (int p0 = gb0; p0 < gb0 + n; p0 += kWave) {
+                        const int p = p0 + lane;
+                        less += __popcll(__ballot(p < gb0 + n && p != pr && l.cu[p] < xnew));
+                    }
+                    const int t = gb0 + less;                          // where the new entry goes
+                    if (t > pr) {
+                        for (int p0 = pr; p0 < t; p0 += kWave) {       // entries (pr, t] move down by one
+                            const int p = p0 + lane;
+                            const bool in = p < t;
+                            const uint32_t v = in ? l.cu[p + 1] : 0u;
+                            const uint16_t jv = in ? l.job[p + 1] : (uint16_t)0;
+                            __builtin_amdgcn_wave_barrier();
+                            if (in) { l.cu[p] = v; l.job[p] = jv; }
+                            __builtin_amdgcn_wave_barrier();
+                        }
+                    } else if (t < pr) {
+                        for (int p1 = pr; p1 > t; p1 -= kWave) {       // entries [t, pr) move up by one
+                            const int p = p1 - lane;
+                            const bool in = p > t;
+                            const uint32_t v = in ? l.cu[p - 1] : 0u;
+                            const uint16_t jv = in ? l.job[p - 1] : (uint16_t)0;
+                            __builtin_amdgcn_wave_barrier();
+                            if (in) { l.cu[p] = v; l.job[p] = jv; }
+                            __builtin_amdgcn_wave_barrier();
+                        }
+                    }
+                    if (lane == 0) { l.cu[t] = xnew; l.job[t] = (uint16_t)jnew; }
+                };
+                replace_sorted(ga, pi, xk, jk);
+                replace_sorted(gb, pk, xi, ji);
+            }
             if (lane == 0) {
                 if (!SMALLM) { l.load[ga] -= (long long)(int32_t)d; l.load[gb] += (long long)(int32_t)d; }
-                l.cu[pi] = xk; l.cu[pk] = xi;
-                l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
+                if constexpr (!PRUNE) {
+                    l.cu[pi] = xk; l.cu[pk] = xi;
+                    l.job[pi] = (uint16_t)jk; l.job[pk] = (uint16_t)ji;
+                }
                 asg[ji] = gb; asg[jk] = ga;
                 if (applied_log)
                     applied_log[(size_t)s * max_passes + w_passes] =
@@ -776,8 +885,8 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     }
 }
 
-template <typename CostT, int BLOCK, bool SMALLM>
-hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_passes, int prune, int32_t *assign,
+template <typename CostT, int BLOCK, bool SMALLM, bool PRUNE>
+hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_passes, int32_t *assign,
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
@@ -787,12 +896,12 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
 #endif
     if (bytes > 64 * 1024) {                             // beyond the default limit: raise it for this kernel (per device,
                                                          // cheap, so done at every such launch)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ls_lds_kernel<CostT, BLOCK, SMALLM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ls_lds_kernel<CostT, BLOCK, SMALLM, PRUNE>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
         if (e != hipSuccess) return e;
     }
-    ls_lds_kernel<CostT, BLOCK, SMALLM><<<dim3(S), dim3(BLOCK), bytes, st>>>(
-        (const CostT *)cost, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out, evals_out,
+    ls_lds_kernel<CostT, BLOCK, SMALLM, PRUNE><<<dim3(S), dim3(BLOCK), bytes, st>>>(
+        (const CostT *)cost, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out,
         applied_log, status_out);
     return hipGetLastError();
 }
@@ -814,8 +923,10 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
     const int block = pmax <= 512 ? 256 : 512;
 #endif
 #define MMBP_LDS_LAUNCH(T, B, SM) \
-    launch_one<T, B, SM>(cost, S, N, M, cap, max_passes, prune, assign, load_out, makespan_out, passes_out, evals_out, \
-                         applied_log, status_out, st)
+    (prune ? launch_one<T, B, SM, true>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
+                                        applied_log, status_out, st) \
+           : launch_one<T, B, SM, false>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
+                                         applied_log, status_out, st))
 #define MMBP_LDS_PICK(T) \
     (block == 256 ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 256, true) : MMBP_LDS_LAUNCH(T, 256, false)) \
      : block == 512 ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 512, true) : MMBP_LDS_LAUNCH(T, 512, false)) \

@@ -353,6 +353,20 @@ def test_ls_pruned_configs(oracle):
     compare_ls(gpu_local_search(cost, assign, 5, 50, 300, pruned=True), o, label="pruned 64-bit mix")
 
 
+def test_ls_pruned_sorted_search_with_ties_and_uneven_clients(oracle):
+    """The pruned scan keeps every client's positions sorted and finds partners by binary search:
+    uneven client sizes (random start, ranges of several 64-position segments), costs from a small range
+    (many equal keys, so equal neighbours above and below), swaps and moves mixed."""
+    rng = np.random.default_rng(2026)
+    for (S, N, M, cap, hi, passes) in [(4, 2000, 5, 600, 50, 300), (4, 700, 3, 400, 7, 200), (3, 3000, 11, 280, 100000, 150),
+                                       (6, 130, 2, 129, 2, 100)]:
+        say(f"ls_pruned sorted search N={N} M={M} cap={cap} hi={hi}")
+        cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=hi, dtype=np.int32)
+        o = oracle.local_search(cost, assign, M, cap, passes, want_log=True)
+        compare_ls(gpu_local_search(cost, assign, M, cap, passes, pruned=True, use_workspace=False), o,
+                   label=f"pruned sorted N={N} M={M}")
+
+
 # ------------------------------------------------------------------ lower bound
 def test_lb_parity(oracle):
     rng = np.random.default_rng(31)
