@@ -30,7 +30,7 @@ extern "C" {
 #define MMBP_OK            0
 #define MMBP_EINVAL       -1  /* null pointer, non-positive size, bad dtype, negative max_passes, unknown policy */
 #define MMBP_EINFEASIBLE  -2  /* N > M * cap: no assignment satisfies the cardinality limit */
-#define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 64,
+#define MMBP_EUNSUPPORTED -3  /* outside the supported range (N <= 2^20, M <= 256, sim cap <= 256,
                                  assigned simulator N <= 8192, max_passes <= MMBP_GRID_MAX_PASSES for a
                                  scenario that does not fit one workgroup's LDS) */
 #define MMBP_EWORKSPACE   -4  /* workspace missing, smaller than mmbp_workspace_bytes(), or not 256-byte aligned */
@@ -52,7 +52,7 @@ extern "C" {
 #define MMBP_MAX_N (1 << 20)
 #define MMBP_MAX_M 256
 #define MMBP_GRID_MAX_PASSES 4096   /* candidates one call can apply on the multi-workgroup path */
-#define MMBP_SIM_MAX_CAP 64
+#define MMBP_SIM_MAX_CAP 256
 #define MMBP_SIM_ASSIGNED_MAX_N 8192
 
 int mmbp_version(void);
@@ -237,7 +237,7 @@ int mmbp_local_search_static(const void *cost, int dtype, int S, int N, int M, i
  * a prefill iteration over P tokens takes a_prefill*P + c_prefill, a decode iteration over D
  * running requests takes b_decode*D + c_decode. */
 typedef struct mmbp_sim_params {
-    int32_t cap;                /* batch size |J|: requests processed simultaneously, 1..64 */
+    int32_t cap;                /* batch size |J|: requests processed simultaneously, 1..256 */
     int32_t policy;             /* MMBP_POLICY_* */
     int64_t a_prefill;          /* T^p per token */
     int64_t b_decode;           /* T^d per token (one token per running request per round) */

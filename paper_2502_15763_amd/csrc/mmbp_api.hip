@@ -58,7 +58,7 @@ const char *mmbp_strerror(int code)
     case MMBP_OK: return "ok";
     case MMBP_EINVAL: return "invalid argument (null pointer, non-positive size, bad dtype, negative max_passes or unknown policy)";
     case MMBP_EINFEASIBLE: return "infeasible: N > M * cap";
-    case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 64, assigned simulator N <= 8192, "
+    case MMBP_EUNSUPPORTED: return "unsupported size (N <= 2^20, M <= 256, simulator cap <= 256, assigned simulator N <= 8192, "
                                    "max_passes <= 4096 per call for scenarios that need the multi-workgroup path)";
     case MMBP_EWORKSPACE: return "workspace missing, too small or not 256-byte aligned (see mmbp_workspace_bytes), or the "
                                  "shape needs more scratch than mmbp_local_search_static holds (MMBP_STATIC_SCRATCH_BYTES)";

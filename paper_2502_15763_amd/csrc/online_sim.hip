@@ -1,10 +1,11 @@
-// Iteration-level online simulator: one wavefront per scenario, lane = client slot.
+// Iteration-level online simulator: one wavefront per scenario, lane = client slot (up to four slots
+// per lane when the batch size exceeds the wave).
 // Decision rule of the paper's section "Online requests and iteration scheduling": with
 // C_p = a_prefill * P + c_prefill the cost of the prefill that could be dispatched now and C_d the
 // decode time accumulated since the last prefill, C_p >= C_d continues decoding, otherwise the
 // prefill runs.  Iteration times follow the affine model of section "Experiment settings and
 // baseline".  Every scalar of the state (time, C_d, counters, queue head) is wave-uniform; the
-// per-request remaining tokens live one per lane.
+// per-request remaining tokens live in the lanes' registers.
 #include "mmbp_dev.hpp"
 
 #include "sim_trace.hpp"
@@ -14,12 +15,18 @@ namespace {
 
 constexpr int kBlock = 256;
 
-__global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
+// Q = client slots per lane: the batch size |J| may exceed one wave (the paper's node runs about 200
+// clients), so slot c lives in lane c % 64, register c / 64.
+template <int Q>
+__global__ __launch_bounds__(kBlock, Q == 1 ? 8 : 4) void online_sim_kernel(
     const int64_t *__restrict__ arrival_all, const int32_t *__restrict__ in_all, const int32_t *__restrict__ out_all,
     int S, int N, mmbp_sim_params p, int64_t *finish_all, int64_t *total_us, int64_t *busy_slot_us,
     int32_t *n_prefill_iter, int32_t *n_decode_iter, uint64_t *trace_hash, mmbp_trace_rec *trace_buf,
     int32_t *trace_len, int trace_scenarios, int trace_capacity, int32_t *status_out)
 {
+    constexpr int kWin = kWave * Q;            // requests per window chunk: one admission takes at most this many
+    constexpr int kWinShift = Q == 1 ? 6 : Q == 2 ? 7 : 8;
+    static_assert(Q == 1 || Q == 2 || Q == 4, "the window index is a mask");
     const int lane = threadIdx.x & 63;
     const int s = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6)));
     if (s >= S) return;
@@ -56,19 +63,21 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
     tr.cap = traced ? trace_capacity : 0;
     tr.len = 0; tr.run_open = 0; tr.run_count = 0; tr.run_t = 0; tr.run_D = 0;
 
-    // The queue is consumed in order: a window of two 64-request chunks per wave is kept in LDS
-    // (the chunk that holds the queue head and the one after it), so the dependent reads of every
-    // admission are LDS reads; a chunk is fetched from memory once, when the head enters the chunk
-    // before it.
-    __shared__ int64_t win_arr[kBlock / kWave][2 * kWave];
-    __shared__ int32_t win_in[kBlock / kWave][2 * kWave], win_out[kBlock / kWave][2 * kWave];
+    // The queue is consumed in order: a window of two chunks per wave is kept in LDS (the chunk that
+    // holds the queue head and the one after it), so the dependent reads of every admission are LDS
+    // reads; a chunk is fetched from memory once, when the head enters the chunk before it.
+    __shared__ int64_t win_arr[kBlock / kWave][2 * kWin];
+    __shared__ int32_t win_in[kBlock / kWave][2 * kWin], win_out[kBlock / kWave][2 * kWin];
     const int w = threadIdx.x >> 6;
     auto load_chunk = [&](int chunk) {
-        const int i = chunk * kWave + lane, slot = i & (2 * kWave - 1);
-        const bool in = i < N;
-        win_arr[w][slot] = in ? arrival[i] : INT64_MAX;
-        win_in[w][slot] = in ? in_len[i] : 0;
-        win_out[w][slot] = in ? out_len[i] : 0;
+#pragma unroll
+        for (int q = 0; q < Q; q++) {
+            const int i = chunk * kWin + q * kWave + lane, slot = i & (2 * kWin - 1);
+            const bool in = i < N;
+            win_arr[w][slot] = in ? arrival[i] : INT64_MAX;
+            win_in[w][slot] = in ? in_len[i] : 0;
+            win_out[w][slot] = in ? out_len[i] : 0;
+        }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     };
@@ -76,7 +85,9 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
     load_chunk(1);
     int loaded = 1;                            // highest chunk in the window
 
-    int32_t rem = 0, rid = 0;                  // this lane's slot: remaining output tokens, request id
+    int32_t rem[Q], rid[Q];                    // this lane's slots: remaining output tokens, request id
+#pragma unroll
+    for (int q = 0; q < Q; q++) { rem[q] = 0; rid[q] = 0; }
     int64_t t = 0, Cd = 0, busy = 0;
     int next = 0, done = 0, nR = 0, npre = 0, ndec = 0;
     int64_t head_arr = uniform_i64(win_arr[w][0]);
@@ -88,23 +99,38 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
         if (free_slots > 0 && head_arr <= t) {
             // admissible set A: FCFS prefix of the arrived requests that fits the free slots and the
             // token capacity (an oversized head request is still admitted alone)
-            const int idx = next + lane;
-            const bool cand = lane < free_slots && idx < N;
-            const int slot = idx & (2 * kWave - 1);
-            const int64_t arr = cand ? win_arr[w][slot] : INT64_MAX;
-            const bool arrived = cand && arr <= t;
-            const int64_t tok = arrived ? (int64_t)win_in[w][slot] : 0;
-            nA = __popcll(__ballot(arrived));
+            int64_t tok[Q];
+            bool arrived[Q];
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                const int c = q * kWave + lane, idx = next + c;
+                const bool cand = c < free_slots && idx < N;
+                const int slot = idx & (2 * kWin - 1);
+                const int64_t arr = cand ? win_arr[w][slot] : INT64_MAX;
+                arrived[q] = cand && arr <= t;
+                tok[q] = arrived[q] ? (int64_t)win_in[w][slot] : 0;
+                nA += __popcll(__ballot(arrived[q]));
+            }
             if (maxtok > 0) {
-                const int64_t pre = wave_incl_scan_i64(tok, lane);
-                int n2 = __popcll(__ballot(arrived && pre <= maxtok));
+                int n2 = 0;
+                int64_t carry = 0;
+#pragma unroll
+                for (int q = 0; q < Q; q++) {
+                    const int64_t pre = carry + wave_incl_scan_i64(tok[q], lane);
+                    n2 += __popcll(__ballot(arrived[q] && pre <= maxtok));
+                    if (Q > 1) carry = uniform_i64(__shfl((long long)pre, kWave - 1));
+                }
                 nA = n2 == 0 ? 1 : n2;
             }
-            P = nA == 1 ? uniform_i64(tok) : wave_sum_i64(lane < nA ? tok : 0);
+            if (Q == 1) P = nA == 1 ? uniform_i64(tok[0]) : wave_sum_i64(lane < nA ? tok[0] : 0);
+            else {
+#pragma unroll
+                for (int q = 0; q < Q; q++) P += wave_sum_i64(q * kWave + lane < nA ? tok[q] : 0);
+            }
         }
         if (p.policy == MMBP_POLICY_PREFILL_FIRST_SINGLE && nA > 1) {      // baseline without batched prefill
             nA = 1;
-            P = uniform_i64((int64_t)win_in[w][next & (2 * kWave - 1)]);
+            P = uniform_i64((int64_t)win_in[w][next & (2 * kWin - 1)]);
         }
         if (nA == 0 && nR == 0) {              // nothing running, nothing arrived: jump to the next arrival
             tr.other(2u, 1u, t, 0, lane);
@@ -120,15 +146,20 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
             const int64_t dt = p.a_prefill * P + p.c_prefill;
             tr.other(1u, (uint32_t)nA, t, P, lane);
             t += dt;
-            const bool is_free = lane < cap && rem == 0;
-            const uint64_t fm = __ballot(is_free);
-            const int rank = __popcll(fm & ((1ull << lane) - 1ull));
-            if (is_free && rank < nA) {
-                rid = next + rank;
-                rem = win_out[w][rid & (2 * kWave - 1)];
+            int base = 0;                      // free slots before this register's block
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                const bool is_free = q * kWave + lane < cap && rem[q] == 0;
+                const uint64_t fm = __ballot(is_free);
+                const int rank = base + __popcll(fm & ((1ull << lane) - 1ull));
+                if (is_free && rank < nA) {
+                    rid[q] = next + rank;
+                    rem[q] = win_out[w][rid[q] & (2 * kWin - 1)];
+                }
+                base += __popcll(fm);
             }
             next += nA;
-            while ((next >> 6) + 1 > loaded) {     // (at most two rounds: nA <= 64)
+            while ((next >> kWinShift) + 1 > loaded) {     // (at most two rounds: nA <= kWin)
                 loaded += 1;
                 load_chunk(loaded);
             }
@@ -136,7 +167,7 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
             busy += (int64_t)nA * dt;
             Cd = 0;
             npre++;
-            head_arr = next < N ? uniform_i64(win_arr[w][next & (2 * kWave - 1)]) : INT64_MAX;
+            head_arr = next < N ? uniform_i64(win_arr[w][next & (2 * kWin - 1)]) : INT64_MAX;
         } else {
             const int64_t D = nR;
             const int64_t bD = p.b_decode * D;              // decode time of the D tokens of one iteration
@@ -146,7 +177,10 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
             // applied at once.  Otherwise (a prefill is waiting for C_d to pass C_p) one at a time.
             int64_t k = 1;
             if (nA == 0) {
-                k = (int64_t)wave_min_u32(rem > 0 ? (uint32_t)rem : 0xFFFFFFFFu);
+                uint32_t m = 0xFFFFFFFFu;
+#pragma unroll
+                for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
+                k = (int64_t)wave_min_u32(m);
                 if (free_slots > 0 && head_arr != INT64_MAX && dt > 0) {
                     const int64_t j = (head_arr - t + dt - 1) / dt;      // first boundary at or after the arrival
                     k = min(k, max(j, (int64_t)1));
@@ -155,11 +189,15 @@ __global__ __launch_bounds__(kBlock, 8) void online_sim_kernel(
             tr.decode(t, D, (uint32_t)k, lane);
             const int64_t kdt = k * dt;
             t += kdt;
-            const bool active = rem > 0;
-            if (active) rem -= (int32_t)k;
-            const bool fin = active && rem == 0;
-            if (fin) finish[rid] = t;
-            const int nf = __popcll(__ballot(fin));
+            int nf = 0;
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                const bool active = rem[q] > 0;
+                if (active) rem[q] -= (int32_t)k;
+                const bool fin = active && rem[q] == 0;
+                if (fin) finish[rid[q]] = t;
+                nf += __popcll(__ballot(fin));
+            }
             done += nf;
             nR -= nf;
             busy += D * kdt;
@@ -186,9 +224,14 @@ hipError_t launch_online_sim(const int64_t *arrival_us, const int32_t *in_len, c
 {
     const int per_block = kBlock / kWave;
     dim3 g((S + per_block - 1) / per_block), b(kBlock);
-    online_sim_kernel<<<g, b, 0, st>>>(arrival_us, in_len, out_len, S, N, p, finish_us, total_us, busy_slot_us,
-                                       n_prefill_iter, n_decode_iter, trace_hash, trace_buf, trace_len,
-                                       trace_scenarios, trace_capacity, status_out);
+#define MMBP_SIM_LAUNCH(QQ) \
+    online_sim_kernel<QQ><<<g, b, 0, st>>>(arrival_us, in_len, out_len, S, N, p, finish_us, total_us, busy_slot_us, \
+                                           n_prefill_iter, n_decode_iter, trace_hash, trace_buf, trace_len, \
+                                           trace_scenarios, trace_capacity, status_out)
+    if (p.cap <= kWave) MMBP_SIM_LAUNCH(1);
+    else if (p.cap <= 2 * kWave) MMBP_SIM_LAUNCH(2);
+    else MMBP_SIM_LAUNCH(4);
+#undef MMBP_SIM_LAUNCH
     return hipGetLastError();
 }
 

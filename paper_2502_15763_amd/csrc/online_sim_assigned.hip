@@ -1,4 +1,5 @@
-// Iteration-level simulator fed by an offline assignment: one wavefront per scenario, lane = client.
+// Iteration-level simulator fed by an offline assignment: one wavefront per scenario, lane = client
+// (up to four clients per lane when there are more clients than lanes).
 //
 // Request scheduling follows the sorting and online preemptive method of the paper's section
 // "Online requests and iteration scheduling": I_j = the requests assigned to client j, sorted by
@@ -27,6 +28,19 @@ __device__ __forceinline__ int64_t readlane_i64(int64_t x, int l)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// value of register block sq (uniform) of a per-lane array
+template <int Q, typename T>
+__device__ __forceinline__ T sel(const T (&a)[Q], int sq)
+{
+    T v = a[0];
+#pragma unroll
+    for (int q = 1; q < Q; q++) v = sq == q ? a[q] : v;
+    return v;
+}
+
+// Q = clients per lane: client j lives in lane j % 64, register j / 64 (the paper's node runs about
+// 200 clients, more than one wave has lanes).
+template <int Q>
 __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     const int32_t *__restrict__ in_all, const int32_t *__restrict__ out_all, const int32_t *__restrict__ assign_all,
     int S, int N, mmbp_sim_params p, int64_t *finish_all, int64_t *total_us, int64_t *busy_slot_us,
@@ -36,7 +50,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     extern __shared__ __align__(16) unsigned char lds_raw[];
     uint32_t *qlen = reinterpret_cast<uint32_t *>(lds_raw);                 // [N] length of the request at a queue position
     uint16_t *order = reinterpret_cast<uint16_t *>(lds_raw + 4 * (size_t)N); // [N] request index at a queue position
-    __shared__ int cursor[kWave];
+    __shared__ int cursor[kWave * Q];
 
     const int lane = threadIdx.x;
     const int s = blockIdx.x;
@@ -71,21 +85,32 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     }
 
     // ---- the sorted queues ----
-    cursor[lane] = 0;
+#pragma unroll
+    for (int q = 0; q < Q; q++) cursor[q * kWave + lane] = 0;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     for (int i = lane; i < N; i += kWave) atomicAdd(&cursor[assign[i]], 1);
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    const int cnt = cursor[lane];
-    int incl = cnt;
-    for (int off = 1; off < kWave; off <<= 1) {
-        const int y = __shfl_up(incl, off);
-        if (lane >= off) incl += y;
+    int qbeg[Q], qend[Q];
+    {
+        int carry = 0;                         // requests of the clients in earlier register blocks
+#pragma unroll
+        for (int q = 0; q < Q; q++) {
+            const int cnt = cursor[q * kWave + lane];
+            int incl = cnt;
+            for (int off = 1; off < kWave; off <<= 1) {
+                const int y = __shfl_up(incl, off);
+                if (lane >= off) incl += y;
+            }
+            qbeg[q] = carry + incl - cnt;
+            qend[q] = carry + incl;
+            carry += __builtin_amdgcn_readlane(incl, kWave - 1);
+        }
     }
-    const int qbeg = incl - cnt, qend = incl;
     __builtin_amdgcn_wave_barrier();
-    cursor[lane] = qbeg;
+#pragma unroll
+    for (int q = 0; q < Q; q++) cursor[q * kWave + lane] = qbeg[q];
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     for (int i = lane; i < N; i += kWave) {
@@ -95,20 +120,24 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    int64_t remain = 0;
-    for (int a = qbeg; a < qend; a++) {                  // insertion sort of this lane's queue: longest first, then index
-        const uint32_t kl = qlen[a];
-        const uint16_t ki = order[a];
-        remain += (int64_t)kl;
-        int b = a;
-        while (b > qbeg) {
-            const uint32_t pl = qlen[b - 1];
-            const uint16_t pi = order[b - 1];
-            if (pl > kl || (pl == kl && pi < ki)) break;
-            qlen[b] = pl; order[b] = pi;
-            b--;
+    int64_t remain[Q];
+#pragma unroll
+    for (int q = 0; q < Q; q++) {
+        remain[q] = 0;
+        for (int a = qbeg[q]; a < qend[q]; a++) {        // insertion sort of this client's queue: longest first, then index
+            const uint32_t kl = qlen[a];
+            const uint16_t ki = order[a];
+            remain[q] += (int64_t)kl;
+            int b = a;
+            while (b > qbeg[q]) {
+                const uint32_t pl = qlen[b - 1];
+                const uint16_t pi = order[b - 1];
+                if (pl > kl || (pl == kl && pi < ki)) break;
+                qlen[b] = pl; order[b] = pi;
+                b--;
+            }
+            qlen[b] = kl; order[b] = ki;
         }
-        qlen[b] = kl; order[b] = ki;
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -122,62 +151,114 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     tr.len = 0; tr.run_open = 0; tr.run_count = 0; tr.run_t = 0; tr.run_D = 0;
 
     const int64_t maxtok = p.max_prefill_tokens;
-    int head = qbeg;
-    int32_t rem = 0, rid = 0;                  // this client's running request: remaining output tokens, index
+    int head[Q];
+    int32_t rem[Q], rid[Q];                    // each client's running request: remaining output tokens, index
+#pragma unroll
+    for (int q = 0; q < Q; q++) { head[q] = qbeg[q]; rem[q] = 0; rid[q] = 0; }
     int64_t t = 0, Cd = 0, busy = 0;
     int done = 0, nR = 0, npre = 0, ndec = 0;
     int status = MMBP_ST_OK;
 
     while (done < N) {                         // every trip starts a request or retires output tokens
         // ---- what the idle clients would take now (nothing is taken yet) ----
-        const bool idle = lane < cap && rem == 0;
-        const unsigned long long idle_mask = __ballot(idle);
-        int pick_pos = -1, pick_src = -1;
-        if (idle_mask) {
-            const unsigned long long steal_mask = __ballot(idle && head >= qend);
-            if (steal_mask == 0) {
-                if (idle) { pick_pos = head; pick_src = lane; }          // every idle client has work of its own
+        bool idle[Q];
+        unsigned long long idle_mask[Q];
+        bool any_idle = false, any_steal = false;
+#pragma unroll
+        for (int q = 0; q < Q; q++) {
+            idle[q] = q * kWave + lane < cap && rem[q] == 0;
+            idle_mask[q] = __ballot(idle[q]);
+            any_idle = any_idle || idle_mask[q] != 0;
+            any_steal = any_steal || __ballot(idle[q] && head[q] >= qend[q]) != 0;
+        }
+        int pick_pos[Q], pick_src[Q];
+#pragma unroll
+        for (int q = 0; q < Q; q++) { pick_pos[q] = -1; pick_src[q] = -1; }
+        if (any_idle) {
+            if (!any_steal) {
+#pragma unroll
+                for (int q = 0; q < Q; q++)
+                    if (idle[q]) { pick_pos[q] = head[q]; pick_src[q] = q * kWave + lane; }   // every idle client has work of its own
             } else {
-                int th = head;                                           // tentative heads and remain_token
-                int64_t trm = remain;
-                unsigned long long m = idle_mask;
-                while (m) {
-                    const int j = __builtin_ctzll(m);
-                    m &= m - 1;
-                    int src = -1;
-                    if (__builtin_amdgcn_readlane(th, j) < __builtin_amdgcn_readlane(qend, j)) src = j;
-                    else {
-                        const uint32_t hi = wave_max_u32((uint32_t)((uint64_t)trm >> 32));
-                        const uint32_t lo = wave_max_u32((uint32_t)((uint64_t)trm >> 32) == hi ? (uint32_t)trm : 0u);
-                        const int64_t mx = (int64_t)(((uint64_t)hi << 32) | lo);
-                        if (mx > 0) src = __builtin_ctzll(__ballot(trm == mx));
+                int th[Q];                                               // tentative heads and remain_token
+                int64_t trm[Q];
+#pragma unroll
+                for (int q = 0; q < Q; q++) { th[q] = head[q]; trm[q] = remain[q]; }
+#pragma unroll
+                for (int jq = 0; jq < Q; jq++) {                         // the idle clients in index order
+                    unsigned long long m = idle_mask[jq];
+                    while (m) {
+                        const int jl = __builtin_ctzll(m);
+                        m &= m - 1;
+                        int src = -1;
+                        if (__builtin_amdgcn_readlane(th[jq], jl) < __builtin_amdgcn_readlane(qend[jq], jl)) src = jq * kWave + jl;
+                        else {
+                            int64_t bm = trm[0];                          // the largest remain_token, lowest client among equals
+#pragma unroll
+                            for (int q = 1; q < Q; q++) bm = max(bm, trm[q]);
+                            const uint32_t hi = wave_max_u32((uint32_t)((uint64_t)bm >> 32));
+                            const uint32_t lo = wave_max_u32((uint32_t)((uint64_t)bm >> 32) == hi ? (uint32_t)bm : 0u);
+                            const int64_t mx = (int64_t)(((uint64_t)hi << 32) | lo);
+                            if (mx > 0) {
+                                uint32_t c = 0xFFFFFFFFu;
+#pragma unroll
+                                for (int q = Q - 1; q >= 0; q--) c = trm[q] == mx ? (uint32_t)(q * kWave + lane) : c;
+                                src = (int)wave_min_u32(c);
+                            }
+                        }
+                        if (src < 0) continue;
+                        const int sq = src >> 6, sl = src & 63;
+                        const int pos = min(max(__builtin_amdgcn_readlane(sel<Q>(th, sq), sl), 0), N - 1);
+                        const int64_t len = (int64_t)qlen[pos];
+                        if (lane == jl) { pick_pos[jq] = pos; pick_src[jq] = src; }
+                        if (lane == sl) {
+#pragma unroll
+                            for (int q = 0; q < Q; q++)
+                                if (q == sq) { th[q] += 1; trm[q] -= len; }
+                        }
                     }
-                    if (src < 0) continue;
-                    const int pos = min(max(__builtin_amdgcn_readlane(th, src), 0), N - 1);
-                    const int64_t len = (int64_t)qlen[pos];
-                    if (lane == j) { pick_pos = pos; pick_src = src; }
-                    if (lane == src) { th += 1; trm -= len; }
                 }
             }
         }
         // picks in client order, cut like the FCFS prefix by the token cap (the first always fits)
-        bool pick = pick_pos >= 0;
-        const int idx = pick ? (int)order[pick_pos] : 0;
-        const int64_t tok = pick ? (int64_t)in_len[idx] : 0;
-        const int64_t len = pick ? (int64_t)qlen[pick_pos] : 0;
-        unsigned long long pick_mask = __ballot(pick);
-        if (pick_mask) {
-            const int first = __builtin_ctzll(pick_mask);
-            if (p.policy == MMBP_POLICY_PREFILL_FIRST_SINGLE) pick = pick && lane == first;
-            else if (maxtok > 0) {
-                const int64_t pre = wave_incl_scan_i64(tok, lane);
-                const unsigned long long fail = __ballot(pick && lane != first && pre > maxtok);
-                if (fail) pick = pick && lane < __builtin_ctzll(fail);
-            }
-            pick_mask = __ballot(pick);
+        bool pick[Q];
+        int idx[Q];
+        int64_t tok[Q], len[Q];
+        uint32_t first = 0xFFFFFFFFu;          // the first client that picks
+#pragma unroll
+        for (int q = Q - 1; q >= 0; q--) {
+            pick[q] = pick_pos[q] >= 0;
+            idx[q] = pick[q] ? (int)order[pick_pos[q]] : 0;
+            tok[q] = pick[q] ? (int64_t)in_len[idx[q]] : 0;
+            len[q] = pick[q] ? (int64_t)qlen[pick_pos[q]] : 0;
+            const unsigned long long pm = __ballot(pick[q]);
+            if (pm) first = (uint32_t)(q * kWave + __builtin_ctzll(pm));
         }
-        const int nA = __popcll(pick_mask);
-        const int64_t P = nA == 0 ? 0 : wave_sum_i64(pick ? tok : 0);
+        int nA = 0;
+        int64_t P = 0;
+        if (first != 0xFFFFFFFFu) {
+            if (p.policy == MMBP_POLICY_PREFILL_FIRST_SINGLE) {
+#pragma unroll
+                for (int q = 0; q < Q; q++) pick[q] = pick[q] && (uint32_t)(q * kWave + lane) == first;
+            } else if (maxtok > 0) {
+                uint32_t failpos = 0xFFFFFFFFu;  // the first pick that does not fit: it and the later ones wait
+                int64_t carry = 0;
+#pragma unroll
+                for (int q = 0; q < Q; q++) {
+                    const int64_t pre = carry + wave_incl_scan_i64(tok[q], lane);
+                    const unsigned long long fail = __ballot(pick[q] && (uint32_t)(q * kWave + lane) != first && pre > maxtok);
+                    if (fail && failpos == 0xFFFFFFFFu) failpos = (uint32_t)(q * kWave + __builtin_ctzll(fail));
+                    if (Q > 1) carry = uniform_i64(__shfl((long long)pre, kWave - 1));
+                }
+#pragma unroll
+                for (int q = 0; q < Q; q++) pick[q] = pick[q] && (uint32_t)(q * kWave + lane) < failpos;
+            }
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                nA += __popcll(__ballot(pick[q]));
+                P += wave_sum_i64(pick[q] ? tok[q] : 0);
+            }
+        }
         if (nA == 0 && nR == 0) { status = MMBP_ST_BAD_SIM_INPUT; break; }      // cannot happen while requests are left
 
         bool do_prefill = false;
@@ -188,19 +269,29 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
         if (do_prefill) {
             const int64_t dt = p.a_prefill * P + p.c_prefill;
             tr.other(1u, (uint32_t)nA, t, P, lane);
-            if (pick) {
-                rid = idx;
-                rem = (int32_t)(len - tok);
-                if (served_by) served_by[idx] = lane;
-                if (start_us) start_us[idx] = t;
-            }
-            unsigned long long m = pick_mask;                // the queues the picks came from move on
-            while (m) {
-                const int j = __builtin_ctzll(m);
-                m &= m - 1;
-                const int src = __builtin_amdgcn_readlane(pick_src, j);
-                const int64_t lj = readlane_i64(len, j);
-                if (lane == src) { head += 1; remain -= lj; }
+#pragma unroll
+            for (int q = 0; q < Q; q++)
+                if (pick[q]) {
+                    rid[q] = idx[q];
+                    rem[q] = (int32_t)(len[q] - tok[q]);
+                    if (served_by) served_by[idx[q]] = q * kWave + lane;
+                    if (start_us) start_us[idx[q]] = t;
+                }
+#pragma unroll
+            for (int jq = 0; jq < Q; jq++) {                 // the queues the picks came from move on
+                unsigned long long m = __ballot(pick[jq]);
+                while (m) {
+                    const int jl = __builtin_ctzll(m);
+                    m &= m - 1;
+                    const int src = __builtin_amdgcn_readlane(pick_src[jq], jl);
+                    const int64_t lj = readlane_i64(len[jq], jl);
+                    const int sq = src >> 6, sl = src & 63;
+                    if (lane == sl) {
+#pragma unroll
+                        for (int q = 0; q < Q; q++)
+                            if (q == sq) { head[q] += 1; remain[q] -= lj; }
+                    }
+                }
             }
             t += dt;
             nR += nA;
@@ -212,15 +303,24 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             const int64_t bD = p.b_decode * D;              // decode time of the D tokens of one iteration
             const int64_t dt = bD + p.c_decode;
             int64_t k = 1;                                   // nothing to pick: straight to the next finish
-            if (nA == 0) k = (int64_t)wave_min_u32(rem > 0 ? (uint32_t)rem : 0xFFFFFFFFu);
+            if (nA == 0) {
+                uint32_t m = 0xFFFFFFFFu;
+#pragma unroll
+                for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
+                k = (int64_t)wave_min_u32(m);
+            }
             tr.decode(t, D, (uint32_t)k, lane);
             const int64_t kdt = k * dt;
             t += kdt;
-            const bool active = rem > 0;
-            if (active) rem -= (int32_t)k;
-            const bool fin = active && rem == 0;
-            if (fin) finish[rid] = t;
-            const int nf = __popcll(__ballot(fin));
+            int nf = 0;
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                const bool active = rem[q] > 0;
+                if (active) rem[q] -= (int32_t)k;
+                const bool fin = active && rem[q] == 0;
+                if (fin) finish[rid[q]] = t;
+                nf += __popcll(__ballot(fin));
+            }
             done += nf;
             nR -= nf;
             busy += D * kdt;
@@ -248,9 +348,14 @@ hipError_t launch_online_sim_assigned(const int32_t *in_len, const int32_t *out_
                                       mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
                                       int trace_capacity, int32_t *status_out, hipStream_t st)
 {
-    online_sim_assigned_kernel<<<dim3(S), dim3(kWave), sim_assigned_lds_bytes(N), st>>>(
-        in_len, out_len, assign, S, N, p, finish_us, total_us, busy_slot_us, n_prefill_iter, n_decode_iter, trace_hash,
-        served_by, start_us, trace_buf, trace_len, trace_scenarios, trace_capacity, status_out);
+#define MMBP_SIMA_LAUNCH(QQ) \
+    online_sim_assigned_kernel<QQ><<<dim3(S), dim3(kWave), sim_assigned_lds_bytes(N), st>>>( \
+        in_len, out_len, assign, S, N, p, finish_us, total_us, busy_slot_us, n_prefill_iter, n_decode_iter, trace_hash, \
+        served_by, start_us, trace_buf, trace_len, trace_scenarios, trace_capacity, status_out)
+    if (p.cap <= kWave) MMBP_SIMA_LAUNCH(1);
+    else if (p.cap <= 2 * kWave) MMBP_SIMA_LAUNCH(2);
+    else MMBP_SIMA_LAUNCH(4);
+#undef MMBP_SIMA_LAUNCH
     return hipGetLastError();
 }
 

@@ -91,7 +91,7 @@ def test_host_side_argument_validation():
     assert lpt(one, 0, 1, 5, 2, 2, one, one, one, one, None) == api.EINFEASIBLE
     assert lpt(one, 0, 1, api.LPT_MAX_N + 1, 2, 1 << 20, one, one, one, one, None) == api.EUNSUPPORTED
     sim = lib.online_iter_sim
-    p = api.SimParams(65, 0, 1, 1, 1, 1, 0)
+    p = api.SimParams(257, 0, 1, 1, 1, 1, 0)
     args = lambda pp: (one, one, one, 1, 4, C.byref(pp), one, one, one, one, one, one, None, None, 0, 0, one, None)
     assert sim(*args(p)) == api.EUNSUPPORTED
     p = api.SimParams(0, 0, 1, 1, 1, 1, 0)
@@ -103,7 +103,7 @@ def test_host_side_argument_validation():
     assert sim(one, one, one, 1, 4, None, one, one, one, one, one, one, None, None, 0, 0, one, None) == api.EINVAL
     sa = lib.online_iter_sim_assigned
     aargs = lambda pp, n=4: (one, one, one, 1, n, C.byref(pp), one, one, one, one, one, one, None, None, None, None, 0, 0, one, None)
-    assert sa(*aargs(api.SimParams(65, 0, 1, 1, 1, 1, 0))) == api.EUNSUPPORTED
+    assert sa(*aargs(api.SimParams(257, 0, 1, 1, 1, 1, 0))) == api.EUNSUPPORTED
     assert sa(*aargs(api.SimParams(4, 0, 1, 1, 1, 1, 0), 8193)) == api.EUNSUPPORTED
     assert sa(*aargs(api.SimParams(4, 5, 1, 1, 1, 1, 0))) == api.EINVAL
     assert sa(*aargs(api.SimParams(0, 0, 1, 1, 1, 1, 0))) == api.EINVAL

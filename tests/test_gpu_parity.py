@@ -674,3 +674,65 @@ def test_hybrid_pipeline_offline_search_then_assigned_sim(oracle):
     o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, ls["assign"], p, 2, 8192)
     g = gpu_online_sim_assigned(w.in_len, w.out_len, ls["assign"], p, 2, 8192)
     compare_sim(g, o, label="hybrid")
+
+
+# ------------------------------------------------------------------ more clients than one wave has lanes
+@pytest.mark.parametrize("policy", [0, 1, 2])
+def test_sim_many_clients(oracle, policy):
+    """Batch sizes above 64 (up to the limit of 256): several client slots per lane."""
+    rng = np.random.default_rng(400 + policy)
+    for (S, N, cap, tok, rate) in [(5, 300, 65, 0, 400.0), (5, 700, 100, 0, 2000.0), (4, 900, 128, 5000, 3000.0),
+                                   (4, 900, 129, 0, 50.0), (4, 1319, 200, 0, 1e9), (3, 2500, 256, 9000, 5000.0),
+                                   (3, 600, 256, 300, 1e9)]:
+        w = W.config5(S=S, N=N, rate_per_s=rate, seed_offset=N + cap + policy)
+        p = dict(w.params, cap=cap, max_prefill_tokens=tok, policy=policy)
+        say(f"sim many clients policy={policy} N={N} cap={cap} tok={tok} rate={rate}")
+        o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, p, S, 6 * N + 8)
+        g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, p, S, 6 * N + 8)
+        compare_sim(g, o, label=f"many clients policy={policy} N={N} cap={cap}")
+
+
+def test_sim_paper_shaped_200_clients(oracle):
+    """The paper's own shape (Table "Experiment Settings": 1319 requests, 200 clients, its time model),
+    lengths drawn from its printed means and deviations: FCFS simulator with all requests at t = 0, and the
+    offline assignment (local search over 200 clients) run through the sorted queues with stealing."""
+    in_len, out_len = W.paper_shaped(S=12)
+    S, N = in_len.shape
+    p = dict(W.PAPER_PARAMS)
+    arr = np.zeros((S, N), np.int64)
+    say("paper-shaped FCFS, cap 200")
+    for pol in (0, 1, 2):
+        pp = dict(p, policy=pol)
+        compare_sim(gpu_online_sim(arr, in_len, out_len, pp, 2, 4096), oracle.online_iter_sim(arr, in_len, out_len, pp, 2, 4096),
+                    label=f"paper-shaped fcfs policy {pol}")
+    cost = W.job_cost(in_len, out_len, np.int32)
+    M = p["cap"]
+    cap = -(-N // M)
+    a0 = np.tile((np.arange(N) % M).astype(np.int32), (S, 1))
+    say("paper-shaped: local search over 200 clients, then the assigned simulator")
+    ls = gpu_local_search(cost, a0, M, cap + 2, 400, want_log=True)
+    ols = oracle.local_search(cost, a0, M, cap + 2, 400, want_log=True)
+    compare_ls(ls, ols, label="paper-shaped local search")
+    for pol in (0, 1):
+        pp = dict(p, policy=pol)
+        o = oracle.online_iter_sim_assigned(in_len, out_len, ls["assign"], pp, 2, 4096)
+        g = gpu_online_sim_assigned(in_len, out_len, ls["assign"], pp, 2, 4096)
+        compare_sim(g, o, label=f"paper-shaped assigned policy {pol}")
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2])
+def test_sim_assigned_many_clients(oracle, policy):
+    rng = np.random.default_rng(500 + policy)
+    for (S, N, cap, tok) in [(6, 300, 65, 0), (6, 500, 130, 0), (5, 1319, 200, 0), (5, 1319, 200, 900), (4, 2000, 256, 0),
+                             (4, 256, 256, 0), (4, 100, 200, 150)]:
+        w = W.config5(S=S, N=N, seed_offset=N + cap + policy)
+        assign = rng.integers(0, cap, (S, N)).astype(np.int32)
+        assign[0] = np.arange(N) % cap
+        assign[1] = np.minimum(np.arange(N) // max(N // 3, 1), cap - 1)      # few loaded clients, the others steal
+        assign[2] = cap - 1                                                  # one queue on the last client
+        assign[3] = (np.arange(N) * 7 % 3) * 64 % cap                       # queues on clients 0, 64, 128 (one per register block)
+        p = dict(w.params, cap=cap, max_prefill_tokens=tok, policy=policy)
+        say(f"sim assigned many clients policy={policy} N={N} cap={cap} tok={tok}")
+        o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
+        g = gpu_online_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
+        compare_sim(g, o, label=f"assigned many clients policy={policy} N={N} cap={cap}")
