@@ -191,7 +191,10 @@ int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap,
  * them improves.  Assignments, loads, makespans, pass counts, applied_log and status are identical
  * to mmbp_local_search on every input.  evals_out reports the candidates a full scan would have
  * enumerated (the same numbers mmbp_local_search reports), not the smaller number evaluated here.
- * Arguments, workspace and error behaviour as for mmbp_local_search.
+ * Arguments, workspace and error behaviour as for mmbp_local_search; a scenario that fits one
+ * workgroup's LDS is always searched there (each client's costs are kept sorted and the best partner of
+ * a request is found by binary search), and more shapes fit than for the full scan, which needs tables
+ * for its tiles: for those the workspace may be NULL although mmbp_workspace_bytes() is not 0.
  */
 int mmbp_local_search_pruned(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
                              int32_t *assign, int64_t *load_out, int64_t *makespan_out,

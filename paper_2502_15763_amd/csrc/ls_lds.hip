@@ -109,19 +109,19 @@ __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a -
 struct LdsDims {
     size_t P, U, C, T;            // padded positions, row units, column chunks, tasks (upper bounds)
 };
-__host__ __device__ inline LdsDims lds_dims(int N, int M)
+__host__ __device__ inline LdsDims lds_dims(int N, int M, bool prune)
 {
     LdsDims d;
     d.P = ((size_t)N + 63u) / 64u * 64u + 64u * (size_t)M;   // multiple of 64: keeps every array 16-byte aligned
-    d.U = d.P / (64u * kRMax) + (size_t)M;
-    d.C = (size_t)N / kChunk + (size_t)M;
+    d.U = prune ? 0 : d.P / (64u * kRMax) + (size_t)M;       // the pruned scan searches sorted columns: no tile tables
+    d.C = prune ? 0 : (size_t)N / kChunk + (size_t)M;
     d.T = d.U * d.C;
     return d;
 }
 
-__host__ __device__ inline size_t lds_bytes(int N, int M)
+__host__ __device__ inline size_t lds_bytes(int N, int M, bool prune)
 {
-    const LdsDims d = lds_dims(N, M);
+    const LdsDims d = lds_dims(N, M, prune);
     size_t b = 0;
     b += 4 * d.P;                     // cu
     b += 4 * d.P;                     // rowkey
@@ -139,9 +139,9 @@ __host__ __device__ inline size_t lds_bytes(int N, int M)
     return b;
 }
 
-__device__ inline Lds carve(unsigned char *base, int N, int M)
+__device__ inline Lds carve(unsigned char *base, int N, int M, bool prune)
 {
-    const LdsDims d = lds_dims(N, M);
+    const LdsDims d = lds_dims(N, M, prune);
     Lds l;
     size_t o = 0;
     l.cu = (uint32_t *)(base + o); o += 4 * d.P;
@@ -260,7 +260,7 @@ template <typename CostT, int BLOCK>
 __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const int32_t *asg, int N, int M, int cap, bool sorted)
 {
     const int tid = threadIdx.x;
-    const LdsDims d = lds_dims(N, M);
+    const LdsDims d = lds_dims(N, M, sorted);            // (sorted = the pruned scan: its tables have no entries)
     if (tid == 0) {
         int pos = 0, nf = 0, nch = 0, nu = 0;
         unsigned long long sq = 0;
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     uint64_t *applied_log, int32_t *status_out)
 {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    const Lds l = carve(lds_raw, N, M);
+    const Lds l = carve(lds_raw, N, M, PRUNE);
     Ctrl *ctrl = l.ctrl;
     const int s = blockIdx.x;
     const CostT *c = cost_all + (size_t)s * N;
@@ -400,7 +400,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
     // loads stay below 2^29 on this path: their low words are used
     auto load32 = [&](int g) -> uint32_t { return (uint32_t)l.load[g]; };
     const int Pmax = N + 64 * M;
-    const int Tmax = (int)lds_dims(N, M).T, Umax = (int)lds_dims(N, M).U, Cmax = (int)lds_dims(N, M).C;
+    const int Tmax = (int)lds_dims(N, M, PRUNE).T, Umax = (int)lds_dims(N, M, PRUNE).U, Cmax = (int)lds_dims(N, M, PRUNE).C;
     // A workgroup's waves go round the four SIMDs of its CU; the two halves of a SIMD's waves get
     // neighbouring ranges of the task table, so the SIMDs carry equal shares when waves outnumber them.
     const int twave = kWaves >= 8 ? (wave & 3) * (kWaves / 4) + (wave >> 2) : wave;
@@ -890,7 +890,7 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
-    size_t bytes = lds_bytes(N, M);
+    size_t bytes = lds_bytes(N, M, PRUNE);
 #ifdef MMBP_LDS_MINBYTES
     if (bytes < (size_t)(MMBP_LDS_MINBYTES)) bytes = (size_t)(MMBP_LDS_MINBYTES);
 #endif
@@ -908,7 +908,10 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
 
 }  // namespace
 
-bool ls_lds_fits(int N, int M) { return N < 65535 && N + 64 * M <= 65536 && lds_bytes(N, M) <= kLdsLimit; }
+bool ls_lds_fits(int N, int M, bool prune)
+{
+    return N < 65535 && N + 64 * M <= 65536 && lds_bytes(N, M, prune) <= kLdsLimit;
+}
 
 hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,

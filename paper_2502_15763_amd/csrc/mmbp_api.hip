@@ -83,7 +83,7 @@ static bool prefer_multi_workgroup(int S, int N, int M)
 size_t mmbp_workspace_bytes(int S, int N, int M)
 {
     if (S <= 0 || N <= 0 || M <= 0 || N > MMBP_MAX_N || M > MMBP_MAX_M) return 0;
-    if (mmbp::ls_lds_fits(N, M) && !prefer_multi_workgroup(S, N, M)) return 0;
+    if (mmbp::ls_lds_fits(N, M, false) && !prefer_multi_workgroup(S, N, M)) return 0;
     return mmbp::ls_grid_workspace_bytes(S, N, M);
 }
 
@@ -167,7 +167,7 @@ static int local_search_impl(int prune, const void *cost, int dtype, int S, int 
     if ((int64_t)N > (int64_t)M * (int64_t)cap) return MMBP_EINFEASIBLE;
     const size_t need = mmbp_workspace_bytes(S, N, M);
     const bool ws_ok = need > 0 && workspace && workspace_bytes >= need && ((uintptr_t)workspace & 255u) == 0;
-    const bool fits = mmbp::ls_lds_fits(N, M);
+    const bool fits = mmbp::ls_lds_fits(N, M, prune != 0);
     if (!fits && !ws_ok) return MMBP_EWORKSPACE;
     // The multi-workgroup path enqueues its launches pass by pass and cannot see convergence from the
     // host: a call applies at most MMBP_GRID_MAX_PASSES candidates.  A larger limit on a shape that
@@ -229,7 +229,7 @@ int mmbp_local_search_static(const void *cost, int dtype, int S, int N, int M, i
     void *ws = nullptr;
     if (need > kStaticScratchBytes) {
         // where the multi-workgroup path is only preferred the one-workgroup path still runs
-        if (!mmbp::ls_lds_fits(N, M)) return MMBP_EWORKSPACE;
+        if (!mmbp::ls_lds_fits(N, M, false)) return MMBP_EWORKSPACE;
     } else if (need > 0) {
         const int rc = static_scratch(&ws);
         if (rc != MMBP_OK) return rc;

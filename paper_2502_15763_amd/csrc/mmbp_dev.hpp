@@ -15,8 +15,9 @@ hipError_t launch_ls_generic(const void *cost, int dtype, int S, int N, int M, i
                              int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                              uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st);
 
-// LDS-resident path: true if shapes fit (N + 64*M padded positions in one workgroup's LDS).
-bool ls_lds_fits(int N, int M);
+// LDS-resident path: true if shapes fit (N + 64*M padded positions in one workgroup's LDS; the pruned
+// scan needs no tile tables, so more shapes fit it).
+bool ls_lds_fits(int N, int M, bool prune);
 hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes, int prune,
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                          uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st);

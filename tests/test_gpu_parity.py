@@ -713,6 +713,10 @@ def test_sim_paper_shaped_200_clients(oracle):
     ls = gpu_local_search(cost, a0, M, cap + 2, 400, want_log=True)
     ols = oracle.local_search(cost, a0, M, cap + 2, 400, want_log=True)
     compare_ls(ls, ols, label="paper-shaped local search")
+    # the pruned scan of this shape fits one workgroup (no tile tables), with or without a workspace
+    compare_ls(gpu_local_search(cost, a0, M, cap + 2, 400, pruned=True), ols, label="paper-shaped pruned search")
+    compare_ls(gpu_local_search(cost, a0, M, cap + 2, 400, pruned=True, use_workspace=False), ols,
+               label="paper-shaped pruned search, no workspace")
     for pol in (0, 1):
         pp = dict(p, policy=pol)
         o = oracle.online_iter_sim_assigned(in_len, out_len, ls["assign"], pp, 2, 4096)
