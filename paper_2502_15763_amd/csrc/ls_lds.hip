@@ -65,7 +65,7 @@ namespace mmbp {
 namespace {
 
 #ifndef MMBP_LDS_CHUNK
-#define MMBP_LDS_CHUNK 128
+#define MMBP_LDS_CHUNK 256
 #endif
 #ifndef MMBP_LDS_WPE
 #define MMBP_LDS_WPE 4
@@ -79,6 +79,7 @@ static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnabl
 struct Ctrl {
     unsigned long long pairs_per_scan;
     unsigned long long k0key;     // min over the rows against the critical client of (makespan << 32 | job << 16 | pos)
+    unsigned long long counted;   // candidates the waves have evaluated in this scan (sum of their own counts)
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
@@ -94,9 +95,9 @@ struct Ctrl {
 struct Lds {
     uint32_t *cu, *rowkey;        // rowkey[p]: best swap makespan of the job at p against the critical client
     uint16_t *job;
-    unsigned long long *tasks;    // (rowbase/64 | R << 10 | g << 13) | chunk record << 32
-    uint32_t *chunks;             // c0/64 | ncols << 10 | b << 19
-    uint32_t *uinfo;              // per row unit: rowbase/64 | R << 10 | g << 13
+    unsigned long long *tasks;    // row unit record | chunk record << 32
+    uint32_t *chunks;             // c0/64 | columns (jobs of the client in the chunk) << 10 | b << 19
+    uint32_t *uinfo;              // per row unit: rowbase/64 | R << 10 | g << 13 | rows (jobs of the client in the unit) << 21
     long long *load;
     int *cnt, *gstart, *fillc, *feas, *chpre, *upre;
     uint32_t *tdl, *tr1;          // per client, for the selection: l_g - l_critical and the key bound of a best swap
@@ -292,9 +293,9 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
     for (int p = tid; p < P; p += BLOCK) { l.cu[p] = kPad; l.job[p] = kNoJob; l.rowkey[p] = kInf; }
     // chunk records: one thread per client
     for (int g = tid; g < M; g += BLOCK) {
-        const int n = l.cnt[g], ncols = (n + 7) & ~7;
+        const int n = l.cnt[g];
         for (int k = l.chpre[g], q = 0; k < l.chpre[g + 1]; k++, q++)
-            l.chunks[k] = (uint32_t)((l.gstart[g] + q * kChunk) >> 6) | ((uint32_t)min(kChunk, ncols - q * kChunk) << 10) |
+            l.chunks[k] = (uint32_t)((l.gstart[g] + q * kChunk) >> 6) | ((uint32_t)min(kChunk, n - q * kChunk) << 10) |
                           ((uint32_t)g << 19);
     }
     __syncthreads();
@@ -311,7 +312,8 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
         while (g + 1 < M && l.upre[g + 1] <= u) g++;
         const int blk = (u - l.upre[g]) * kRMax;
         const int gseg = (l.gstart[g + 1] - l.gstart[g]) >> 6;
-        const uint32_t w0 = (uint32_t)((l.gstart[g] >> 6) + blk) | ((uint32_t)min(kRMax, gseg - blk) << 10) | ((uint32_t)g << 13);
+        const uint32_t w0 = (uint32_t)((l.gstart[g] >> 6) + blk) | ((uint32_t)min(kRMax, gseg - blk) << 10) | ((uint32_t)g << 13) |
+                            ((uint32_t)min(64 * kRMax, max(l.cnt[g] - blk * 64, 0)) << 21);
         if (u < (int)d.U) l.uinfo[u] = w0;
         const int k0 = l.chpre[g + 1], n = nCh - k0;
         if (n <= 0) continue;
@@ -419,13 +421,12 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         if ((long long)w_iters > (long long)max_passes + 1) { w_status = MMBP_ST_INTERNAL; w_stop = true; }
         else if (w_stop) { }
         else if (w_passes == max_passes) { w_status = MMBP_ST_TRUNCATED; w_stop = true; }
-        else w_evals += (unsigned long long)N * (unsigned long long)(M - 1) + w_pairs;
         __builtin_amdgcn_wave_barrier();   // lanes of a wave run in lockstep: earlier LDS updates are complete
         const Top3 t = SMALLM ? wave_top3_small(vnew, M, lane) : wave_top3(l.load, M, lane);
         if (lane == 0) {
             ctrl->top = t;
             ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->vrest = kInf; ctrl->k0key = ~0ull;
-            ctrl->next = 0; ctrl->adone = 0;
+            ctrl->next = 0; ctrl->adone = 0; ctrl->counted = 0;
             if (w_stop) ctrl->stop = 1;
         }
         if (reset_rows) {
@@ -451,9 +452,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             build_layout<CostT, BLOCK>(l, c, asg, N, M, cap, PRUNE);
             if (tid == 0) ctrl->rebuild = 0;             // (after the last barrier of build_layout: nobody
                                                          //  reads the flag before the next B0)
-            const unsigned long long np = ctrl->pairs_per_scan;
-            w_evals = w_evals - w_pairs + np;            // the pair count of the scan that starts now
-            w_pairs = np;
+            w_pairs = ctrl->pairs_per_scan;              // the pair count of the scan that starts now
         }
 
         const int P = min(ctrl->P, Pmax) & ~63;
@@ -469,8 +468,13 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         auto wload = [&](int g) -> uint32_t {
             return SMALLM ? (uint32_t)__builtin_amdgcn_readlane((int)vload, g) : uniu(load32(g));
         };
-        auto run = [&](int rowbase, int R, int X, int c0, int c1, int Y, bool star, uint32_t &sb, unsigned long long &kb) {
+        unsigned long long w_cnt = 0;                    // candidates this wave evaluates in this scan (uniform)
+        // w0: row unit record, w1: chunk record (their client fields are passed decoded as X and Y)
+        auto run = [&](uint32_t w0, int X, uint32_t w1, int Y, bool star, uint32_t &sb, unsigned long long &kb) {
+            const int rowbase = (int)(w0 & 0x3FFu) << 6, R = (int)((w0 >> 10) & 7u), c0 = (int)(w1 & 0x3FFu) << 6;
+            const int ncols = (int)((w1 >> 10) & 0x1FFu), c1 = c0 + ((ncols + 7) & ~7);
             if (R < 1 || R > kRMax || c1 <= c0 || c1 > Pmax || rowbase + 64 * R > Pmax) return;   // cannot happen
+            w_cnt += (unsigned long long)((w0 >> 21) & 0x1FFu) * (unsigned long long)ncols;   // jobs in the unit x jobs in the chunk
             const uint32_t lx = wload(X), ly = wload(Y);
             const uint32_t oth = others_max(top, X, Y);
             if (R == 1) run_tile<1>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sb, kb);
@@ -482,6 +486,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         };
         auto segment_moves = [&](int seg, int g) -> uint32_t {     // best move makespan of the 64 positions of a segment
                 const uint32_t x = l.cu[seg * 64 + lane];
+                w_cnt += (unsigned long long)__popcll(__ballot(x != kPad)) * (unsigned long long)(M - 1);
                 const uint32_t ci = (x - kBias) >> 1;
                 const uint32_t la = load32(g);
                 uint32_t m = kInf;
@@ -532,9 +537,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 for (int k = lo; k < hi; k++) {
                     const int u = uq < ua0 ? uq : uq + nua;
                     const uint32_t w0 = uniu(l.uinfo[min(u, Umax - 1)]), w1 = uniu(l.chunks[min(ca0 + cq, Cmax - 1)]);
-                    const int c0 = (int)(w1 & 0x3FFu) << 6;
-                    run((int)(w0 & 0x3FFu) << 6, (int)((w0 >> 10) & 7u), (int)((w0 >> 13) & 0xFFu), c0,
-                        c0 + (int)((w1 >> 10) & 0x1FFu), astar, true, sbest, kbest);
+                    run(w0, (int)((w0 >> 13) & 0xFFu), w1, astar, true, sbest, kbest);
                     if (++cq == nca) { cq = 0; uq++; }
                 }
             }
@@ -765,11 +768,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 if (t < ntask) {
                     const uint32_t w0 = uniu((uint32_t)rec), w1 = uniu((uint32_t)(rec >> 32));
                     const int X = (int)((w0 >> 13) & 0xFFu), Y = (int)((w1 >> 19) & 0xFFu);
-                    if (X != astar && Y != astar) {
-                        const int c0 = (int)(w1 & 0x3FFu) << 6;
-                        run((int)(w0 & 0x3FFu) << 6, (int)((w0 >> 10) & 7u), X, c0, c0 + (int)((w1 >> 10) & 0x1FFu), Y, false,
-                            rbest, knone);
-                    }
+                    if (X != astar && Y != astar) run(w0, X, w1, Y, false, rbest, knone);
                 } else {
                     const int seg = t - ntask;
                     const int g = l.seg_grp[seg];
@@ -778,6 +777,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             }
             rbest = wave_min_u32(rbest);
             if (lane == 0 && rbest != kInf) atomicMin(&ctrl->vrest, rbest);
+            if (lane == 0 && w_cnt != 0) atomicAdd(&ctrl->counted, w_cnt);
         }
         __syncthreads();                                 // B2: the scan is complete
         if (wave != 0) {                                 // the waves that now wait put the row minima back to "none"
@@ -789,6 +789,21 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         // ---- wave 0: apply (its operands were read before the barrier), open the next pass ----
         uint32_t vnew = vload;
         if (!PRUNE && uniu(ctrl->vrest) < T) act = kActError;       // cannot happen: those candidates keep the critical load
+        {
+            // The candidates of the scan: N (M - 1) moves and every pair on different clients.  The full
+            // scan reports what its waves counted while they ran the tiles and the move segments (moves
+            // whose targets are all full are the uniform capacity test: counted here) and stops the
+            // scenario if that is not the whole neighbourhood; the pruned scan reports the same number,
+            // which is by definition what a full scan would have enumerated.
+            const unsigned long long whole = (unsigned long long)N * (unsigned long long)(M - 1) + w_pairs;
+            if constexpr (PRUNE) w_evals += whole;
+            else {
+                unsigned long long counted = ctrl->counted;
+                if (nfeas == 0) counted += (unsigned long long)N * (unsigned long long)(M - 1);
+                if (counted != whole) act = kActError;
+                w_evals += counted;
+            }
+        }
         if (act == kActStop) {
             if (lane == 0) ctrl->stop = 1;
             continue;
