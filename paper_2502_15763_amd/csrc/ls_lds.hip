@@ -79,7 +79,7 @@ static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnabl
 struct Ctrl {
     unsigned long long pairs_per_scan;
     unsigned long long k0key;     // min over the rows against the critical client of (makespan << 32 | job << 16 | pos)
-    unsigned long long counted;   // candidates the waves have evaluated in this scan (sum of their own counts)
+    uint32_t counted;             // candidates the waves have evaluated in this scan (sum of their own counts)
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
@@ -468,13 +468,14 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         auto wload = [&](int g) -> uint32_t {
             return SMALLM ? (uint32_t)__builtin_amdgcn_readlane((int)vload, g) : uniu(load32(g));
         };
-        unsigned long long w_cnt = 0;                    // candidates this wave evaluates in this scan (uniform)
+        uint32_t w_cnt = 0;                              // candidates this wave evaluates in this scan (uniform; a scan of a
+                                                         // layout that fits the LDS has far fewer than 2^32)
         // w0: row unit record, w1: chunk record (their client fields are passed decoded as X and Y)
         auto run = [&](uint32_t w0, int X, uint32_t w1, int Y, bool star, uint32_t &sb, unsigned long long &kb) {
             const int rowbase = (int)(w0 & 0x3FFu) << 6, R = (int)((w0 >> 10) & 7u), c0 = (int)(w1 & 0x3FFu) << 6;
             const int ncols = (int)((w1 >> 10) & 0x1FFu), c1 = c0 + ((ncols + 7) & ~7);
             if (R < 1 || R > kRMax || c1 <= c0 || c1 > Pmax || rowbase + 64 * R > Pmax) return;   // cannot happen
-            w_cnt += (unsigned long long)((w0 >> 21) & 0x1FFu) * (unsigned long long)ncols;   // jobs in the unit x jobs in the chunk
+            w_cnt += ((w0 >> 21) & 0x1FFu) * (uint32_t)ncols;   // jobs in the unit x jobs in the chunk
             const uint32_t lx = wload(X), ly = wload(Y);
             const uint32_t oth = others_max(top, X, Y);
             if (R == 1) run_tile<1>(l, rowbase, c0, c1, lx, ly, oth, star, lane, sb, kb);
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         };
         auto segment_moves = [&](int seg, int g) -> uint32_t {     // best move makespan of the 64 positions of a segment
                 const uint32_t x = l.cu[seg * 64 + lane];
-                w_cnt += (unsigned long long)__popcll(__ballot(x != kPad)) * (unsigned long long)(M - 1);
+                w_cnt += (uint32_t)__popcll(__ballot(x != kPad)) * (uint32_t)(M - 1);
                 const uint32_t ci = (x - kBias) >> 1;
                 const uint32_t la = load32(g);
                 uint32_t m = kInf;
@@ -798,7 +799,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             const unsigned long long whole = (unsigned long long)N * (unsigned long long)(M - 1) + w_pairs;
             if constexpr (PRUNE) w_evals += whole;
             else {
-                unsigned long long counted = ctrl->counted;
+                unsigned long long counted = (unsigned long long)ctrl->counted;
                 if (nfeas == 0) counted += (unsigned long long)N * (unsigned long long)(M - 1);
                 if (counted != whole) act = kActError;
                 w_evals += counted;

@@ -35,24 +35,9 @@ __global__ __launch_bounds__(kBlock, Q == 1 ? 8 : 4) void online_sim_kernel(
     const int32_t *out_len = out_all + (size_t)s * N;
     int64_t *finish = finish_all + (size_t)s * N;
 
-    // ---- validation ----
-    int bad = 0;
-    for (int i = lane; i < N; i += kWave) {
-        int64_t a = arrival[i];
-        if (a < 0 || in_len[i] < 1 || out_len[i] < 1) bad = 1;
-        if (i > 0 && a < arrival[i - 1]) bad = 1;
-    }
-    if (__any(bad)) {
-        for (int i = lane; i < N; i += kWave) finish[i] = 0;
-        if (lane == 0) {
-            total_us[s] = 0; busy_slot_us[s] = 0; n_prefill_iter[s] = 0; n_decode_iter[s] = 0;
-            trace_hash[s] = 0;
-            if (trace_len && s < trace_scenarios) trace_len[s] = 0;
-            status_out[s] = MMBP_ST_BAD_SIM_INPUT;
-        }
-        return;
-    }
-
+    // Inputs are validated as they enter the window (one read of every array): nothing of a chunk is
+    // used before the chunk has been checked, and a scenario found invalid, however late, ends with
+    // all its outputs zero.
     const int cap = p.cap;
     const int64_t maxtok = p.max_prefill_tokens;
     Trace tr;
@@ -69,15 +54,25 @@ __global__ __launch_bounds__(kBlock, Q == 1 ? 8 : 4) void online_sim_kernel(
     __shared__ int64_t win_arr[kBlock / kWave][2 * kWin];
     __shared__ int32_t win_in[kBlock / kWave][2 * kWin], win_out[kBlock / kWave][2 * kWin];
     const int w = threadIdx.x >> 6;
+    bool invalid = false;
     auto load_chunk = [&](int chunk) {
+        int bad = 0;
 #pragma unroll
         for (int q = 0; q < Q; q++) {
             const int i = chunk * kWin + q * kWave + lane, slot = i & (2 * kWin - 1);
             const bool in = i < N;
-            win_arr[w][slot] = in ? arrival[i] : INT64_MAX;
-            win_in[w][slot] = in ? in_len[i] : 0;
-            win_out[w][slot] = in ? out_len[i] : 0;
+            const int64_t a = in ? arrival[i] : INT64_MAX;
+            const int32_t li = in ? in_len[i] : 1, lo = in ? out_len[i] : 1;
+            // arrival times must not decrease: the previous request's comes from the neighbouring lane, for
+            // lane 0 from memory (the same cache line, or the previous one)
+            int64_t prev = __shfl_up((long long)a, 1);
+            if (lane == 0) prev = (in && i > 0) ? arrival[i - 1] : 0;
+            if (in && (a < 0 || li < 1 || lo < 1 || a < prev)) bad = 1;
+            win_arr[w][slot] = a;
+            win_in[w][slot] = in ? li : 0;
+            win_out[w][slot] = in ? lo : 0;
         }
+        if (__any(bad)) invalid = true;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
     };
@@ -92,7 +87,7 @@ __global__ __launch_bounds__(kBlock, Q == 1 ? 8 : 4) void online_sim_kernel(
     int next = 0, done = 0, nR = 0, npre = 0, ndec = 0;
     int64_t head_arr = uniform_i64(win_arr[w][0]);
 
-    while (done < N) {
+    while (done < N && !invalid) {
         const int free_slots = cap - nR;
         int nA = 0;
         int64_t P = 0;
@@ -204,6 +199,16 @@ __global__ __launch_bounds__(kBlock, Q == 1 ? 8 : 4) void online_sim_kernel(
             Cd += k * bD;
             ndec += (int)k;
         }
+    }
+    if (invalid) {
+        for (int i = lane; i < N; i += kWave) finish[i] = 0;
+        if (lane == 0) {
+            total_us[s] = 0; busy_slot_us[s] = 0; n_prefill_iter[s] = 0; n_decode_iter[s] = 0;
+            trace_hash[s] = 0;
+            if (trace_len && s < trace_scenarios) trace_len[s] = 0;
+            status_out[s] = MMBP_ST_BAD_SIM_INPUT;
+        }
+        return;
     }
     tr.flush(lane);
     if (lane == 0) {

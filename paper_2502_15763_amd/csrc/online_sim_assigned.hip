@@ -63,13 +63,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     int64_t *start_us = start_all ? start_all + (size_t)s * N : nullptr;
     const int cap = p.cap;
 
-    // ---- validation ----
-    int bad = 0;
-    for (int i = lane; i < N; i += kWave) {
-        const int a = assign[i];
-        if (in_len[i] < 1 || out_len[i] < 1 || a < 0 || a >= cap) bad = 1;
-    }
-    if (__any(bad)) {
+    auto reject = [&]() {
         for (int i = lane; i < N; i += kWave) {
             finish[i] = 0;
             if (served_by) served_by[i] = -1;
@@ -81,15 +75,22 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             if (trace_len && s < trace_scenarios) trace_len[s] = 0;
             status_out[s] = MMBP_ST_BAD_SIM_INPUT;
         }
-        return;
-    }
+    };
 
     // ---- the sorted queues ----
 #pragma unroll
     for (int q = 0; q < Q; q++) cursor[q * kWave + lane] = 0;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    for (int i = lane; i < N; i += kWave) atomicAdd(&cursor[assign[i]], 1);
+    // (inputs are validated where they are first read: the clients here, the lengths in the pass that
+    //  fills the queues; nothing has been written when a scenario is rejected)
+    int bad = 0;
+    for (int i = lane; i < N; i += kWave) {
+        const int a = assign[i];
+        if (a < 0 || a >= cap) bad = 1;
+        else atomicAdd(&cursor[a], 1);
+    }
+    if (__any(bad)) { reject(); return; }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     int qbeg[Q], qend[Q];
@@ -115,9 +116,12 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     __builtin_amdgcn_wave_barrier();
     for (int i = lane; i < N; i += kWave) {
         const int pos = min(atomicAdd(&cursor[assign[i]], 1), N - 1);
+        const int32_t li = in_len[i], lo = out_len[i];
+        if (li < 1 || lo < 1) bad = 1;
         order[pos] = (uint16_t)i;
-        qlen[pos] = (uint32_t)in_len[i] + (uint32_t)out_len[i];
+        qlen[pos] = (uint32_t)li + (uint32_t)lo;
     }
+    if (__any(bad)) { reject(); return; }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
     int64_t remain[Q];

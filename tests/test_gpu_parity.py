@@ -489,6 +489,39 @@ def test_sim_bad_input(oracle):
     compare_sim(g, o, label="bad input")
 
 
+def test_sim_bad_input_found_late(oracle):
+    """Inputs are checked as they enter the simulator's window, so a bad entry far down the list is
+    found after hundreds of iterations have run and finish times have been written: every output of such
+    a scenario must still come out zero, and the scenarios around it untouched.  Entries at window
+    boundaries (multiples of 64 and 256) take the path that re-reads the previous arrival."""
+    for cap in (8, 200):
+        w = W.config5(S=9, N=1500, seed_offset=cap)
+        w.out_len[1, 1400] = 0
+        w.arrival_us[2, 1024] = w.arrival_us[2, 1023] - 1          # decreasing exactly at a window boundary
+        w.arrival_us[3, 641:] -= 5 * 10 ** 6
+        w.arrival_us[3, 641:] = np.maximum(w.arrival_us[3, 641:], 0)   # drops below its predecessor at 641
+        w.in_len[4, 1499] = -3
+        w.arrival_us[5, 768] = -1
+        w.arrival_us[6, 1] = w.arrival_us[6, 0] - 1 if w.arrival_us[6, 0] > 0 else -1
+        p = dict(w.params, cap=cap)
+        say(f"sim bad input found late, cap={cap}")
+        o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, p, 9, 64)
+        g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, p, 9, 64)
+        assert o["status"].tolist() == [0, 4, 4, 4, 4, 4, 4, 0, 0]
+        compare_sim(g, o, label=f"bad input late cap={cap}")
+        assert not g["finish_us"][1:7].any()
+    # the assigned simulator: lengths are checked in the pass that fills the queues
+    w = W.config5(S=4, N=900)
+    assign = (np.arange(4 * 900).reshape(4, 900) % 130).astype(np.int32)
+    w.in_len[1, 899] = 0
+    w.out_len[2, 450] = -1
+    p = dict(w.params, cap=130)
+    o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, assign, p)
+    g = gpu_online_sim_assigned(w.in_len, w.out_len, assign, p)
+    assert o["status"].tolist() == [0, 4, 4, 0]
+    compare_sim(g, o, label="assigned bad lengths")
+
+
 def test_sim_trace_capacity_overflow(oracle):
     w = W.config5(S=3, N=100)
     say("sim trace capacity smaller than the trace")
