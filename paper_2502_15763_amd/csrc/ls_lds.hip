@@ -201,11 +201,20 @@ __device__ __forceinline__ void run_tile(const Lds &l, int rowbase, int c0, int 
         x[r] = rowx[r] - (lx - ly);
     }
     tile_columns<R>(l.cu, x, c0, c1, key);
+    if (!star) {
+        // only the tile's best makespan is wanted, and the makespan grows with the key: one conversion
+        // for the smallest key of the lane's rows (an empty row's key is out of range and converts to none)
+        uint32_t kmin = kInf;
+#pragma unroll
+        for (int r = 0; r < R; r++) kmin = min(kmin, rowx[r] != kPad ? key[r] : kInf);
+        sbest = min(sbest, swap_value(kmin, lx + ly, oth));
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < R; r++) {
         const uint32_t v = rowx[r] != kPad ? swap_value(key[r], lx + ly, oth) : kInf;
         sbest = min(sbest, v);
-        if (star && v != kInf) {
+        if (v != kInf) {
             const int p = rowbase + 64 * r + lane;
             atomicMin(&l.rowkey[p], v);
             kbest = min(kbest, ((unsigned long long)v << 32) | ((unsigned long long)l.job[p] << 16) | (unsigned long long)p);
