@@ -825,12 +825,68 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 vnew = vload - (lane == a ? ci : 0u) + (lane == b ? ci : 0u);
                 if (lane == a || lane == b) l.load[lane] = (long long)vnew;
             }
+            bool in_place = false;
+            if constexpr (PRUNE) {
+                // Sorted layout, no tile tables: the job leaves its client's range (the later entries move down)
+                // and enters the target's at its place (the later entries move up) when the target's range has
+                // a free position; only a full range needs the jobs regrouped.
+                const int p = (int)(uint32_t)win;
+                const int ga0 = min(max(uni(l.gstart[a]), 0), P), na = min(max(uni(l.cnt[a]), 0), P - ga0);
+                const int gb0 = min(max(uni(l.gstart[b]), 0), P), gb1 = min(max(uni(l.gstart[b + 1]), 0), P);
+                const int nb = min(max(uni(l.cnt[b]), 0), P - gb0);
+                if (gb0 + nb < gb1 && p >= ga0 && p < ga0 + na) {
+                    in_place = true;
+                    const uint32_t x = 2u * ci + kBias;
+                    const int last = ga0 + na - 1;
+                    for (int p0 = p; p0 < last; p0 += kWave) {             // entries (p, last] move down by one
+                        const int q = p0 + lane;
+                        const bool in = q < last;
+                        const uint32_t v = in ? l.cu[q + 1] : 0u;
+                        const uint16_t jv = in ? l.job[q + 1] : (uint16_t)0;
+                        __builtin_amdgcn_wave_barrier();
+                        if (in) { l.cu[q] = v; l.job[q] = jv; }
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    if (lane == 0) { l.cu[last] = kPad; l.job[last] = kNoJob; }
+                    int less = 0;
+                    for (int p0 = gb0; p0 < gb0 + nb; p0 += kWave) {
+                        const int q = p0 + lane;
+                        less += __popcll(__ballot(q < gb0 + nb && l.cu[q] < x));
+                    }
+                    const int t = gb0 + less;
+                    for (int p1 = gb0 + nb; p1 > t; p1 -= kWave) {         // entries [t, end) move up by one
+                        const int q = p1 - lane;
+                        const bool in = q > t;
+                        const uint32_t v = in ? l.cu[q - 1] : 0u;
+                        const uint16_t jv = in ? l.job[q - 1] : (uint16_t)0;
+                        __builtin_amdgcn_wave_barrier();
+                        if (in) { l.cu[q] = v; l.job[q] = jv; }
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    if (lane == 0) { l.cu[t] = x; l.job[t] = (uint16_t)i; }
+                    // pairs on different clients: (N^2 - sum n^2) / 2 falls by n_b - n_a + 1
+                    w_pairs = (unsigned long long)((long long)w_pairs - ((long long)nb - (long long)na + 1));
+                }
+            }
             if (lane == 0) {
                 if (!SMALLM) { l.load[a] -= (long long)ci; l.load[b] += (long long)ci; }
                 l.cnt[a] -= 1; l.cnt[b] += 1;
                 asg[i] = b;
                 if (applied_log) applied_log[(size_t)s * max_passes + w_passes] = (uint64_t)(uint32_t)(win >> 32);
-                ctrl->rebuild = 1;
+                if (in_place) ctrl->pairs_per_scan = w_pairs;
+                else ctrl->rebuild = 1;
+            }
+            if (in_place) {                                  // move targets: the clients below the limit, ascending
+                __builtin_amdgcn_wave_barrier();
+                int nf = 0;
+                for (int j0 = 0; j0 < M; j0 += kWave) {
+                    const int j = j0 + lane;
+                    const bool ok = j < M && l.cnt[j] < cap;
+                    const unsigned long long m = __ballot(ok);
+                    if (ok) l.feas[nf + __popcll(m & ((1ull << lane) - 1ull))] = j;
+                    nf += __popcll(m);
+                }
+                if (lane == 0) ctrl->nfeas = nf;
             }
             w_passes += 1;
         } else if (act == kActSwap) {

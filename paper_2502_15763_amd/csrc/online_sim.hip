@@ -18,7 +18,7 @@ constexpr int kBlock = 256;
 // Q = client slots per lane: the batch size |J| may exceed one wave (the paper's node runs about 200
 // clients), so slot c lives in lane c % 64, register c / 64.
 template <int Q>
-__global__ __launch_bounds__(kBlock, Q == 1 ? 8 : 4) void online_sim_kernel(
+__global__ __launch_bounds__(kBlock) void online_sim_kernel(
     const int64_t *__restrict__ arrival_all, const int32_t *__restrict__ in_all, const int32_t *__restrict__ out_all,
     int S, int N, mmbp_sim_params p, int64_t *finish_all, int64_t *total_us, int64_t *busy_slot_us,
     int32_t *n_prefill_iter, int32_t *n_decode_iter, uint64_t *trace_hash, mmbp_trace_rec *trace_buf,

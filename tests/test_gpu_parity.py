@@ -365,6 +365,15 @@ def test_ls_pruned_sorted_search_with_ties_and_uneven_clients(oracle):
         o = oracle.local_search(cost, assign, M, cap, passes, want_log=True)
         compare_ls(gpu_local_search(cost, assign, M, cap, passes, pruned=True, use_workspace=False), o,
                    label=f"pruned sorted N={N} M={M}")
+    # many small clients, no binding limit, round-robin start: nearly every pass is a move, applied in place in
+    # the sorted layout until a client's range is full (then the jobs are regrouped)
+    for (S, N, M, cap, hi, passes) in [(3, 2048, 64, 2048, 60000, 400), (3, 640, 10, 640, 900, 200)]:
+        say(f"ls_pruned moves in place N={N} M={M}")
+        cost, assign = W.random_offline(rng, S, N, M, cap, cost_hi=hi, dtype=np.int32, start="rr")
+        o = oracle.local_search(cost, assign, M, cap, passes, want_log=True)
+        assert (o["log"][:, :20] < N * M).any()
+        compare_ls(gpu_local_search(cost, assign, M, cap, passes, pruned=True, use_workspace=False), o,
+                   label=f"pruned moves in place N={N} M={M}")
 
 
 # ------------------------------------------------------------------ lower bound
