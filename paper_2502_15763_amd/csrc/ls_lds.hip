@@ -586,10 +586,11 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             if (act == kActError) { }
             else if (V >= T) act = kActStop;                  // local optimum (status stays OK)
             else if (Vm <= Vs) {
-                // ---- a move wins (move ids are below swap ids): lowest id among moves of value V ----
+                // ---- a move wins (move ids are below swap ids): lowest id among moves of value V.  V is
+                //      below the makespan, so the job leaves the critical client: only its segments are scanned ----
                 unsigned long long best = ~0ull;
-                for (int seg = 0; seg < nseg; seg++) {
-                    const int g = l.seg_grp[seg];
+                for (int seg = sega; seg < segb; seg++) {
+                    const int g = astar;
                     const int p = seg * 64 + lane;
                     const uint32_t x = l.cu[p];
                     const uint32_t ci = (x - kBias) >> 1;
