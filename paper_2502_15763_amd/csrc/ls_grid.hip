@@ -50,6 +50,7 @@ static_assert(kSelWaves * 4 == kWave, "one candidate per lane in the selection o
 
 struct GCtrl {
     unsigned long long evals, pairs_per_scan;
+    int egrid;                                 // workgroups of the evaluation kernel (each leaves its candidate count)
     uint32_t vswap, vmove;
     uint32_t bjob[4];                          // first batch of a swap selection (grid_flag_kernel)
     Top3 top;
@@ -57,10 +58,10 @@ struct GCtrl {
 };
 
 struct GTask {
-    uint32_t xy;        // X | Y << 8 | nseg << 16   (row client, column client, row segments)
+    uint32_t xy;        // X | Y << 8 | nseg << 16 | rows << 21   (row client, column client, row segments, jobs in the row block)
     uint32_t xrow0;     // first row position
     uint32_t ycol0;     // first column position
-    uint32_t yncols;    // columns (multiple of 8)
+    uint32_t yncols;    // columns (multiple of 8) | jobs in the column chunk << 16
 };
 
 // what one workgroup of grid_flag_kernel found in its share of the layout
@@ -74,7 +75,7 @@ struct FlagPart {
 __host__ __device__ inline size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 struct GLayout {        // byte offsets inside one scenario's workspace slice
-    size_t ctrl, load, cnt, gstart, feas, cu, job, rowkey, pos, seg_grp, tasks, fpart, total;
+    size_t ctrl, load, cnt, gstart, feas, cu, job, rowkey, pos, seg_grp, tasks, fpart, ecount, total;
     int pmax, pstride, tmax;
 };
 
@@ -97,6 +98,7 @@ __host__ __device__ inline GLayout grid_layout(int N, int M)
     g.seg_grp = o; o += up256((size_t)g.pmax / 64 + 1);
     g.tasks = o; o += up256(sizeof(GTask) * (size_t)g.tmax);
     g.fpart = o; o += up256(sizeof(FlagPart) * (size_t)kFlagGrid);
+    g.ecount = o; o += up256(sizeof(unsigned long long) * (size_t)kEvalGrid);
     g.total = o;
     return g;
 }
@@ -110,6 +112,7 @@ struct GWs {
     uint8_t *seg_grp;
     GTask *tasks;
     FlagPart *fpart;
+    unsigned long long *ecount;          // per evaluation workgroup: candidates it evaluated in this scan
     int pmax, pstride, tmax;
 };
 
@@ -131,6 +134,7 @@ __device__ inline GWs grid_ws(void *workspace, int s, int N, int M)
     w.seg_grp = (uint8_t *)(b + g.seg_grp);
     w.tasks = (GTask *)(b + g.tasks);
     w.fpart = (FlagPart *)(b + g.fpart);
+    w.ecount = (unsigned long long *)(b + g.ecount);
     w.pmax = g.pmax;
     w.tmax = g.tmax;
     w.pstride = g.pstride;
@@ -246,18 +250,13 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
         // (the control fields are fetched before the top-3 reduction and used after it, so that
         // their latency overlaps with the loads of the reduction)
         int iters = 0, stop = 0, passes = 0, rk = 0;
-        unsigned long long evals = 0, pairs = 0;
-        if (lane == 0) {
-            iters = ctrl->iters + 1; stop = ctrl->stop; passes = ctrl->passes; rk = ctrl->rk;
-            evals = ctrl->evals; pairs = ctrl->pairs_per_scan;
-        }
+        if (lane == 0) { iters = ctrl->iters + 1; stop = ctrl->stop; passes = ctrl->passes; rk = ctrl->rk; }
         const Top3 t = wave_top3(w.load, M, lane);
         if (lane == 0) {
             ctrl->iters = iters;
             if ((long long)iters > (long long)max_passes + 1) { ctrl->status = MMBP_ST_INTERNAL; ctrl->stop = 1; }
             else if (stop) { }
             else if (passes == max_passes || last_launch) { ctrl->status = MMBP_ST_TRUNCATED; ctrl->stop = 1; }
-            else ctrl->evals = evals + (unsigned long long)N * (unsigned long long)(M - 1) + pairs;
             ctrl->vswap = kInf; ctrl->vmove = kInf;
             if (toggle) ctrl->rk = (rk & 1) ^ 1;         // the other buffer has been reset for the next pass
             *s_ntask = 0;
@@ -309,10 +308,11 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
                 for (int cc = 0; cc < ncc; cc++) {
                     if ((rb == 0 && cc == 0) != (round == 0)) continue;
                     GTask e;
-                    e.xy = (uint32_t)X | ((uint32_t)Y << 8) | ((uint32_t)min(kRowBlockSegs, segx - rb * kRowBlockSegs) << 16);
+                    e.xy = (uint32_t)X | ((uint32_t)Y << 8) | ((uint32_t)min(kRowBlockSegs, segx - rb * kRowBlockSegs) << 16) |
+                           ((uint32_t)min(kRowBlockSegs * 64, nx - rb * kRowBlockSegs * 64) << 21);
                     e.xrow0 = (uint32_t)(s_gs[X] + rb * kRowBlockSegs * 64);
                     e.ycol0 = (uint32_t)(s_gs[Y] + cc * cchunk);
-                    e.yncols = (uint32_t)min(cchunk, ncols - cc * cchunk);
+                    e.yncols = (uint32_t)min(cchunk, ncols - cc * cchunk) | ((uint32_t)min(cchunk, ny - cc * cchunk) << 16);
                     w.tasks[slot++] = e;
                 }
         }
@@ -326,8 +326,8 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
 // ---- kernel 0: validation, narrowing decision, layout, first pass preparation ----
 template <typename CostT>
 __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__restrict__ cost_all, int N, int M, int cap,
-                                                               int max_passes, int prune, int cchunk, int32_t *assign_all,
-                                                               OutPtrs o, void *workspace)
+                                                               int max_passes, int prune, int cchunk, int egrid,
+                                                               int32_t *assign_all, OutPtrs o, void *workspace)
 {
     const int s = blockIdx.x;
     const GWs w = grid_ws(workspace, s, N, M);
@@ -345,7 +345,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
     if (tid == 0) {
         s_bad_cost = 0; s_bad_assign = 0;
         ctrl->passes = 0; ctrl->status = MMBP_ST_OK; ctrl->stop = 0; ctrl->evals = 0; ctrl->iters = 0; ctrl->ntask = 0;
-        ctrl->prune = prune; ctrl->rk = 0; ctrl->cchunk = cchunk;
+        ctrl->prune = prune; ctrl->rk = 0; ctrl->cchunk = cchunk; ctrl->egrid = egrid;
     }
     __syncthreads();
     {
@@ -444,6 +444,7 @@ __global__ __launch_bounds__(kEvalBlock, 8) void grid_eval_kernel(int N, int M, 
     const int P = min(ctrl->P, w.pmax);
     const int nfeas = min(ctrl->nfeas, M);
     uint32_t sbest = kInf, mbest = kInf;
+    unsigned long long ecnt = 0, mcnt = 0;      // candidates of this workgroup's tasks (uniform) and of this wave's move segments
     for (int j = tid; j < M; j += kEvalBlock) { s_ld[j] = (uint32_t)w.load[j]; s_feas[j] = j < nfeas ? w.feas[j] : 0; }
     __syncthreads();
 
@@ -452,8 +453,9 @@ __global__ __launch_bounds__(kEvalBlock, 8) void grid_eval_kernel(int N, int M, 
     // tasks first instead, so the stride gives every workgroup the same number of them)
     for (int t = blockIdx.x; t < ntask; t += gridDim.x) {
         const GTask e = w.tasks[t];
-        const int X = (int)(e.xy & 0xFFu), Y = (int)((e.xy >> 8) & 0xFFu), nseg = min((int)(e.xy >> 16), kRowBlockSegs);
-        const int ncols = min((int)e.yncols, kColChunk) & ~7;
+        const int X = (int)(e.xy & 0xFFu), Y = (int)((e.xy >> 8) & 0xFFu), nseg = min((int)((e.xy >> 16) & 0x1Fu), kRowBlockSegs);
+        const int ncols = min((int)(e.yncols & 0xFFFFu), kColChunk) & ~7;
+        ecnt += (unsigned long long)(e.xy >> 21) * (unsigned long long)(e.yncols >> 16);     // jobs in the row block x jobs in the chunk
         const int ycol0 = max(min((int)e.ycol0, w.pmax - ncols), 0);
         for (int i = tid; i < ncols; i += kEvalBlock) cols[i] = w.cu[ycol0 + i];
         __syncthreads();
@@ -483,6 +485,7 @@ __global__ __launch_bounds__(kEvalBlock, 8) void grid_eval_kernel(int N, int M, 
             const uint32_t x = w.cu[seg * 64 + lane];
             const uint32_t ci = (x - kBias) >> 1;
             const uint32_t la = s_ld[g];
+            mcnt += (unsigned long long)__popcll(__ballot(x != kPad)) * (unsigned long long)(M - 1);
             uint32_t m = kInf;
             for (int q = 0; q < nfeas; q++) {
                 const int b = s_feas[q];
@@ -498,9 +501,12 @@ __global__ __launch_bounds__(kEvalBlock, 8) void grid_eval_kernel(int N, int M, 
     mbest = wave_min_u32(mbest);
     sbest = wave_min_u32(sbest);
     __shared__ uint32_t s_wm[kEvalBlock / kWave], s_ws[kEvalBlock / kWave];
-    if (lane == 0) { s_wm[wave] = mbest; s_ws[wave] = sbest; }
+    __shared__ unsigned long long s_wc[kEvalBlock / kWave];
+    if (lane == 0) { s_wm[wave] = mbest; s_ws[wave] = sbest; s_wc[wave] = mcnt; }
     __syncthreads();
     if (tid == 0) {
+        for (int q = 0; q < kEvalBlock / kWave; q++) ecnt += s_wc[q];
+        w.ecount[blockIdx.x] = ecnt;                     // plain store, every workgroup: the selection kernel adds them up
         for (int q = 1; q < kEvalBlock / kWave; q++) { mbest = min(mbest, s_wm[q]); sbest = min(sbest, s_ws[q]); }
         if (mbest < __hip_atomic_load(&ctrl->vmove, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMin(&ctrl->vmove, mbest);
         if (sbest < __hip_atomic_load(&ctrl->vswap, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicMin(&ctrl->vswap, sbest);
@@ -701,7 +707,36 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
     const uint32_t V = min(Vm, Vs);
     if (tid == 0) { s_rebuild = 0; s_later = kNoJob32; s_nlist = 0; s_best = ~0ull; }
     for (int j = tid; j < M; j += kSelBlock) { s_ld[j] = (uint32_t)w.load[j]; s_feas[j] = j < nfeas ? w.feas[j] : 0; }
+    // The candidates of the scan just run: N (M - 1) moves and every pair on different clients.  The
+    // full scan adds up what its evaluation workgroups counted (moves whose targets are all full are the
+    // uniform capacity test: counted here) and stops the scenario if that is not the whole
+    // neighbourhood; the pruned scan reports that number by definition.
+    __shared__ unsigned long long s_cnt[kSelWaves];
+    __shared__ int s_short;
+    {
+        unsigned long long part = 0;
+        const int eg = min(max(ctrl->egrid, 0), kEvalGrid);
+        if (!ctrl->prune)
+            for (int q = tid; q < eg; q += kSelBlock) part += w.ecount[q];
+        for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
+        if (lane == 0) s_cnt[tid >> 6] = part;
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned long long moves = (unsigned long long)N * (unsigned long long)(M - 1);
+            const unsigned long long whole = moves + ctrl->pairs_per_scan;
+            unsigned long long counted = nfeas == 0 ? moves : 0ull;
+            for (int q = 0; q < kSelWaves; q++) counted += s_cnt[q];
+            if (ctrl->prune) counted = whole;
+            s_short = counted != whole;
+            ctrl->evals += counted;
+            if (counted != whole) ctrl->status = MMBP_ST_INTERNAL;
+        }
+    }
     __syncthreads();
+    if (s_short) {                                       // cannot happen: the task table covers every client pair
+        g_finish(w, o, s, M);
+        return;
+    }
     if (V >= T) {                                        // local optimum
         g_finish(w, o, s, M);
         return;
@@ -958,10 +993,10 @@ hipError_t launch_ls_grid(const void *cost, int dtype, int S, int N, int M, int 
     const int egrid = want < 64 ? 64 : want < kEvalGrid ? (int)want : kEvalGrid;
     if (dtype == MMBP_I32)
         grid_stage_kernel<int32_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int32_t *)cost, N, M, cap, max_passes,
-                                                                       prune, cchunk, assign, o, workspace);
+                                                                       prune, cchunk, egrid, assign, o, workspace);
     else
         grid_stage_kernel<int64_t><<<dim3(S), dim3(kSelBlock), 0, st>>>((const int64_t *)cost, N, M, cap, max_passes,
-                                                                       prune, cchunk, assign, o, workspace);
+                                                                       prune, cchunk, egrid, assign, o, workspace);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int launches = max_passes < kMaxPassLaunches ? max_passes : kMaxPassLaunches;
