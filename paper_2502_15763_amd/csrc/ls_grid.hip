@@ -712,28 +712,32 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
     // uniform capacity test: counted here) and stops the scenario if that is not the whole
     // neighbourhood; the pruned scan reports that number by definition.
     __shared__ unsigned long long s_cnt[kSelWaves];
-    __shared__ int s_short;
+    bool count_short;
     {
+        // (the control words are fetched before the reduction so that their latency overlaps with it)
+        const unsigned long long pairs = ctrl->pairs_per_scan;
+        const int prune = ctrl->prune;
+        const unsigned long long ev0 = tid == 0 ? ctrl->evals : 0ull;
         unsigned long long part = 0;
         const int eg = min(max(ctrl->egrid, 0), kEvalGrid);
-        if (!ctrl->prune)
+        if (!prune)
             for (int q = tid; q < eg; q += kSelBlock) part += w.ecount[q];
         for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
         if (lane == 0) s_cnt[tid >> 6] = part;
         __syncthreads();
+        const unsigned long long moves = (unsigned long long)N * (unsigned long long)(M - 1);
+        const unsigned long long whole = moves + pairs;
+        unsigned long long counted = nfeas == 0 ? moves : 0ull;
+#pragma unroll
+        for (int q = 0; q < kSelWaves; q++) counted += s_cnt[q];
+        if (prune) counted = whole;
+        count_short = counted != whole;                  // the same in every thread: all read the same words
         if (tid == 0) {
-            const unsigned long long moves = (unsigned long long)N * (unsigned long long)(M - 1);
-            const unsigned long long whole = moves + ctrl->pairs_per_scan;
-            unsigned long long counted = nfeas == 0 ? moves : 0ull;
-            for (int q = 0; q < kSelWaves; q++) counted += s_cnt[q];
-            if (ctrl->prune) counted = whole;
-            s_short = counted != whole;
-            ctrl->evals += counted;
-            if (counted != whole) ctrl->status = MMBP_ST_INTERNAL;
+            ctrl->evals = ev0 + counted;
+            if (count_short) ctrl->status = MMBP_ST_INTERNAL;
         }
     }
-    __syncthreads();
-    if (s_short) {                                       // cannot happen: the task table covers every client pair
+    if (count_short) {                                   // cannot happen: the task table covers every client pair
         g_finish(w, o, s, M);
         return;
     }
