@@ -77,6 +77,15 @@ __device__ __forceinline__ HashLane hash_lane_init(int lane)
     return c;
 }
 
+// Writes the wave-uniform value v into lane LANE of x (v_writelane_b32: scalar source, constant lane).
+template <int LANE>
+__device__ __forceinline__ uint32_t put_lane(uint32_t x, uint32_t v)
+{
+    const uint32_t sv = (uint32_t)__builtin_amdgcn_readfirstlane((int)v);     // (already uniform: pins it to a scalar register)
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(x) : "s"(sv), "n"(LANE));
+    return x;
+}
+
 __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32_t count, int64_t t_start, int64_t x,
                                                const HashLane &c, int lane)
 {
@@ -90,33 +99,26 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
     uint32_t vv = 0;
     constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP2 = (uint32_t)fnv_pow(2), kP3 = (uint32_t)fnv_pow(3),
                        kP6 = (uint32_t)fnv_pow(6), kP24 = (uint32_t)fnv_pow(24);
-    int st = 0;
-    auto byte_step = [&](uint32_t b) {
-        const uint32_t v = lo ^ b;
-        vv = lane == st ? v : vv;
-        lo = v * kP1;
-        st++;
-    };
-    auto run_step = [&](uint32_t pl) {
-        vv = lane == st ? lo : vv;
-        lo = lo * pl;
-        st++;
-    };
+    // v is wave-uniform (a scalar), so lane ST takes it with one lane write: no lane mask, no select
+#define MMBP_BYTE_STEP(ST, B) do { const uint32_t v_ = lo ^ (B); vv = put_lane<ST>(vv, v_); lo = v_ * kP1; } while (0)
+#define MMBP_RUN_STEP(ST, PL) do { vv = put_lane<ST>(vv, lo); lo = lo * (PL); } while (0)
     const uint32_t tl = (uint32_t)ut, th = (uint32_t)(ut >> 32);
-    byte_step(kind);
-    run_step(kP3);
-    byte_step(count & 0xffu);
-    byte_step(count >> 8);
-    run_step(kP2);
-    byte_step(tl & 0xffu);
-    byte_step((tl >> 8) & 0xffu);
-    byte_step((tl >> 16) & 0xffu);
-    byte_step(tl >> 24);
-    byte_step(th);
-    run_step(kP3);
-    byte_step((uint32_t)ux & 0xffu);
-    byte_step((uint32_t)ux >> 8);
-    run_step(kP6);
+    MMBP_BYTE_STEP(0, kind);
+    MMBP_RUN_STEP(1, kP3);
+    MMBP_BYTE_STEP(2, count & 0xffu);
+    MMBP_BYTE_STEP(3, count >> 8);
+    MMBP_RUN_STEP(4, kP2);
+    MMBP_BYTE_STEP(5, tl & 0xffu);
+    MMBP_BYTE_STEP(6, (tl >> 8) & 0xffu);
+    MMBP_BYTE_STEP(7, (tl >> 16) & 0xffu);
+    MMBP_BYTE_STEP(8, tl >> 24);
+    MMBP_BYTE_STEP(9, th);
+    MMBP_RUN_STEP(10, kP3);
+    MMBP_BYTE_STEP(11, (uint32_t)ux & 0xffu);
+    MMBP_BYTE_STEP(12, (uint32_t)ux >> 8);
+    MMBP_RUN_STEP(13, kP6);
+#undef MMBP_BYTE_STEP
+#undef MMBP_RUN_STEP
     uint32_t e = (vv * c.ph + __umulhi(vv, c.pl)) * c.w;
     e += dpp_u32<0x111, 0xf>(0u, e);           // sum over the first row of 16 lanes
     e += dpp_u32<0x112, 0xf>(0u, e);
