@@ -17,7 +17,10 @@ constexpr int kBlock = 256;
 
 // Q = client slots per lane: the batch size |J| may exceed one wave (the paper's node runs about 200
 // clients), so slot c lives in lane c % 64, register c / 64.
-template <int Q>
+// FAST = the host saw that no trace records are wanted and that a_prefill and b_decode fit 31 bits: the
+// trace-store code is absent and the products of the time model take 32 x 64-bit multiplies.  The kernel
+// is bound by scalar instruction issue, so both count.
+template <int Q, bool FAST>
 __global__ __launch_bounds__(kBlock) void online_sim_kernel(
     const int64_t *__restrict__ arrival_all, const int32_t *__restrict__ in_all, const int32_t *__restrict__ out_all,
     int S, int N, mmbp_sim_params p, int64_t *finish_all, int64_t *total_us, int64_t *busy_slot_us,
@@ -40,10 +43,10 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
     // all its outputs zero.
     const int cap = p.cap;
     const int64_t maxtok = p.max_prefill_tokens;
-    Trace tr;
+    Trace<!FAST> tr;
     tr.h = kFnvBasis;
     tr.hc = hash_lane_init(lane);
-    const bool traced = trace_buf && s < trace_scenarios;
+    const bool traced = !FAST && trace_buf && s < trace_scenarios;
     tr.buf = traced ? trace_buf + (size_t)s * trace_capacity : nullptr;
     tr.cap = traced ? trace_capacity : 0;
     tr.len = 0; tr.run_open = 0; tr.run_count = 0; tr.run_t = 0; tr.run_D = 0;
@@ -133,12 +136,13 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             continue;
         }
         bool do_prefill = false;
+        int64_t Cp = 0;                        // cost of the prefill that could run now = its duration
         if (nA > 0) {
-            const int64_t Cp = p.a_prefill * P + p.c_prefill;
+            Cp = (FAST ? mul_u32_i64((uint32_t)p.a_prefill, P) : p.a_prefill * P) + p.c_prefill;
             do_prefill = (nR == 0) || (Cp < Cd) || p.policy != MMBP_POLICY_RULE;   // baseline: prefill at once
         }
         if (do_prefill) {
-            const int64_t dt = p.a_prefill * P + p.c_prefill;
+            const int64_t dt = Cp;
             tr.other(1u, (uint32_t)nA, t, P, lane);
             t += dt;
             int base = 0;                      // free slots before this register's block
@@ -159,13 +163,14 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 load_chunk(loaded);
             }
             nR += nA;
-            busy += (int64_t)nA * dt;
+            busy += FAST ? mul_u32_i64((uint32_t)nA, dt) : (int64_t)nA * dt;
             Cd = 0;
             npre++;
             head_arr = next < N ? uniform_i64(win_arr[w][next & (2 * kWin - 1)]) : INT64_MAX;
         } else {
             const int64_t D = nR;
-            const int64_t bD = p.b_decode * D;              // decode time of the D tokens of one iteration
+            // decode time of the D tokens of one iteration
+            const int64_t bD = FAST ? (int64_t)((uint64_t)(uint32_t)p.b_decode * (uint64_t)(uint32_t)nR) : p.b_decode * D;
             const int64_t dt = bD + p.c_decode;
             // With nothing admissible, every boundary up to the next finish or the next arrival that
             // finds a free slot takes the same decision with the same D: those k iterations are
@@ -182,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 }
             }
             tr.decode(t, D, (uint32_t)k, lane);
-            const int64_t kdt = k * dt;
+            const int64_t kdt = FAST ? mul_u32_i64((uint32_t)k, dt) : k * dt;
             t += kdt;
             int nf = 0;
 #pragma unroll
@@ -195,8 +200,8 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             }
             done += nf;
             nR -= nf;
-            busy += D * kdt;
-            Cd += k * bD;
+            busy += FAST ? mul_u32_i64((uint32_t)D, kdt) : D * kdt;
+            Cd += FAST ? mul_u32_i64((uint32_t)k, bD) : k * bD;
             ndec += (int)k;
         }
     }
@@ -229,13 +234,21 @@ hipError_t launch_online_sim(const int64_t *arrival_us, const int32_t *in_len, c
 {
     const int per_block = kBlock / kWave;
     dim3 g((S + per_block - 1) / per_block), b(kBlock);
-#define MMBP_SIM_LAUNCH(QQ) \
-    online_sim_kernel<QQ><<<g, b, 0, st>>>(arrival_us, in_len, out_len, S, N, p, finish_us, total_us, busy_slot_us, \
-                                           n_prefill_iter, n_decode_iter, trace_hash, trace_buf, trace_len, \
-                                           trace_scenarios, trace_capacity, status_out)
-    if (p.cap <= kWave) MMBP_SIM_LAUNCH(1);
-    else if (p.cap <= 2 * kWave) MMBP_SIM_LAUNCH(2);
-    else MMBP_SIM_LAUNCH(4);
+#define MMBP_SIM_LAUNCH(QQ, FF) \
+    online_sim_kernel<QQ, FF><<<g, b, 0, st>>>(arrival_us, in_len, out_len, S, N, p, finish_us, total_us, busy_slot_us, \
+                                               n_prefill_iter, n_decode_iter, trace_hash, trace_buf, trace_len, \
+                                               trace_scenarios, trace_capacity, status_out)
+    const bool fast = (!trace_buf || trace_scenarios <= 0) && p.a_prefill >= 0 && p.a_prefill < (1ll << 31) &&
+                      p.b_decode >= 0 && p.b_decode < (1ll << 31);
+    if (fast) {
+        if (p.cap <= kWave) MMBP_SIM_LAUNCH(1, true);
+        else if (p.cap <= 2 * kWave) MMBP_SIM_LAUNCH(2, true);
+        else MMBP_SIM_LAUNCH(4, true);
+    } else {
+        if (p.cap <= kWave) MMBP_SIM_LAUNCH(1, false);
+        else if (p.cap <= 2 * kWave) MMBP_SIM_LAUNCH(2, false);
+        else MMBP_SIM_LAUNCH(4, false);
+    }
 #undef MMBP_SIM_LAUNCH
     return hipGetLastError();
 }

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    Trace tr;
+    Trace<true> tr;
     tr.h = kFnvBasis;
     tr.hc = hash_lane_init(lane);
     const bool traced = trace_buf && s < trace_scenarios;

@@ -32,6 +32,16 @@ __device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t x, int lane)
     return x;
 }
 
+// a * b modulo 2^64 for a 32-bit a: three 32-bit multiplies and one add (a full 64 x 64 product takes seven
+// scalar instructions once a sign extension is involved)
+__device__ __forceinline__ int64_t mul_u32_i64(uint32_t a, int64_t b)
+{
+    const uint64_t ub = (uint64_t)b;
+    const uint64_t lo = (uint64_t)a * (uint64_t)(uint32_t)ub;
+    const uint32_t hi = a * (uint32_t)(ub >> 32);
+    return (int64_t)(lo + ((uint64_t)hi << 32));
+}
+
 template <int NBYTES>
 __device__ __forceinline__ uint64_t fnv_plain(uint64_t h, uint64_t w)
 {
@@ -128,6 +138,8 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
     return ((uint64_t)hi << 32) | lo;
 }
 
+// TRACED = false: the caller asked for no trace records, so none of the code that would store them exists.
+template <bool TRACED = true>
 struct Trace {
     uint64_t h;
     HashLane hc;
@@ -140,10 +152,12 @@ struct Trace {
     __device__ __forceinline__ void emit(uint32_t kind, uint32_t count, int64_t t_start, int64_t x, int lane)
     {
         h = fnv_record(h, kind, count, t_start, x, hc, lane);
-        if (buf && len < cap && lane == 0) {
-            mmbp_trace_rec r;
-            r.kind = kind; r.count = count; r.t_start = t_start; r.x = x;
-            buf[len] = r;
+        if constexpr (TRACED) {
+            if (buf && len < cap && lane == 0) {
+                mmbp_trace_rec r;
+                r.kind = kind; r.count = count; r.t_start = t_start; r.x = x;
+                buf[len] = r;
+            }
         }
         len++;
     }
