@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
         } else {
             const int64_t D = nR;
             // decode time of the D tokens of one iteration
-            const int64_t bD = FAST ? (int64_t)((uint64_t)(uint32_t)p.b_decode * (uint64_t)(uint32_t)nR) : p.b_decode * D;
+            const int64_t bD = FAST ? mul_u32_u32((uint32_t)p.b_decode, (uint32_t)nR) : p.b_decode * D;
             const int64_t dt = bD + p.c_decode;
             // With nothing admissible, every boundary up to the next finish or the next arrival that
             // finds a free slot takes the same decision with the same D: those k iterations are

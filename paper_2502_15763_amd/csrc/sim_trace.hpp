@@ -32,14 +32,26 @@ __device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t x, int lane)
     return x;
 }
 
-// a * b modulo 2^64 for a 32-bit a: three 32-bit multiplies and one add (a full 64 x 64 product takes seven
-// scalar instructions once a sign extension is involved)
+// Products of wave-uniform operands on the scalar unit, written out in 32-bit pieces: a 64 x 64-bit
+// product whose operands are known to be narrow still costs the full expansion (the zero halves are
+// multiplied too), and scalar issue is what bounds the simulators.
+__device__ __forceinline__ uint32_t s_mul_hi(uint32_t a, uint32_t b)
+{
+    uint32_t r;
+    asm("s_mul_hi_u32 %0, %1, %2" : "=s"(r) : "s"(a), "s"(b));
+    return r;
+}
+// a * b for 32-bit a and b: two instructions
+__device__ __forceinline__ int64_t mul_u32_u32(uint32_t a, uint32_t b)
+{
+    return (int64_t)(((uint64_t)s_mul_hi(a, b) << 32) | (uint64_t)(a * b));
+}
+// a * b modulo 2^64 for a 32-bit a: four instructions
 __device__ __forceinline__ int64_t mul_u32_i64(uint32_t a, int64_t b)
 {
-    const uint64_t ub = (uint64_t)b;
-    const uint64_t lo = (uint64_t)a * (uint64_t)(uint32_t)ub;
-    const uint32_t hi = a * (uint32_t)(ub >> 32);
-    return (int64_t)(lo + ((uint64_t)hi << 32));
+    const uint32_t bl = (uint32_t)(uint64_t)b, bh = (uint32_t)((uint64_t)b >> 32);
+    const uint32_t hi = s_mul_hi(a, bl) + a * bh;
+    return (int64_t)(((uint64_t)hi << 32) | (uint64_t)(a * bl));
 }
 
 template <int NBYTES>
