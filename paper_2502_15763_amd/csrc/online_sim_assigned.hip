@@ -40,7 +40,8 @@ __device__ __forceinline__ T sel(const T (&a)[Q], int sq)
 
 // Q = clients per lane: client j lives in lane j % 64, register j / 64 (the paper's node runs about
 // 200 clients, more than one wave has lanes).
-template <int Q>
+// FAST: no trace records wanted and time-model slopes below 2^31 (decided on the host), as in the FCFS simulator.
+template <int Q, bool FAST>
 __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     const int32_t *__restrict__ in_all, const int32_t *__restrict__ out_all, const int32_t *__restrict__ assign_all,
     int S, int N, mmbp_sim_params p, int64_t *finish_all, int64_t *total_us, int64_t *busy_slot_us,
@@ -146,10 +147,10 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
-    Trace<true> tr;
+    Trace<!FAST> tr;
     tr.h = kFnvBasis;
     tr.hc = hash_lane_init(lane);
-    const bool traced = trace_buf && s < trace_scenarios;
+    const bool traced = !FAST && trace_buf && s < trace_scenarios;
     tr.buf = traced ? trace_buf + (size_t)s * trace_capacity : nullptr;
     tr.cap = traced ? trace_capacity : 0;
     tr.len = 0; tr.run_open = 0; tr.run_count = 0; tr.run_t = 0; tr.run_D = 0;
@@ -266,12 +267,13 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
         if (nA == 0 && nR == 0) { status = MMBP_ST_BAD_SIM_INPUT; break; }      // cannot happen while requests are left
 
         bool do_prefill = false;
+        int64_t Cp = 0;                        // cost of the prefill that could run now = its duration
         if (nA > 0) {
-            const int64_t Cp = p.a_prefill * P + p.c_prefill;
+            Cp = (FAST ? mul_u32_i64((uint32_t)p.a_prefill, P) : p.a_prefill * P) + p.c_prefill;
             do_prefill = (nR == 0) || (Cp < Cd) || p.policy != MMBP_POLICY_RULE;
         }
         if (do_prefill) {
-            const int64_t dt = p.a_prefill * P + p.c_prefill;
+            const int64_t dt = Cp;
             tr.other(1u, (uint32_t)nA, t, P, lane);
 #pragma unroll
             for (int q = 0; q < Q; q++)
@@ -299,12 +301,13 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             }
             t += dt;
             nR += nA;
-            busy += (int64_t)nA * dt;
+            busy += FAST ? mul_u32_i64((uint32_t)nA, dt) : (int64_t)nA * dt;
             Cd = 0;
             npre++;
         } else {
             const int64_t D = nR;
-            const int64_t bD = p.b_decode * D;              // decode time of the D tokens of one iteration
+            // decode time of the D tokens of one iteration
+            const int64_t bD = FAST ? mul_u32_u32((uint32_t)p.b_decode, (uint32_t)nR) : p.b_decode * D;
             const int64_t dt = bD + p.c_decode;
             int64_t k = 1;                                   // nothing to pick: straight to the next finish
             if (nA == 0) {
@@ -314,7 +317,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                 k = (int64_t)wave_min_u32(m);
             }
             tr.decode(t, D, (uint32_t)k, lane);
-            const int64_t kdt = k * dt;
+            const int64_t kdt = FAST ? mul_u32_i64((uint32_t)k, dt) : k * dt;
             t += kdt;
             int nf = 0;
 #pragma unroll
@@ -327,8 +330,8 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             }
             done += nf;
             nR -= nf;
-            busy += D * kdt;
-            Cd += k * bD;
+            busy += FAST ? mul_u32_i64((uint32_t)D, kdt) : D * kdt;
+            Cd += FAST ? mul_u32_i64((uint32_t)k, bD) : k * bD;
             ndec += (int)k;
         }
     }
@@ -352,13 +355,21 @@ hipError_t launch_online_sim_assigned(const int32_t *in_len, const int32_t *out_
                                       mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
                                       int trace_capacity, int32_t *status_out, hipStream_t st)
 {
-#define MMBP_SIMA_LAUNCH(QQ) \
-    online_sim_assigned_kernel<QQ><<<dim3(S), dim3(kWave), sim_assigned_lds_bytes(N), st>>>( \
+#define MMBP_SIMA_LAUNCH(QQ, FF) \
+    online_sim_assigned_kernel<QQ, FF><<<dim3(S), dim3(kWave), sim_assigned_lds_bytes(N), st>>>( \
         in_len, out_len, assign, S, N, p, finish_us, total_us, busy_slot_us, n_prefill_iter, n_decode_iter, trace_hash, \
         served_by, start_us, trace_buf, trace_len, trace_scenarios, trace_capacity, status_out)
-    if (p.cap <= kWave) MMBP_SIMA_LAUNCH(1);
-    else if (p.cap <= 2 * kWave) MMBP_SIMA_LAUNCH(2);
-    else MMBP_SIMA_LAUNCH(4);
+    const bool fast = (!trace_buf || trace_scenarios <= 0) && p.a_prefill >= 0 && p.a_prefill < (1ll << 31) &&
+                      p.b_decode >= 0 && p.b_decode < (1ll << 31);
+    if (fast) {
+        if (p.cap <= kWave) MMBP_SIMA_LAUNCH(1, true);
+        else if (p.cap <= 2 * kWave) MMBP_SIMA_LAUNCH(2, true);
+        else MMBP_SIMA_LAUNCH(4, true);
+    } else {
+        if (p.cap <= kWave) MMBP_SIMA_LAUNCH(1, false);
+        else if (p.cap <= 2 * kWave) MMBP_SIMA_LAUNCH(2, false);
+        else MMBP_SIMA_LAUNCH(4, false);
+    }
 #undef MMBP_SIMA_LAUNCH
     return hipGetLastError();
 }

@@ -122,6 +122,14 @@ def gpu_online_sim_assigned(in_len, out_len, assign, params, trace_scenarios=0, 
         from oracle.oracle import TRACE_DTYPE
         out["trace"] = r["trace"].cpu().numpy().view(TRACE_DTYPE).reshape(trace_scenarios, trace_capacity)
         out["trace_len"] = r["trace_len"].cpu().numpy()
+        if r["rc"] == 0:                                 # the variant without trace records, as in gpu_online_sim
+            r2 = api.run_online_sim_assigned(to_dev(in_len.astype(np.int32)), to_dev(out_len.astype(np.int32)),
+                                             to_dev(assign.astype(np.int32)), params, 0, 0)
+            torch.cuda.synchronize()
+            assert r2["rc"] == 0
+            for k in ("finish_us", "total_us", "busy_slot_us", "n_prefill_iter", "n_decode_iter", "status", "served_by", "start_us"):
+                assert np.array_equal(r2[k].cpu().numpy(), out[k]), f"untraced variant: {k} differs from the traced run"
+            assert np.array_equal(u64(r2["trace_hash"]), out["trace_hash"]), "untraced variant: trace_hash differs"
     return out
 
 
