@@ -972,10 +972,7 @@ hipError_t launch_one(const void *cost, int S, int N, int M, int cap, int max_pa
                       int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
                       uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
-    size_t bytes = lds_bytes(N, M, PRUNE);
-#ifdef MMBP_LDS_MINBYTES
-    if (bytes < (size_t)(MMBP_LDS_MINBYTES)) bytes = (size_t)(MMBP_LDS_MINBYTES);
-#endif
+    const size_t bytes = lds_bytes(N, M, PRUNE);
     if (bytes > 64 * 1024) {                             // beyond the default limit: raise it for this kernel (per device,
                                                          // cheap, so done at every such launch)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&ls_lds_kernel<CostT, BLOCK, SMALLM, PRUNE>),
@@ -999,14 +996,10 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
                          int32_t *assign, int64_t *load_out, int64_t *makespan_out, int32_t *passes_out,
                          uint64_t *evals_out, uint64_t *applied_log, int32_t *status_out, hipStream_t st)
 {
-    // workgroup size by padded problem size: more waves shorten a pass when the workgroup is alone
-    // on its CU at the tail of a batch
-#ifdef MMBP_LDS_FORCE_BLOCK
-    const int block = (MMBP_LDS_FORCE_BLOCK);
-#else
+    // workgroup size by padded problem size (1024 threads were measured slower at every size: a scan has
+    // too few tiles for 16 waves)
     const int pmax = N + 64 * M;
     const int block = pmax <= 512 ? 256 : 512;
-#endif
 #define MMBP_LDS_LAUNCH(T, B, SM) \
     (prune ? launch_one<T, B, SM, true>(cost, S, N, M, cap, max_passes, assign, load_out, makespan_out, passes_out, evals_out, \
                                         applied_log, status_out, st) \
@@ -1014,8 +1007,7 @@ hipError_t launch_ls_lds(const void *cost, int dtype, int S, int N, int M, int c
                                          applied_log, status_out, st))
 #define MMBP_LDS_PICK(T) \
     (block == 256 ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 256, true) : MMBP_LDS_LAUNCH(T, 256, false)) \
-     : block == 512 ? (M <= 64 ? MMBP_LDS_LAUNCH(T, 512, true) : MMBP_LDS_LAUNCH(T, 512, false)) \
-                    : (M <= 64 ? MMBP_LDS_LAUNCH(T, 1024, true) : MMBP_LDS_LAUNCH(T, 1024, false)))
+                  : (M <= 64 ? MMBP_LDS_LAUNCH(T, 512, true) : MMBP_LDS_LAUNCH(T, 512, false)))
     if (dtype == MMBP_I32) return MMBP_LDS_PICK(int32_t);
     return MMBP_LDS_PICK(int64_t);
 #undef MMBP_LDS_PICK
