@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
         }
         if (do_prefill) {
             const int64_t dt = Cp;
-            tr.other(1u, (uint32_t)nA, t, P, lane);
+            tr.template other<FAST>(1u, (uint32_t)nA, t, P, lane);
             t += dt;
             int base = 0;                      // free slots before this register's block
 #pragma unroll
