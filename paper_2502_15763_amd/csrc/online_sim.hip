@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
 
     while (done < N && !invalid) {
         const int free_slots = cap - nR;
-        int nA = 0;
+        int nA = 0, nArr = 0;                  // admissible requests; arrived requests among the free_slots next ones
         int64_t P = 0;
         if (free_slots > 0 && head_arr <= t) {
             // admissible set A: FCFS prefix of the arrived requests that fits the free slots and the
@@ -109,21 +109,24 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 tok[q] = arrived[q] ? (int64_t)win_in[w][slot] : 0;
                 nA += __popcll(__ballot(arrived[q]));
             }
+            nArr = nA;
             if (maxtok > 0) {
                 int n2 = 0;
                 int64_t carry = 0;
 #pragma unroll
                 for (int q = 0; q < Q; q++) {
-                    const int64_t pre = carry + wave_incl_scan_i64(tok[q], lane);
+                    const int64_t pre = carry + wave_incl_scan_tokens(tok[q]);
                     n2 += __popcll(__ballot(arrived[q] && pre <= maxtok));
                     if (Q > 1) carry = uniform_i64(__shfl((long long)pre, kWave - 1));
                 }
                 nA = n2 == 0 ? 1 : n2;
             }
-            if (Q == 1) P = nA == 1 ? uniform_i64(tok[0]) : wave_sum_i64(lane < nA ? tok[0] : 0);
+            if (nA == 1) P = uniform_i64(tok[0]);
             else {
+                int64_t mine = 0;                  // this lane's share: at most Q input lengths
 #pragma unroll
-                for (int q = 0; q < Q; q++) P += wave_sum_i64(q * kWave + lane < nA ? tok[q] : 0);
+                for (int q = 0; q < Q; q++) mine += q * kWave + lane < nA ? tok[q] : 0;
+                P = wave_sum_tokens(mine);
             }
         }
         if (p.policy == MMBP_POLICY_PREFILL_FIRST_SINGLE && nA > 1) {      // baseline without batched prefill
@@ -172,19 +175,26 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             // decode time of the D tokens of one iteration
             const int64_t bD = FAST ? mul_u32_u32((uint32_t)p.b_decode, (uint32_t)nR) : p.b_decode * D;
             const int64_t dt = bD + p.c_decode;
-            // With nothing admissible, every boundary up to the next finish or the next arrival that
-            // finds a free slot takes the same decision with the same D: those k iterations are
-            // applied at once.  Otherwise (a prefill is waiting for C_d to pass C_p) one at a time.
-            int64_t k = 1;
-            if (nA == 0) {
+            // Until a request finishes or one more request arrives that could be admitted, every boundary
+            // sees the same admissible set and the same D, so the same decision: those k iterations are
+            // applied at once.  With nothing admissible they run to the next finish or the next arrival
+            // that finds a free slot; with a prefill waiting, also no further than the first j with
+            // C_d + j * bD > C_p.
+            int64_t k;
+            {
                 uint32_t m = 0xFFFFFFFFu;
 #pragma unroll
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
-                if (free_slots > 0 && head_arr != INT64_MAX && dt > 0) {
-                    const int64_t j = (head_arr - t + dt - 1) / dt;      // first boundary at or after the arrival
-                    k = min(k, max(j, (int64_t)1));
-                }
+            }
+            if (nA > 0 && bD > 0) k = min(k, (int64_t)((uint64_t)(Cp - Cd) / (uint64_t)bD) + 1);
+            // the first request that has not arrived yet, if a slot would be free for it
+            const int64_t next_arr = nArr == 0 ? head_arr
+                                   : (nArr < free_slots && next + nArr < N)
+                                         ? uniform_i64(win_arr[w][(next + nArr) & (2 * kWin - 1)]) : INT64_MAX;
+            if (free_slots > 0 && next_arr != INT64_MAX && dt > 0) {
+                const int64_t j = (next_arr - t + dt - 1) / dt;          // first boundary at or after the arrival
+                k = min(k, max(j, (int64_t)1));
             }
             tr.decode(t, D, (uint32_t)k, lane);
             const int64_t kdt = FAST ? mul_u32_i64((uint32_t)k, dt) : k * dt;

@@ -11,8 +11,9 @@
 // the iteration decision and the time model are those of the FCFS simulator, and picks are only
 // taken when the prefill is dispatched.  All requests are known at t = 0.
 //
-// Layout: the sorted queues sit one after the other in LDS (request index u16 and length u32 per
-// position); a lane keeps the head / end of its queue, its remain_token and its running request
+// Layout: the sorted queues sit one after the other in LDS (request index u16, length u32 and, while
+// every input length fits 16 bits, input length u16 per position, so that a pick reads nothing from
+// global memory; 8 bytes per request keep eight scenarios of 2048 requests on a CU); a lane keeps the head / end of its queue, its remain_token and its running request
 // in registers; time, C_d and the counters are wave-uniform.
 #include "mmbp_dev.hpp"
 
@@ -28,13 +29,18 @@ __device__ __forceinline__ int64_t readlane_i64(int64_t x, int l)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-// value of register block sq (uniform) of a per-lane array
-template <int Q, typename T>
-__device__ __forceinline__ T sel(const T (&a)[Q], int sq)
+// Lane sl's value of register block sq (both uniform) of a per-lane array.  Every block is read with a
+// constant index and the choice is made among the scalars: a select among the vector registers
+// themselves was compiled into an indexed array in scratch memory, a trip to memory per steal.
+template <int Q>
+__device__ __forceinline__ int lane_value(const int (&a)[Q], int sq, int sl)
 {
-    T v = a[0];
+    int v = __builtin_amdgcn_readlane(a[0], sl);
 #pragma unroll
-    for (int q = 1; q < Q; q++) v = sq == q ? a[q] : v;
+    for (int q = 1; q < Q; q++) {
+        const int vq = __builtin_amdgcn_readlane(a[q], sl);
+        v = sq == q ? vq : v;
+    }
     return v;
 }
 
@@ -51,6 +57,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     extern __shared__ __align__(16) unsigned char lds_raw[];
     uint32_t *qlen = reinterpret_cast<uint32_t *>(lds_raw);                 // [N] length of the request at a queue position
     uint16_t *order = reinterpret_cast<uint16_t *>(lds_raw + 4 * (size_t)N); // [N] request index at a queue position
+    uint16_t *qin = reinterpret_cast<uint16_t *>(lds_raw + 6 * (size_t)N);  // [N] its N^p_i (unused if one exceeds 16 bits)
     __shared__ int cursor[kWave * Q];
 
     const int lane = threadIdx.x;
@@ -85,7 +92,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     __builtin_amdgcn_wave_barrier();
     // (inputs are validated where they are first read: the clients here, the lengths in the pass that
     //  fills the queues; nothing has been written when a scenario is rejected)
-    int bad = 0;
+    int bad = 0, wide = 0;
     for (int i = lane; i < N; i += kWave) {
         const int a = assign[i];
         if (a < 0 || a >= cap) bad = 1;
@@ -119,6 +126,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
         const int pos = min(atomicAdd(&cursor[assign[i]], 1), N - 1);
         const int32_t li = in_len[i], lo = out_len[i];
         if (li < 1 || lo < 1) bad = 1;
+        if (li > 0xFFFF) wide = 1;
         order[pos] = (uint16_t)i;
         qlen[pos] = (uint32_t)li + (uint32_t)lo;
     }
@@ -144,6 +152,11 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             qlen[b] = kl; order[b] = ki;
         }
     }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const bool wide_in = __any(wide);          // some N^p_i does not fit 16 bits: picks read in_len from memory
+    if (!wide_in)
+        for (int pos = lane; pos < N; pos += kWave) qin[pos] = (uint16_t)in_len[order[pos]];
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
@@ -189,9 +202,15 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                 int64_t trm[Q];
 #pragma unroll
                 for (int q = 0; q < Q; q++) { th[q] = head[q]; trm[q] = remain[q]; }
+                // Only a prefix of the picks can join the prefill (one pick under the single-request baseline,
+                // the picks up to the first that exceeds the token cap otherwise), and nothing is taken
+                // here, so the visit ends with the pick that closes that prefix.
+                int64_t acc_tok = 0;
+                int npk = 0;
+                bool closed = false;
 #pragma unroll
                 for (int jq = 0; jq < Q; jq++) {                         // the idle clients in index order
-                    unsigned long long m = idle_mask[jq];
+                    unsigned long long m = closed ? 0ull : idle_mask[jq];
                     while (m) {
                         const int jl = __builtin_ctzll(m);
                         m &= m - 1;
@@ -209,11 +228,14 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
 #pragma unroll
                                 for (int q = Q - 1; q >= 0; q--) c = trm[q] == mx ? (uint32_t)(q * kWave + lane) : c;
                                 src = (int)wave_min_u32(c);
+                            } else {
+                                closed = true;           // every queue is empty by now (lengths are positive), also for
+                                m = 0;                   // the clients still to come: nobody else picks anything
                             }
                         }
                         if (src < 0) continue;
                         const int sq = src >> 6, sl = src & 63;
-                        const int pos = min(max(__builtin_amdgcn_readlane(sel<Q>(th, sq), sl), 0), N - 1);
+                        const int pos = min(max(lane_value<Q>(th, sq, sl), 0), N - 1);
                         const int64_t len = (int64_t)qlen[pos];
                         if (lane == jl) { pick_pos[jq] = pos; pick_src[jq] = src; }
                         if (lane == sl) {
@@ -221,6 +243,13 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                             for (int q = 0; q < Q; q++)
                                 if (q == sq) { th[q] += 1; trm[q] -= len; }
                         }
+                        npk++;
+                        if (p.policy == MMBP_POLICY_PREFILL_FIRST_SINGLE) closed = true;
+                        else if (maxtok > 0) {
+                            acc_tok += wide_in ? (int64_t)in_len[order[pos]] : (int64_t)qin[pos];
+                            closed = npk > 1 && acc_tok > maxtok;
+                        }
+                        if (closed) m = 0;
                     }
                 }
             }
@@ -234,7 +263,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
         for (int q = Q - 1; q >= 0; q--) {
             pick[q] = pick_pos[q] >= 0;
             idx[q] = pick[q] ? (int)order[pick_pos[q]] : 0;
-            tok[q] = pick[q] ? (int64_t)in_len[idx[q]] : 0;
+            tok[q] = pick[q] ? (wide_in ? (int64_t)in_len[idx[q]] : (int64_t)qin[pick_pos[q]]) : 0;
             len[q] = pick[q] ? (int64_t)qlen[pick_pos[q]] : 0;
             const unsigned long long pm = __ballot(pick[q]);
             if (pm) first = (uint32_t)(q * kWave + __builtin_ctzll(pm));
@@ -250,7 +279,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                 int64_t carry = 0;
 #pragma unroll
                 for (int q = 0; q < Q; q++) {
-                    const int64_t pre = carry + wave_incl_scan_i64(tok[q], lane);
+                    const int64_t pre = carry + wave_incl_scan_tokens(tok[q]);
                     const unsigned long long fail = __ballot(pick[q] && (uint32_t)(q * kWave + lane) != first && pre > maxtok);
                     if (fail && failpos == 0xFFFFFFFFu) failpos = (uint32_t)(q * kWave + __builtin_ctzll(fail));
                     if (Q > 1) carry = uniform_i64(__shfl((long long)pre, kWave - 1));
@@ -258,11 +287,13 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
 #pragma unroll
                 for (int q = 0; q < Q; q++) pick[q] = pick[q] && (uint32_t)(q * kWave + lane) < failpos;
             }
+            int64_t mine = 0;                      // this lane's share: at most Q input lengths
 #pragma unroll
             for (int q = 0; q < Q; q++) {
                 nA += __popcll(__ballot(pick[q]));
-                P += wave_sum_i64(pick[q] ? tok[q] : 0);
+                mine += pick[q] ? tok[q] : 0;
             }
+            P = wave_sum_tokens(mine);
         }
         if (nA == 0 && nR == 0) { status = MMBP_ST_BAD_SIM_INPUT; break; }      // cannot happen while requests are left
 
@@ -309,13 +340,18 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             // decode time of the D tokens of one iteration
             const int64_t bD = FAST ? mul_u32_u32((uint32_t)p.b_decode, (uint32_t)nR) : p.b_decode * D;
             const int64_t dt = bD + p.c_decode;
-            int64_t k = 1;                                   // nothing to pick: straight to the next finish
-            if (nA == 0) {
+            // Until a request finishes, the idle clients and their picks stay what they are, so every
+            // boundary sees the same C_p and the same D: with nothing to pick the decode iterations run
+            // to the next finish; with a prefill waiting they run until C_d has passed C_p (the first j
+            // with C_d + j * bD > C_p), or to the next finish if that comes first.
+            int64_t k;
+            {
                 uint32_t m = 0xFFFFFFFFu;
 #pragma unroll
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
             }
+            if (nA > 0 && bD > 0) k = min(k, (int64_t)((uint64_t)(Cp - Cd) / (uint64_t)bD) + 1);
             tr.decode(t, D, (uint32_t)k, lane);
             const int64_t kdt = FAST ? mul_u32_i64((uint32_t)k, dt) : k * dt;
             t += kdt;
@@ -346,7 +382,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
 
 }  // namespace
 
-size_t sim_assigned_lds_bytes(int N) { return 6 * (size_t)N + 16; }
+size_t sim_assigned_lds_bytes(int N) { return 8 * (size_t)N + 16; }
 
 hipError_t launch_online_sim_assigned(const int32_t *in_len, const int32_t *out_len, const int32_t *assign, int S, int N,
                                       const mmbp_sim_params &p, int64_t *finish_us, int64_t *total_us,
@@ -355,10 +391,19 @@ hipError_t launch_online_sim_assigned(const int32_t *in_len, const int32_t *out_
                                       mmbp_trace_rec *trace_buf, int32_t *trace_len, int trace_scenarios,
                                       int trace_capacity, int32_t *status_out, hipStream_t st)
 {
+    const size_t lds = sim_assigned_lds_bytes(N);
 #define MMBP_SIMA_LAUNCH(QQ, FF) \
-    online_sim_assigned_kernel<QQ, FF><<<dim3(S), dim3(kWave), sim_assigned_lds_bytes(N), st>>>( \
-        in_len, out_len, assign, S, N, p, finish_us, total_us, busy_slot_us, n_prefill_iter, n_decode_iter, trace_hash, \
-        served_by, start_us, trace_buf, trace_len, trace_scenarios, trace_capacity, status_out)
+    do { \
+        if (lds > 64 * 1024) {                           /* beyond the default limit: raise it for this kernel */ \
+            const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&online_sim_assigned_kernel<QQ, FF>), \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                                     (int)sim_assigned_lds_bytes(MMBP_SIM_ASSIGNED_MAX_N)); \
+            if (e != hipSuccess) return e; \
+        } \
+        online_sim_assigned_kernel<QQ, FF><<<dim3(S), dim3(kWave), lds, st>>>( \
+            in_len, out_len, assign, S, N, p, finish_us, total_us, busy_slot_us, n_prefill_iter, n_decode_iter, trace_hash, \
+            served_by, start_us, trace_buf, trace_len, trace_scenarios, trace_capacity, status_out); \
+    } while (0)
     const bool fast = (!trace_buf || trace_scenarios <= 0) && p.a_prefill >= 0 && p.a_prefill < (1ll << 31) &&
                       p.b_decode >= 0 && p.b_decode < (1ll << 31);
     if (fast) {

@@ -17,19 +17,31 @@ __device__ __forceinline__ int64_t uniform_i64(int64_t x)
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
-__device__ __forceinline__ int64_t wave_sum_i64(int64_t x)
+// Wave sum and inclusive wave scan of token counts 0 <= x < 2^33 (up to four input lengths per lane):
+// the low 24 bits and the bits above them go through 32-bit DPP reductions, which replaces twelve
+// dependent LDS permutes of a 64-bit shuffle reduction by twelve DPP adds.
+__device__ __forceinline__ uint32_t wave_incl_scan_u32(uint32_t x)
 {
-    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor((long long)x, off);
-    return uniform_i64(x);
+    uint32_t v = x;
+    v += dpp_u32<0x111, 0xf>(0u, v);           // row_shr 1, 2, 4, 8: inclusive prefix inside each row of 16
+    v += dpp_u32<0x112, 0xf>(0u, v);
+    v += dpp_u32<0x114, 0xf>(0u, v);
+    v += dpp_u32<0x118, 0xf>(0u, v);
+    v += dpp_u32<0x142, 0xa>(0u, v);           // row_bcast:15: rows 1 and 3 add the total of the row before
+    v += dpp_u32<0x143, 0xc>(0u, v);           // row_bcast:31: rows 2 and 3 add the total of rows 0 and 1
+    return v;
 }
 
-__device__ __forceinline__ int64_t wave_incl_scan_i64(int64_t x, int lane)
+__device__ __forceinline__ int64_t wave_sum_tokens(int64_t x)
 {
-    for (int off = 1; off < 64; off <<= 1) {
-        int64_t y = __shfl_up((long long)x, off);
-        if (lane >= off) x += y;
-    }
-    return x;
+    const uint32_t lo = (uint32_t)x & 0xFFFFFFu, hi = (uint32_t)((uint64_t)x >> 24);
+    return (int64_t)(((uint64_t)wave_sum_u32(hi) << 24) + (uint64_t)wave_sum_u32(lo));
+}
+
+__device__ __forceinline__ int64_t wave_incl_scan_tokens(int64_t x)
+{
+    const uint32_t lo = (uint32_t)x & 0xFFFFFFu, hi = (uint32_t)((uint64_t)x >> 24);
+    return (int64_t)(((uint64_t)wave_incl_scan_u32(hi) << 24) + (uint64_t)wave_incl_scan_u32(lo));
 }
 
 // Products of wave-uniform operands on the scalar unit, written out in 32-bit pieces: a 64 x 64-bit

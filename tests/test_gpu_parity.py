@@ -798,3 +798,43 @@ def test_sim_assigned_many_clients(oracle, policy):
         o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
         g = gpu_online_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
         compare_sim(g, o, label=f"assigned many clients policy={policy} N={N} cap={cap}")
+
+
+@pytest.mark.parametrize("cap", [64, 130, 256])
+def test_sim_assigned_maximum_size(oracle, cap):
+    """The largest request count the assigned simulator takes (its queues need more LDS than the
+    default limit of a launch there), for one, two and four clients per lane."""
+    N, S = 8192, 2
+    rng = np.random.default_rng(97 + cap)
+    w = W.config5(S=S, N=N, seed_offset=cap)
+    assign = rng.integers(0, cap, size=(S, N)).astype(np.int32)
+    assign[1] = np.minimum(assign[1], cap // 3)                             # idle clients from the start: stealing
+    in_len = w.in_len.copy()
+    if cap != 64:
+        in_len[1, ::1500] = 70000 + np.arange(len(in_len[1, ::1500]))       # input lengths beyond 16 bits in one scenario
+    w.in_len = in_len
+    p = dict(w.params, cap=cap, max_prefill_tokens=3000)
+    say(f"sim assigned maximum size N={N} cap={cap}")
+    o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
+    g = gpu_online_sim_assigned(w.in_len, w.out_len, assign, p, S, 4 * N + 8)
+    compare_sim(g, o, label=f"assigned maximum size cap={cap}")
+
+
+@pytest.mark.parametrize("b_decode", [0, 1, 7])
+def test_sim_prefill_waits_many_iterations(oracle, b_decode):
+    """A small decode slope against a large prefill constant: C_d needs hundreds of decode iterations
+    to pass C_p (never, with slope 0: then the prefill waits until nothing runs).  The kernels apply such
+    a wait in one step, bounded by the next finish and, in the FCFS simulator, by the next arrival that
+    could join the prefill; finish times, counters and the run-length trace must not change."""
+    S, N = 6, 400
+    for cap, rate, tok in ((8, 20, 0), (64, 200, 500), (200, 2000, 0)):
+        w = W.config5(S=S, N=N, rate_per_s=rate, seed_offset=cap + b_decode)
+        p = dict(cap=cap, a_prefill=3, b_decode=b_decode, c_prefill=40000, c_decode=900, max_prefill_tokens=tok, policy=0)
+        say(f"sim long waits b_decode={b_decode} cap={cap} rate={rate}")
+        o = oracle.online_iter_sim(w.arrival_us, w.in_len, w.out_len, p, S, 6 * N + 8)
+        g = gpu_online_sim(w.arrival_us, w.in_len, w.out_len, p, S, 6 * N + 8)
+        compare_sim(g, o, label=f"long waits b={b_decode} cap={cap}")
+        assign = (np.arange(N)[None, :] * 7 % max(cap // 2, 1)).astype(np.int32).repeat(S, axis=0)
+        o = oracle.online_iter_sim_assigned(w.in_len, w.out_len, assign, p, S, 6 * N + 8)
+        g = gpu_online_sim_assigned(w.in_len, w.out_len, assign, p, S, 6 * N + 8)
+        compare_sim(g, o, label=f"assigned, long waits b={b_decode} cap={cap}")
