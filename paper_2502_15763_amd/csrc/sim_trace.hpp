@@ -77,6 +77,14 @@ __device__ __forceinline__ uint64_t fnv_plain(uint64_t h, uint64_t w)
     return h;
 }
 
+// the byte-by-byte form of the record hash: rare, kept out of line so that the loops stay compact
+__device__ __attribute__((noinline)) uint64_t fnv_record_wide(uint64_t h, uint32_t kind, uint32_t count, uint64_t ut, uint64_t ux)
+{
+    h = fnv_plain<8>(h, (uint64_t)kind | ((uint64_t)count << 32));
+    h = fnv_plain<8>(h, ut);
+    return fnv_plain<8>(h, ux);
+}
+
 // FNV-1a of one 24-byte trace record (kind u32, count u32, t_start i64, x i64, little endian).
 //
 // A byte step is (hi:lo) <- ((hi:lo) ^ b) * prime.  The xor only touches lo, and a run of z zero
@@ -128,11 +136,8 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
                                                const HashLane &c, int lane)
 {
     const uint64_t ut = (uint64_t)t_start, ux = (uint64_t)x;
-    if (((uint64_t)(count >> 16) | (ut >> 40) | (ux >> 16) | (uint64_t)(kind >> 8)) != 0) {
-        h = fnv_plain<8>(h, (uint64_t)kind | ((uint64_t)count << 32));
-        h = fnv_plain<8>(h, ut);
-        return fnv_plain<8>(h, ux);
-    }
+    if (__builtin_expect(((uint64_t)(count >> 16) | (ut >> 40) | (ux >> 16) | (uint64_t)(kind >> 8)) != 0, 0))
+        return fnv_record_wide(h, kind, count, ut, ux);
     uint32_t lo = (uint32_t)h, hi = (uint32_t)(h >> 32);
     uint32_t vv = 0;
     constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP2 = (uint32_t)fnv_pow(2), kP3 = (uint32_t)fnv_pow(3),
