@@ -187,13 +187,14 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
             }
-            if (nA > 0 && bD > 0) k = min(k, (int64_t)((uint64_t)(Cp - Cd) / (uint64_t)bD) + 1);
+            if (nA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
             // the first request that has not arrived yet, if a slot would be free for it
             const int64_t next_arr = nArr == 0 ? head_arr
                                    : (nArr < free_slots && next + nArr < N)
                                          ? uniform_i64(win_arr[w][(next + nArr) & (2 * kWin - 1)]) : INT64_MAX;
             if (free_slots > 0 && next_arr != INT64_MAX && dt > 0) {
-                const int64_t j = (next_arr - t + dt - 1) / dt;          // first boundary at or after the arrival
+                // first boundary at or after the arrival (next_arr > t here, so the dividend is positive)
+                const int64_t j = (int64_t)udiv64((uint64_t)(next_arr - t + dt - 1), (uint64_t)dt);
                 k = min(k, max(j, (int64_t)1));
             }
             tr.decode(t, D, (uint32_t)k, lane);

@@ -351,7 +351,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
             }
-            if (nA > 0 && bD > 0) k = min(k, (int64_t)((uint64_t)(Cp - Cd) / (uint64_t)bD) + 1);
+            if (nA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
             tr.decode(t, D, (uint32_t)k, lane);
             const int64_t kdt = FAST ? mul_u32_i64((uint32_t)k, dt) : k * dt;
             t += kdt;

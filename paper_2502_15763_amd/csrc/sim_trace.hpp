@@ -44,13 +44,20 @@ __device__ __forceinline__ int64_t wave_incl_scan_tokens(int64_t x)
     return (int64_t)(((uint64_t)wave_incl_scan_u32(hi) << 24) + (uint64_t)wave_incl_scan_u32(lo));
 }
 
+// 64-bit division is a long instruction sequence: one copy, out of line, keeps the simulator loops compact
+// (they run from the instruction cache with eight waves per SIMD at different places).
+__device__ __attribute__((noinline)) uint64_t udiv64(uint64_t a, uint64_t b) { return a / b; }
+
 // Products of wave-uniform operands on the scalar unit, written out in 32-bit pieces: a 64 x 64-bit
 // product whose operands are known to be narrow still costs the full expansion (the zero halves are
 // multiplied too), and scalar issue is what bounds the simulators.
 __device__ __forceinline__ uint32_t s_mul_hi(uint32_t a, uint32_t b)
 {
+    // (the operands are wave-uniform; readfirstlane pins them to scalar registers even where the compiler
+    //  cannot prove that, and costs nothing where it can)
+    const uint32_t sa = (uint32_t)__builtin_amdgcn_readfirstlane((int)a), sb = (uint32_t)__builtin_amdgcn_readfirstlane((int)b);
     uint32_t r;
-    asm("s_mul_hi_u32 %0, %1, %2" : "=s"(r) : "s"(a), "s"(b));
+    asm("s_mul_hi_u32 %0, %1, %2" : "=s"(r) : "s"(sa), "s"(sb));
     return r;
 }
 // a * b for 32-bit a and b: two instructions
