@@ -102,8 +102,8 @@ def main():
         print(json.dumps({k: sources_sha256(k) for k in KERNEL_SOURCES}))
         return
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (scenarios are independent; see DESIGN.md for how "
-              "the batch would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU (scenarios are independent: more GPUs would each take a share of "
+              "the batch, with no exchange between them); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     if args.only:
         args.no_cpu_baseline = True
