@@ -79,6 +79,7 @@ static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnabl
 struct Ctrl {
     unsigned long long pairs_per_scan;
     unsigned long long k0key;     // min over the rows against the critical client of (makespan << 32 | job << 16 | pos)
+    unsigned long long kmove;     // min over the moves off the critical client of (makespan << 32 | move id)
     uint32_t counted;             // candidates the waves have evaluated in this scan (sum of their own counts)
     unsigned long long wsum[16];
     unsigned long long wmax[16];
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         const Top3 t = SMALLM ? wave_top3_small(vnew, M, lane) : wave_top3(l.load, M, lane);
         if (lane == 0) {
             ctrl->top = t;
-            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->vrest = kInf; ctrl->k0key = ~0ull;
+            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->vrest = kInf; ctrl->k0key = ~0ull; ctrl->kmove = ~0ull;
             ctrl->next = 0; ctrl->adone = 0; ctrl->counted = 0;
             if (w_stop) ctrl->stop = 1;
         }
@@ -514,8 +515,28 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         uint32_t mbest = kInf, sbest = kInf;
         unsigned long long kbest = ~0ull;
         const int sega = min(max(uni(l.gstart[astar]), 0), P) >> 6, segb = min(max(uni(l.gstart[astar + 1]), 0), P) >> 6;
+        // Moves off the critical client, with their ids (a move that wins is then known without a second
+        // look): every wave takes every segment of the client and a slice of the target clients, which
+        // keeps all waves busy where clients are many and small.
+        unsigned long long mkey = ~0ull;
         if (nfeas > 0)
-            for (int seg = sega + wave; seg < segb; seg += kWaves) mbest = min(mbest, segment_moves(seg, astar));
+            for (int seg = sega; seg < segb; seg++) {
+                const uint32_t x = l.cu[seg * 64 + lane], jb = l.job[seg * 64 + lane];
+                if (wave == 0) w_cnt += (uint32_t)__popcll(__ballot(x != kPad)) * (uint32_t)(M - 1);
+                const uint32_t ci = (x - kBias) >> 1;
+                const uint32_t la = load32(astar);
+                uint32_t bv = kInf, bid = kInf;
+                for (int q = wave; q < nfeas; q += kWaves) {
+                    const int b = l.feas[q];
+                    if (b == astar) continue;
+                    const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, astar, b));
+                    const uint32_t id = jb * (uint32_t)M + (uint32_t)b;
+                    const bool better = v < bv || (v == bv && id < bid);
+                    bv = better ? v : bv;
+                    bid = better ? id : bid;
+                }
+                if (x != kPad && bv != kInf) mkey = min(mkey, ((unsigned long long)bv << 32) | (unsigned long long)bid);
+            }
         if constexpr (PRUNE) {
             // every position outside the critical client against its sorted columns
             const int sb = min(max(uni(l.gstart[astar]), 0), P), sn = min(max(uni(l.cnt[astar]), 0), P - sb);
@@ -552,11 +573,14 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 }
             }
         }
-        if (nfeas > 0) mbest = wave_min_u32(mbest);
+        if (nfeas > 0) {
+            mkey = wave_min_u64(mkey);
+            mbest = (uint32_t)(mkey >> 32);              // (kInf when this wave saw no move)
+        }
         sbest = wave_min_u32(sbest);
         kbest = wave_min_u64(kbest);
         if (lane == 0) {
-            if (mbest != kInf) atomicMin(&ctrl->vmove, mbest);
+            if (mbest != kInf) { atomicMin(&ctrl->vmove, mbest); atomicMin(&ctrl->kmove, mkey); }
             if (sbest != kInf) atomicMin(&ctrl->vswap, sbest);
             if (kbest != ~0ull) atomicMin(&ctrl->k0key, kbest);
         }
@@ -586,26 +610,17 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             if (act == kActError) { }
             else if (V >= T) act = kActStop;                  // local optimum (status stays OK)
             else if (Vm <= Vs) {
-                // ---- a move wins (move ids are below swap ids): lowest id among moves of value V.  V is
-                //      below the makespan, so the job leaves the critical client: only its segments are scanned ----
+                // ---- a move wins (move ids are below swap ids): phase A left the lowest id among the moves of
+                //      value V; its job sits in one of the critical client's segments ----
+                const unsigned long long km = ctrl->kmove;
+                const uint32_t id = uniu((uint32_t)km);
+                const uint32_t ji = id / (uint32_t)M;
                 unsigned long long best = ~0ull;
-                for (int seg = sega; seg < segb; seg++) {
-                    const int g = astar;
-                    const int p = seg * 64 + lane;
-                    const uint32_t x = l.cu[p];
-                    const uint32_t ci = (x - kBias) >> 1;
-                    const uint32_t la = load32(g);
-                    const uint32_t jb = l.job[p];
-                    for (int q = 0; q < nfeas; q++) {
-                        const int b = l.feas[q];
-                        if (b == g) continue;
-                        const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
-                        if (x != kPad && v == V) {
-                            const unsigned long long id = (unsigned long long)jb * (unsigned long long)M + (unsigned long long)b;
-                            best = min(best, (id << 32) | (unsigned long long)p);
-                        }
+                if ((uint32_t)(km >> 32) == V)
+                    for (int seg = sega; seg < segb; seg++) {
+                        const int p = seg * 64 + lane;
+                        if (l.cu[p] != kPad && (uint32_t)l.job[p] == ji) best = ((unsigned long long)id << 32) | (unsigned long long)p;
                     }
-                }
                 win = wave_min_u64(best);
                 act = kActMove;
             } else {
