@@ -86,6 +86,7 @@ struct Ctrl {
     long long T0;
     uint32_t vswap, vmove, vrest;  // per-pass minima: swaps and moves that involve the critical client, the rest
     int nfeas, P, rebuild, ntask, nchunk;
+    int maxcnt;                   // jobs of the largest client when the layout was built
     int next;                     // work counter of the rest of the scan
     int adone;                    // waves that have posted their phase-A minima
     Top3 top;                     // three largest loads and their clients, published by wave 0
@@ -231,6 +232,28 @@ template <int BLOCK>
 __device__ void sort_groups(const Lds &l, int P)
 {
     const int tid = threadIdx.x;
+    if (l.ctrl->maxcnt <= kWave) {
+        // No client has more jobs than a wave has lanes, so every client is one segment: a wave sorts a
+        // segment in its registers (21 compare-exchange steps across the lanes) instead of all threads
+        // running the network over the whole layout (about a hundred steps with a barrier each, most of
+        // them over empty positions when clients are many and small).
+        const int lane = tid & 63;
+        for (int seg = tid >> 6; seg < (P >> 6); seg += BLOCK / kWave) {
+            uint32_t x = l.cu[seg * 64 + lane], jb = l.job[seg * 64 + lane];
+            for (int k = 2; k <= kWave; k <<= 1)
+                for (int j = k >> 1; j > 0; j >>= 1) {
+                    const uint32_t px = (uint32_t)__shfl_xor((int)x, j), pj = (uint32_t)__shfl_xor((int)jb, j);
+                    const bool take_min = ((lane & j) == 0) == ((lane & k) == 0);      // ascending blocks: the lower lane keeps the smaller
+                    const bool sw = take_min ? px < x : px > x;                        // (equal keys: both lanes keep their own)
+                    x = sw ? px : x;
+                    jb = sw ? pj : jb;
+                }
+            l.cu[seg * 64 + lane] = x;
+            l.job[seg * 64 + lane] = (uint16_t)jb;
+        }
+        __syncthreads();
+        return;
+    }
     int P2 = 1;
     while (P2 < P) P2 <<= 1;
     for (int k = 2; k <= P2; k <<= 1)
@@ -273,7 +296,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
     const int tid = threadIdx.x;
     const LdsDims d = lds_dims(N, M, sorted);            // (sorted = the pruned scan: its tables have no entries)
     if (tid == 0) {
-        int pos = 0, nf = 0, nch = 0, nu = 0;
+        int pos = 0, nf = 0, nch = 0, nu = 0, maxn = 0;
         unsigned long long sq = 0;
         for (int g = 0; g < M; g++) {
             l.gstart[g] = pos;
@@ -287,7 +310,9 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
             nu += (ns + kRMax - 1) / kRMax;
             if (n < cap) l.feas[nf++] = g;
             sq += (unsigned long long)n * (unsigned long long)n;
+            maxn = max(maxn, n);
         }
+        l.ctrl->maxcnt = maxn;
         l.gstart[M] = pos;
         l.chpre[M] = min(nch, (int)d.C);
         l.upre[M] = min(nu, (int)d.U);
