@@ -79,19 +79,18 @@ static_assert(kChunk % 64 == 0 && kChunk <= 64 * kRMax, "a chunk must be runnabl
 struct Ctrl {
     unsigned long long pairs_per_scan;
     unsigned long long k0key;     // min over the rows against the critical client of (makespan << 32 | job << 16 | pos)
-    unsigned long long kmove;     // min over the moves off the critical client of (makespan << 32 | move id)
     uint32_t counted;             // candidates the waves have evaluated in this scan (sum of their own counts)
     unsigned long long wsum[16];
     unsigned long long wmax[16];
     long long T0;
     uint32_t vswap, vmove, vrest;  // per-pass minima: swaps and moves that involve the critical client, the rest
     int nfeas, P, rebuild, ntask, nchunk;
-    int maxcnt;                   // jobs of the largest client when the layout was built
     int next;                     // work counter of the rest of the scan
     int adone;                    // waves that have posted their phase-A minima
     Top3 top;                     // three largest loads and their clients, published by wave 0
     int stop;
     int bad_cost, bad_assign;
+    unsigned long long kmove;     // min over the moves off the critical client of (makespan << 32 | move id)
 };
 
 struct Lds {
@@ -229,10 +228,12 @@ __device__ __forceinline__ void run_tile(const Lds &l, int rowbase, int c0, int 
 // act as +infinity without being stored; entries of different clients never change order (clients
 // occupy ascending position ranges), empty positions (kPad) end up last in their client's range.
 template <int BLOCK>
-__device__ void sort_groups(const Lds &l, int P)
+__device__ void sort_groups(const Lds &l, int P, int M)
 {
     const int tid = threadIdx.x;
-    if (l.ctrl->maxcnt <= kWave) {
+    int maxcnt = 0;                                      // jobs of the largest client (every thread reads all counts: broadcasts)
+    for (int g = 0; g < M; g++) maxcnt = max(maxcnt, l.cnt[g]);
+    if (maxcnt <= kWave) {
         // No client has more jobs than a wave has lanes, so every client is one segment: a wave sorts a
         // segment in its registers (21 compare-exchange steps across the lanes) instead of all threads
         // running the network over the whole layout (about a hundred steps with a barrier each, most of
@@ -296,7 +297,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
     const int tid = threadIdx.x;
     const LdsDims d = lds_dims(N, M, sorted);            // (sorted = the pruned scan: its tables have no entries)
     if (tid == 0) {
-        int pos = 0, nf = 0, nch = 0, nu = 0, maxn = 0;
+        int pos = 0, nf = 0, nch = 0, nu = 0;
         unsigned long long sq = 0;
         for (int g = 0; g < M; g++) {
             l.gstart[g] = pos;
@@ -310,9 +311,7 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
             nu += (ns + kRMax - 1) / kRMax;
             if (n < cap) l.feas[nf++] = g;
             sq += (unsigned long long)n * (unsigned long long)n;
-            maxn = max(maxn, n);
         }
-        l.ctrl->maxcnt = maxn;
         l.gstart[M] = pos;
         l.chpre[M] = min(nch, (int)d.C);
         l.upre[M] = min(nu, (int)d.U);
@@ -357,11 +356,11 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
         for (int q = 0; q < n; q++) l.tasks[base + q] = (unsigned long long)w0 | ((unsigned long long)l.chunks[k0 + q] << 32);
     }
     __syncthreads();
-    if (sorted) sort_groups<BLOCK>(l, min(l.ctrl->P, (int)d.P) & ~63);
+    if (sorted) sort_groups<BLOCK>(l, min(l.ctrl->P, (int)d.P) & ~63, M);
 }
 
 template <typename CostT, int BLOCK, bool SMALLM, bool PRUNE>
-__global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
+__global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel(
     const CostT *__restrict__ cost_all, int N, int M, int cap, int max_passes, int32_t *assign_all,
     int64_t *load_out, int64_t *makespan_out, int32_t *passes_out, uint64_t *evals_out,
     uint64_t *applied_log, int32_t *status_out)
@@ -460,7 +459,8 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         const Top3 t = SMALLM ? wave_top3_small(vnew, M, lane) : wave_top3(l.load, M, lane);
         if (lane == 0) {
             ctrl->top = t;
-            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->vrest = kInf; ctrl->k0key = ~0ull; ctrl->kmove = ~0ull;
+            ctrl->vswap = kInf; ctrl->vmove = kInf; ctrl->vrest = kInf; ctrl->k0key = ~0ull;
+            if constexpr (PRUNE) ctrl->kmove = ~0ull;
             ctrl->next = 0; ctrl->adone = 0; ctrl->counted = 0;
             if (w_stop) ctrl->stop = 1;
         }
@@ -540,28 +540,10 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
         uint32_t mbest = kInf, sbest = kInf;
         unsigned long long kbest = ~0ull;
         const int sega = min(max(uni(l.gstart[astar]), 0), P) >> 6, segb = min(max(uni(l.gstart[astar + 1]), 0), P) >> 6;
-        // Moves off the critical client, with their ids (a move that wins is then known without a second
-        // look): every wave takes every segment of the client and a slice of the target clients, which
-        // keeps all waves busy where clients are many and small.
-        unsigned long long mkey = ~0ull;
-        if (nfeas > 0)
-            for (int seg = sega; seg < segb; seg++) {
-                const uint32_t x = l.cu[seg * 64 + lane], jb = l.job[seg * 64 + lane];
-                if (wave == 0) w_cnt += (uint32_t)__popcll(__ballot(x != kPad)) * (uint32_t)(M - 1);
-                const uint32_t ci = (x - kBias) >> 1;
-                const uint32_t la = load32(astar);
-                uint32_t bv = kInf, bid = kInf;
-                for (int q = wave; q < nfeas; q += kWaves) {
-                    const int b = l.feas[q];
-                    if (b == astar) continue;
-                    const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, astar, b));
-                    const uint32_t id = jb * (uint32_t)M + (uint32_t)b;
-                    const bool better = v < bv || (v == bv && id < bid);
-                    bv = better ? v : bv;
-                    bid = better ? id : bid;
-                }
-                if (x != kPad && bv != kInf) mkey = min(mkey, ((unsigned long long)bv << 32) | (unsigned long long)bid);
-            }
+        if constexpr (!PRUNE) {
+            if (nfeas > 0)
+                for (int seg = sega + wave; seg < segb; seg += kWaves) mbest = min(mbest, segment_moves(seg, astar));
+        }
         if constexpr (PRUNE) {
             // every position outside the critical client against its sorted columns
             const int sb = min(max(uni(l.gstart[astar]), 0), P), sn = min(max(uni(l.cnt[astar]), 0), P - sb);
@@ -598,14 +580,43 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
                 }
             }
         }
-        if (nfeas > 0) {
-            mkey = wave_min_u64(mkey);
-            mbest = (uint32_t)(mkey >> 32);              // (kInf when this wave saw no move)
+        unsigned long long mkey = ~0ull;
+        if constexpr (PRUNE) {
+            // Moves off the critical client, with their ids (a move that wins is then known without a second
+            // look): every wave takes every segment of the client and a slice of the target clients, which
+            // keeps all waves busy where clients are many and small.
+            if (nfeas > 0)
+                for (int seg = sega; seg < segb; seg++) {
+                    const uint32_t x = l.cu[seg * 64 + lane], jb = l.job[seg * 64 + lane];
+                    if (wave == 0) w_cnt += (uint32_t)__popcll(__ballot(x != kPad)) * (uint32_t)(M - 1);
+                    const uint32_t ci = (x - kBias) >> 1;
+                    const uint32_t la = load32(astar);
+                    uint32_t bv = kInf, bid = kInf;
+                    for (int q = wave; q < nfeas; q += kWaves) {
+                        const int b = l.feas[q];
+                        if (b == astar) continue;
+                        const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, astar, b));
+                        const uint32_t id = jb * (uint32_t)M + (uint32_t)b;
+                        const bool better = v < bv || (v == bv && id < bid);
+                        bv = better ? v : bv;
+                        bid = better ? id : bid;
+                    }
+                    if (x != kPad && bv != kInf) mkey = min(mkey, ((unsigned long long)bv << 32) | (unsigned long long)bid);
+                }
+            if (nfeas > 0) {
+                mkey = wave_min_u64(mkey);
+                mbest = (uint32_t)(mkey >> 32);              // (kInf when this wave saw no move)
+            }
+        } else {
+            if (nfeas > 0) mbest = wave_min_u32(mbest);
         }
         sbest = wave_min_u32(sbest);
         kbest = wave_min_u64(kbest);
         if (lane == 0) {
-            if (mbest != kInf) { atomicMin(&ctrl->vmove, mbest); atomicMin(&ctrl->kmove, mkey); }
+            if (mbest != kInf) {
+                atomicMin(&ctrl->vmove, mbest);
+                if constexpr (PRUNE) atomicMin(&ctrl->kmove, mkey);
+            }
             if (sbest != kInf) atomicMin(&ctrl->vswap, sbest);
             if (kbest != ~0ull) atomicMin(&ctrl->k0key, kbest);
         }
@@ -635,17 +646,39 @@ __global__ __launch_bounds__(BLOCK, MMBP_LDS_WPE) void ls_lds_kernel(
             if (act == kActError) { }
             else if (V >= T) act = kActStop;                  // local optimum (status stays OK)
             else if (Vm <= Vs) {
-                // ---- a move wins (move ids are below swap ids): phase A left the lowest id among the moves of
-                //      value V; its job sits in one of the critical client's segments ----
-                const unsigned long long km = ctrl->kmove;
-                const uint32_t id = uniu((uint32_t)km);
-                const uint32_t ji = id / (uint32_t)M;
                 unsigned long long best = ~0ull;
-                if ((uint32_t)(km >> 32) == V)
+                if constexpr (PRUNE) {
+                    // ---- a move wins (move ids are below swap ids): phase A left the lowest id among the moves of
+                    //      value V; its job sits in one of the critical client's segments ----
+                    const unsigned long long km = ctrl->kmove;
+                    const uint32_t id = uniu((uint32_t)km);
+                    const uint32_t ji = id / (uint32_t)M;
+                    if ((uint32_t)(km >> 32) == V)
+                        for (int seg = sega; seg < segb; seg++) {
+                            const int p = seg * 64 + lane;
+                            if (l.cu[p] != kPad && (uint32_t)l.job[p] == ji) best = ((unsigned long long)id << 32) | (unsigned long long)p;
+                        }
+                } else {
+                    // ---- a move wins (move ids are below swap ids): lowest id among moves of value V.  V is
+                    //      below the makespan, so the job leaves the critical client: only its segments are scanned ----
                     for (int seg = sega; seg < segb; seg++) {
+                        const int g = astar;
                         const int p = seg * 64 + lane;
-                        if (l.cu[p] != kPad && (uint32_t)l.job[p] == ji) best = ((unsigned long long)id << 32) | (unsigned long long)p;
+                        const uint32_t x = l.cu[p];
+                        const uint32_t ci = (x - kBias) >> 1;
+                        const uint32_t la = load32(g);
+                        const uint32_t jb = l.job[p];
+                        for (int q = 0; q < nfeas; q++) {
+                            const int b = l.feas[q];
+                            if (b == g) continue;
+                            const uint32_t v = max(max(la - ci, load32(b) + ci), others_max(top, g, b));
+                            if (x != kPad && v == V) {
+                                const unsigned long long id = (unsigned long long)jb * (unsigned long long)M + (unsigned long long)b;
+                                best = min(best, (id << 32) | (unsigned long long)p);
+                            }
+                        }
                     }
+                }
                 win = wave_min_u64(best);
                 act = kActMove;
             } else {
