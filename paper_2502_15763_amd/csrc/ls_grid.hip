@@ -266,15 +266,41 @@ __device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M,
     __syncthreads();
     if (ctrl->stop) { g_finish(w, o, s, M); return false; }
     __shared__ int s_cn[MMBP_MAX_M], s_gs[MMBP_MAX_M];
-    for (int j = tid; j < M; j += kSelBlock) { s_cn[j] = w.cnt[j]; s_gs[j] = w.gstart[j]; }
+    __shared__ int s_single;                             // every client is non-empty, one row block and one column chunk
     const int prune = ctrl->prune;
     const int cchunk = min(max(ctrl->cchunk, kMinColChunk), kColChunk) & ~7;
+    if (tid == 0) s_single = 1;
+    __syncthreads();
+    for (int j = tid; j < M; j += kSelBlock) {
+        const int n = w.cnt[j];
+        s_cn[j] = n; s_gs[j] = w.gstart[j];
+        if (n <= 0 || n > kRowBlockSegs * 64 || ((n + 7) & ~7) > cchunk) s_single = 0;
+    }
     __syncthreads();
     // task table: every unordered pair of non-empty clients once, the critical client as columns
     const int astar = min(max(ctrl->top.j0, 0), M - 1);
     // Two rounds: the first task of every pair (a full row block x a full column chunk unless the
     // pair is smaller), then the remainders, so that the stride loop of the evaluation gives every
     // workgroup the same number of large tasks.
+    if (s_single && !prune) {
+        // Every pair of clients is exactly one task: its slot follows from the pair (the pairs (g, b),
+        // g < b, in row-major order), so the table needs no slot reservation and no second round.
+        for (int q = tid; q < M * M; q += kSelBlock) {
+            const int g = q / M, b = q - g * M;
+            if (g >= b) continue;
+            const int X = (g == astar) ? b : g, Y = (g == astar) ? g : b;
+            const int nx = s_cn[X], ny = s_cn[Y];
+            GTask e;
+            e.xy = (uint32_t)X | ((uint32_t)Y << 8) | ((uint32_t)((nx + 63) >> 6) << 16) | ((uint32_t)nx << 21);
+            e.xrow0 = (uint32_t)s_gs[X];
+            e.ycol0 = (uint32_t)s_gs[Y];
+            e.yncols = (uint32_t)((ny + 7) & ~7) | ((uint32_t)ny << 16);
+            const int slot = g * M - (g * (g + 1)) / 2 + (b - g - 1);
+            if (slot < w.tmax) w.tasks[slot] = e;        // (always: tmax bounds the table)
+        }
+        if (tid == 0) ctrl->ntask = min(M * (M - 1) / 2, w.tmax);
+        return true;
+    }
     __shared__ int s_more;                               // some pair has more than one task
     if (tid == 0) s_more = 0;
     __syncthreads();
