@@ -144,8 +144,20 @@ def main():
             ms = a.elapsed_time(b)
             best = ms if best is None else min(best, ms)
         rate = ops / (best / 1e3)
+        # the same loop with fewer resident waves: what one, two and four waves per SIMD sustain (a workgroup
+        # of 256 threads is one wave per SIMD of its CU; 256 workgroups are one per CU)
+        by_occ = {}
+        for waves, nb in ((1, 256), (2, 512), (4, 1024)):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            o = api.mmbp_valu_probe(buf[:nb * 256], nb, trips)
+            b.record()
+            torch.cuda.synchronize()
+            by_occ[str(waves)] = o / (a.elapsed_time(b) / 1e3) / ALU_PEAK_LANE_OPS
+        by_occ["8"] = rate / ALU_PEAK_LANE_OPS
         return {"lane_ops_per_s": rate, "ms": best, "lane_ops": ops,
                 "implied_clock_ghz": rate / (N_CU * LANES_PER_CU_CLK) / 1e9,
+                "fraction_of_nominal_peak_by_waves_per_simd": by_occ,
                 "kernel": "valu_probe_kernel (registers only: 32 v_sub_u32 + 16 v_min3_u32 + 16 v_max3_u32 + 8 v_add_u32 per trip)"}
 
     calib = calibrate()
