@@ -144,6 +144,10 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             Cp = (FAST ? mul_u32_i64((uint32_t)p.a_prefill, P) : p.a_prefill * P) + p.c_prefill;
             do_prefill = (nR == 0) || (Cp < Cd) || p.policy != MMBP_POLICY_RULE;   // baseline: prefill at once
         }
+        // A prefill that fills the last free slot is followed by decode iterations whatever arrives (nothing
+        // is admissible without a slot): they are applied in the same trip.
+        bool decode_now = !do_prefill;
+        int dA = nA, dArr = nArr, dfree = free_slots;
         if (do_prefill) {
             const int64_t dt = Cp;
             tr.template other<FAST>(1u, (uint32_t)nA, t, P, lane);
@@ -170,7 +174,9 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             Cd = 0;
             npre++;
             head_arr = next < N ? uniform_i64(win_arr[w][next & (2 * kWin - 1)]) : INT64_MAX;
-        } else {
+            if (nR == cap && !invalid) { decode_now = true; dA = 0; dArr = 0; dfree = 0; }
+        }
+        if (decode_now) {
             const int64_t D = nR;
             // decode time of the D tokens of one iteration
             const int64_t bD = FAST ? mul_u32_u32((uint32_t)p.b_decode, (uint32_t)nR) : p.b_decode * D;
@@ -187,12 +193,12 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
             }
-            if (nA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
+            if (dA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
             // the first request that has not arrived yet, if a slot would be free for it
-            const int64_t next_arr = nArr == 0 ? head_arr
-                                   : (nArr < free_slots && next + nArr < N)
-                                         ? uniform_i64(win_arr[w][(next + nArr) & (2 * kWin - 1)]) : INT64_MAX;
-            if (free_slots > 0 && next_arr != INT64_MAX && dt > 0) {
+            const int64_t next_arr = dArr == 0 ? head_arr
+                                   : (dArr < dfree && next + dArr < N)
+                                         ? uniform_i64(win_arr[w][(next + dArr) & (2 * kWin - 1)]) : INT64_MAX;
+            if (dfree > 0 && next_arr != INT64_MAX && dt > 0) {
                 // first boundary at or after the arrival (next_arr > t here, so the dividend is positive)
                 const int64_t j = (int64_t)udiv64((uint64_t)(next_arr - t + dt - 1), (uint64_t)dt);
                 k = min(k, max(j, (int64_t)1));

@@ -303,6 +303,10 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             Cp = (FAST ? mul_u32_i64((uint32_t)p.a_prefill, P) : p.a_prefill * P) + p.c_prefill;
             do_prefill = (nR == 0) || (Cp < Cd) || p.policy != MMBP_POLICY_RULE;
         }
+        // A prefill after which every client is busy is followed by decode iterations (nobody can pick):
+        // they are applied in the same trip.
+        bool decode_now = !do_prefill;
+        int dA = nA;
         if (do_prefill) {
             const int64_t dt = Cp;
             tr.other(1u, (uint32_t)nA, t, P, lane);
@@ -335,7 +339,9 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             busy += FAST ? mul_u32_i64((uint32_t)nA, dt) : (int64_t)nA * dt;
             Cd = 0;
             npre++;
-        } else {
+            if (nR == cap) { decode_now = true; dA = 0; }
+        }
+        if (decode_now) {
             const int64_t D = nR;
             // decode time of the D tokens of one iteration
             const int64_t bD = FAST ? mul_u32_u32((uint32_t)p.b_decode, (uint32_t)nR) : p.b_decode * D;
@@ -351,7 +357,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
             }
-            if (nA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
+            if (dA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
             tr.decode(t, D, (uint32_t)k, lane);
             const int64_t kdt = FAST ? mul_u32_i64((uint32_t)k, dt) : k * dt;
             t += kdt;
