@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
         int dA = nA, dArr = nArr, dfree = free_slots;
         if (do_prefill) {
             const int64_t dt = Cp;
-            tr.template other<FAST>(1u, (uint32_t)nA, t, P, lane);
+            tr.other(1u, (uint32_t)nA, t, P, lane);
             t += dt;
             int base = 0;                      // free slots before this register's block
 #pragma unroll
@@ -170,7 +170,9 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 load_chunk(loaded);
             }
             nR += nA;
-            busy += FAST ? mul_u32_i64((uint32_t)nA, dt) : (int64_t)nA * dt;
+            // (the busy time is only read at the end: it is accumulated on the vector unit, which evens out
+            //  the load of the scalar and the vector unit; the asm keeps the factor in a vector register)
+            { int64_t vdt = dt; asm("" : "+v"(vdt)); busy += (int64_t)nA * vdt; }
             Cd = 0;
             npre++;
             head_arr = next < N ? uniform_i64(win_arr[w][next & (2 * kWin - 1)]) : INT64_MAX;
@@ -193,14 +195,14 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
             }
-            if (dA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
+            if (dA > 0 && bD > 0) k = min(k, uniform_i64((int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD)) + 1);
             // the first request that has not arrived yet, if a slot would be free for it
             const int64_t next_arr = dArr == 0 ? head_arr
                                    : (dArr < dfree && next + dArr < N)
                                          ? uniform_i64(win_arr[w][(next + dArr) & (2 * kWin - 1)]) : INT64_MAX;
             if (dfree > 0 && next_arr != INT64_MAX && dt > 0) {
                 // first boundary at or after the arrival (next_arr > t here, so the dividend is positive)
-                const int64_t j = (int64_t)udiv64((uint64_t)(next_arr - t + dt - 1), (uint64_t)dt);
+                const int64_t j = uniform_i64((int64_t)udiv64((uint64_t)(next_arr - t + dt - 1), (uint64_t)dt));
                 k = min(k, max(j, (int64_t)1));
             }
             tr.decode(t, D, (uint32_t)k, lane);
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             }
             done += nf;
             nR -= nf;
-            busy += FAST ? mul_u32_i64((uint32_t)D, kdt) : D * kdt;
+            { int64_t vk = kdt; asm("" : "+v"(vk)); busy += D * vk; }
             Cd += FAST ? mul_u32_i64((uint32_t)k, bD) : k * bD;
             ndec += (int)k;
         }

@@ -336,7 +336,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             }
             t += dt;
             nR += nA;
-            busy += FAST ? mul_u32_i64((uint32_t)nA, dt) : (int64_t)nA * dt;
+            { int64_t vdt = dt; asm("" : "+v"(vdt)); busy += (int64_t)nA * vdt; }     // (on the vector unit, as in the FCFS simulator)
             Cd = 0;
             npre++;
             if (nR == cap) { decode_now = true; dA = 0; }
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                 for (int q = 0; q < Q; q++) m = min(m, rem[q] > 0 ? (uint32_t)rem[q] : 0xFFFFFFFFu);
                 k = (int64_t)wave_min_u32(m);
             }
-            if (dA > 0 && bD > 0) k = min(k, (int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD) + 1);
+            if (dA > 0 && bD > 0) k = min(k, uniform_i64((int64_t)udiv64((uint64_t)(Cp - Cd), (uint64_t)bD)) + 1);
             tr.decode(t, D, (uint32_t)k, lane);
             const int64_t kdt = FAST ? mul_u32_i64((uint32_t)k, dt) : k * dt;
             t += kdt;
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             }
             done += nf;
             nR -= nf;
-            busy += FAST ? mul_u32_i64((uint32_t)D, kdt) : D * kdt;
+            { int64_t vk = kdt; asm("" : "+v"(vk)); busy += D * vk; }
             Cd += FAST ? mul_u32_i64((uint32_t)k, bD) : k * bD;
             ndec += (int)k;
         }

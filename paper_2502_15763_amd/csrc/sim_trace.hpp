@@ -135,10 +135,6 @@ __device__ __forceinline__ uint32_t put_lane(uint32_t x, uint32_t v)
     return x;
 }
 
-// VCHAIN: the lo chain runs on the vector unit (every lane computes the same chain and lane s keeps
-// the value of step s).  The simulators are bound by scalar issue with vector slots to spare, so one of
-// the two records of a prefill (the closing decode run, then the prefill itself) takes this form.
-template <bool VCHAIN = false>
 __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32_t count, int64_t t_start, int64_t x,
                                                const HashLane &c, int lane)
 {
@@ -150,31 +146,6 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
     constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP2 = (uint32_t)fnv_pow(2), kP3 = (uint32_t)fnv_pow(3),
                        kP6 = (uint32_t)fnv_pow(6), kP24 = (uint32_t)fnv_pow(24);
     const uint32_t tl = (uint32_t)ut, th = (uint32_t)(ut >> 32);
-    if constexpr (VCHAIN) {
-        uint32_t lv = lo;
-        int ln = lane;
-        asm("" : "+v"(lv));                              // from here on the chain lives in a vector register
-        asm volatile("" : "+v"(ln));                     // (the lane tests are made here, not kept as 14 mask pairs across the loop)
-#define MMBP_BYTE_STEP(ST, B) do { const uint32_t v_ = lv ^ (B); vv = ln == (ST) ? v_ : vv; lv = v_ * kP1; } while (0)
-#define MMBP_RUN_STEP(ST, PL) do { vv = ln == (ST) ? lv : vv; lv = lv * (PL); } while (0)
-        MMBP_BYTE_STEP(0, kind);
-        MMBP_RUN_STEP(1, kP3);
-        MMBP_BYTE_STEP(2, count & 0xffu);
-        MMBP_BYTE_STEP(3, count >> 8);
-        MMBP_RUN_STEP(4, kP2);
-        MMBP_BYTE_STEP(5, tl & 0xffu);
-        MMBP_BYTE_STEP(6, (tl >> 8) & 0xffu);
-        MMBP_BYTE_STEP(7, (tl >> 16) & 0xffu);
-        MMBP_BYTE_STEP(8, tl >> 24);
-        MMBP_BYTE_STEP(9, th);
-        MMBP_RUN_STEP(10, kP3);
-        MMBP_BYTE_STEP(11, (uint32_t)ux & 0xffu);
-        MMBP_BYTE_STEP(12, (uint32_t)ux >> 8);
-        MMBP_RUN_STEP(13, kP6);
-#undef MMBP_BYTE_STEP
-#undef MMBP_RUN_STEP
-        lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)lv);
-    } else {
     // v is wave-uniform (a scalar), so lane ST takes it with one lane write: no lane mask, no select
 #define MMBP_BYTE_STEP(ST, B) do { const uint32_t v_ = lo ^ (B); vv = put_lane<ST>(vv, v_); lo = v_ * kP1; } while (0)
 #define MMBP_RUN_STEP(ST, PL) do { vv = put_lane<ST>(vv, lo); lo = lo * (PL); } while (0)
@@ -194,7 +165,6 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
     MMBP_RUN_STEP(13, kP6);
 #undef MMBP_BYTE_STEP
 #undef MMBP_RUN_STEP
-    }
     uint32_t e = (vv * c.ph + __umulhi(vv, c.pl)) * c.w;
     e += dpp_u32<0x111, 0xf>(0u, e);           // sum over the first row of 16 lanes
     e += dpp_u32<0x112, 0xf>(0u, e);
@@ -215,10 +185,9 @@ struct Trace {
     uint32_t run_count;
     int64_t run_t, run_D;
 
-    template <bool VCHAIN = false>
     __device__ __forceinline__ void emit(uint32_t kind, uint32_t count, int64_t t_start, int64_t x, int lane)
     {
-        h = fnv_record<VCHAIN>(h, kind, count, t_start, x, hc, lane);
+        h = fnv_record(h, kind, count, t_start, x, hc, lane);
         if constexpr (TRACED) {
             if (buf && len < cap && lane == 0) {
                 mmbp_trace_rec r;
@@ -239,11 +208,10 @@ struct Trace {
         flush(lane);
         run_open = 1; run_count = k; run_t = t; run_D = D;
     }
-    template <bool VCHAIN = false>
     __device__ __forceinline__ void other(uint32_t kind, uint32_t count, int64_t t, int64_t x, int lane)
     {
         flush(lane);
-        emit<VCHAIN>(kind, count, t, x, lane);
+        emit(kind, count, t, x, lane);
     }
 };
 
