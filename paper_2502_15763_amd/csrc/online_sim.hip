@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             //  the load of the scalar and the vector unit; the asm keeps the factor in a vector register)
             { int64_t vdt = dt; asm("" : "+v"(vdt)); busy += (int64_t)nA * vdt; }
             Cd = 0;
-            npre++;
+            { int one = 1; asm("" : "+v"(one)); npre += one; }
             head_arr = next < N ? uniform_i64(win_arr[w][next & (2 * kWin - 1)]) : INT64_MAX;
             if (nR == cap && !invalid) { decode_now = true; dA = 0; dArr = 0; dfree = 0; }
         }
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
             nR -= nf;
             { int64_t vk = kdt; asm("" : "+v"(vk)); busy += D * vk; }
             Cd += FAST ? mul_u32_i64((uint32_t)k, bD) : k * bD;
-            ndec += (int)k;
+            { int vk2 = (int)k; asm("" : "+v"(vk2)); ndec += vk2; }
         }
     }
     if (invalid) {

@@ -195,7 +195,7 @@ struct Trace {
                 buf[len] = r;
             }
         }
-        len++;
+        { int one = 1; asm("" : "+v"(one)); len += one; }
     }
     __device__ __forceinline__ void flush(int lane)
     {
