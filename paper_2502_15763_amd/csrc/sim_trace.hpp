@@ -94,18 +94,18 @@ __device__ __attribute__((noinline)) uint64_t fnv_record_wide(uint64_t h, uint32
 
 // FNV-1a of one 24-byte trace record (kind u32, count u32, t_start i64, x i64, little endian).
 //
-// A byte step is (hi:lo) <- ((hi:lo) ^ b) * prime.  The xor only touches lo, and a run of z zero
-// bytes is one multiplication by prime^z, so every step has the form
-//     v = lo ^ b;   lo' = v * Pl;   hi' = hi * Pl + v * Ph + mulhi(v, Pl)      (Ph:Pl = prime^z)
+// A byte step is (hi:lo) <- ((hi:lo) ^ b) * prime.  The xor only touches lo, and the z zero bytes
+// that follow a byte only multiply by prime^z more, so a byte together with the zeros after it is one step
+//     v = lo ^ b;   lo' = v * Pl;   hi' = hi * Pl + v * Ph + mulhi(v, Pl)      (Ph:Pl = prime^(1+z))
 // The lo chain is the only sequential part (scalar: xor, multiply).  hi is linear in the v of the
 // steps: hi_end = hi_0 * prod(Pl) + sum_s e_s * W_s,  e_s = v_s * Ph_s + mulhi(v_s, Pl_s),
 // W_s = product of the Pl of the later steps, so lane s takes v_s and one 16-lane sum finishes the
 // record.  Trace fields are small numbers in wide words; for count < 2^16, 0 <= t_start < 2^40 and
-// 0 <= x < 2^16 the record is the fixed sequence of 14 steps below (bytes known to be zero are
-// folded into runs).  Anything else takes the byte-by-byte path.
+// 0 <= x < 2^16 the record is the fixed sequence of 10 steps below (bytes known to be zero are
+// folded into the step of the byte before them).  Anything else takes the byte-by-byte path.
 constexpr uint64_t fnv_pow(int z) { uint64_t r = 1; for (int i = 0; i < z; i++) r *= kFnvPrime; return r; }
-constexpr int kHashSteps = 14;
-constexpr int kStepBytes[kHashSteps] = {1, 3, 1, 1, 2, 1, 1, 1, 1, 1, 3, 1, 1, 6};   // kind, 0*3, count*2, 0*2, t*5, 0*3, x*2, 0*6
+constexpr int kHashSteps = 10;
+constexpr int kStepBytes[kHashSteps] = {4, 1, 3, 1, 1, 1, 1, 4, 1, 7};   // kind + 0*3, count, count + 0*2, t*4, t + 0*3, x, x + 0*6
 constexpr int step_after(int s) { int n = 24; for (int i = 0; i <= s; i++) n -= kStepBytes[i]; return n; }
 
 struct HashLane {          // per-lane constants of the record hash (lane s = step s; zero beyond the steps)
@@ -143,28 +143,22 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
         return fnv_record_wide(h, kind, count, ut, ux);
     uint32_t lo = (uint32_t)h, hi = (uint32_t)(h >> 32);
     uint32_t vv = 0;
-    constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP2 = (uint32_t)fnv_pow(2), kP3 = (uint32_t)fnv_pow(3),
-                       kP6 = (uint32_t)fnv_pow(6), kP24 = (uint32_t)fnv_pow(24);
+    constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP3 = (uint32_t)fnv_pow(3), kP4 = (uint32_t)fnv_pow(4),
+                       kP7 = (uint32_t)fnv_pow(7), kP24 = (uint32_t)fnv_pow(24);
     const uint32_t tl = (uint32_t)ut, th = (uint32_t)(ut >> 32);
     // v is wave-uniform (a scalar), so lane ST takes it with one lane write: no lane mask, no select
-#define MMBP_BYTE_STEP(ST, B) do { const uint32_t v_ = lo ^ (B); vv = put_lane<ST>(vv, v_); lo = v_ * kP1; } while (0)
-#define MMBP_RUN_STEP(ST, PL) do { vv = put_lane<ST>(vv, lo); lo = lo * (PL); } while (0)
-    MMBP_BYTE_STEP(0, kind);
-    MMBP_RUN_STEP(1, kP3);
-    MMBP_BYTE_STEP(2, count & 0xffu);
-    MMBP_BYTE_STEP(3, count >> 8);
-    MMBP_RUN_STEP(4, kP2);
-    MMBP_BYTE_STEP(5, tl & 0xffu);
-    MMBP_BYTE_STEP(6, (tl >> 8) & 0xffu);
-    MMBP_BYTE_STEP(7, (tl >> 16) & 0xffu);
-    MMBP_BYTE_STEP(8, tl >> 24);
-    MMBP_BYTE_STEP(9, th);
-    MMBP_RUN_STEP(10, kP3);
-    MMBP_BYTE_STEP(11, (uint32_t)ux & 0xffu);
-    MMBP_BYTE_STEP(12, (uint32_t)ux >> 8);
-    MMBP_RUN_STEP(13, kP6);
-#undef MMBP_BYTE_STEP
-#undef MMBP_RUN_STEP
+#define MMBP_STEP(ST, B, PL) do { const uint32_t v_ = lo ^ (B); vv = put_lane<ST>(vv, v_); lo = v_ * (PL); } while (0)
+    MMBP_STEP(0, kind, kP4);
+    MMBP_STEP(1, count & 0xffu, kP1);
+    MMBP_STEP(2, count >> 8, kP3);
+    MMBP_STEP(3, tl & 0xffu, kP1);
+    MMBP_STEP(4, (tl >> 8) & 0xffu, kP1);
+    MMBP_STEP(5, (tl >> 16) & 0xffu, kP1);
+    MMBP_STEP(6, tl >> 24, kP1);
+    MMBP_STEP(7, th, kP4);
+    MMBP_STEP(8, (uint32_t)ux & 0xffu, kP1);
+    MMBP_STEP(9, (uint32_t)ux >> 8, kP7);
+#undef MMBP_STEP
     uint32_t e = (vv * c.ph + __umulhi(vv, c.pl)) * c.w;
     e += dpp_u32<0x111, 0xf>(0u, e);           // sum over the first row of 16 lanes
     e += dpp_u32<0x112, 0xf>(0u, e);
@@ -195,6 +189,7 @@ struct Trace {
                 buf[len] = r;
             }
         }
+        // (counted in a vector register: nothing in the untraced loop reads it back, so it takes no scalar slot)
         { int one = 1; asm("" : "+v"(one)); len += one; }
     }
     __device__ __forceinline__ void flush(int lane)
