@@ -97,10 +97,13 @@ __device__ __attribute__((noinline)) uint64_t fnv_record_wide(uint64_t h, uint32
 // A byte step is (hi:lo) <- ((hi:lo) ^ b) * prime.  The xor only touches lo, and the z zero bytes
 // that follow a byte only multiply by prime^z more, so a byte together with the zeros after it is one step
 //     v = lo ^ b;   lo' = v * Pl;   hi' = hi * Pl + v * Ph + mulhi(v, Pl)      (Ph:Pl = prime^(1+z))
-// The lo chain is the only sequential part (scalar: xor, multiply).  hi is linear in the v of the
-// steps: hi_end = hi_0 * prod(Pl) + sum_s e_s * W_s,  e_s = v_s * Ph_s + mulhi(v_s, Pl_s),
-// W_s = product of the Pl of the later steps, so lane s takes v_s and one 16-lane sum finishes the
-// record.  Trace fields are small numbers in wide words; for count < 2^16, 0 <= t_start < 2^40 and
+// The lo chain is the only sequential part (xor, multiply).  hi is linear in the v of the steps:
+// hi_end = hi_0 * prod(Pl) + sum_s e_s * W_s,  e_s = v_s * Ph_s + mulhi(v_s, Pl_s), W_s = product of the
+// Pl of the later steps.  Every lane runs the lo chain on the vector unit (measured: with the chain on the
+// scalar unit, whole or one record of two, the simulators are 4 to 7 % slower, the scalar unit being the
+// busier one in their loops); the four lanes of group s keep v_s (one DPP move under a row and bank mask
+// per step), one lane of the group holds the step's constants, and one wave sum finishes the record.
+// Trace fields are small numbers in wide words; for count < 2^16, 0 <= t_start < 2^40 and
 // 0 <= x < 2^16 the record is the fixed sequence of 10 steps below (bytes known to be zero are
 // folded into the step of the byte before them).  Anything else takes the byte-by-byte path.
 constexpr uint64_t fnv_pow(int z) { uint64_t r = 1; for (int i = 0; i < z; i++) r *= kFnvPrime; return r; }
@@ -108,7 +111,7 @@ constexpr int kHashSteps = 10;
 constexpr int kStepBytes[kHashSteps] = {4, 1, 3, 1, 1, 1, 1, 4, 1, 7};   // kind + 0*3, count, count + 0*2, t*4, t + 0*3, x, x + 0*6
 constexpr int step_after(int s) { int n = 24; for (int i = 0; i <= s; i++) n -= kStepBytes[i]; return n; }
 
-struct HashLane {          // per-lane constants of the record hash (lane s = step s; zero beyond the steps)
+struct HashLane {          // per-lane constants of the record hash (lane 16 (s / 4) + 4 (s % 4) + 3 = step s; zero elsewhere)
     uint32_t pl, ph, w;
 };
 
@@ -118,7 +121,7 @@ __device__ __forceinline__ HashLane hash_lane_init(int lane)
     c.pl = 0; c.ph = 0; c.w = 0;
 #pragma unroll
     for (int st = 0; st < kHashSteps; st++)
-        if (lane == st) {
+        if (lane == 16 * (st / 4) + 4 * (st % 4) + 3) {
             c.pl = (uint32_t)fnv_pow(kStepBytes[st]);
             c.ph = (uint32_t)(fnv_pow(kStepBytes[st]) >> 32);
             c.w = (uint32_t)fnv_pow(step_after(st));
@@ -126,13 +129,11 @@ __device__ __forceinline__ HashLane hash_lane_init(int lane)
     return c;
 }
 
-// Writes the wave-uniform value v into lane LANE of x (v_writelane_b32: scalar source, constant lane).
-template <int LANE>
-__device__ __forceinline__ uint32_t put_lane(uint32_t x, uint32_t v)
+// Keeps v in the four lanes of group G (row G / 4, bank G % 4) of x: one DPP move under a row and bank mask.
+template <int G>
+__device__ __forceinline__ uint32_t keep_in_group(uint32_t x, uint32_t v)
 {
-    const uint32_t sv = (uint32_t)__builtin_amdgcn_readfirstlane((int)v);     // (already uniform: pins it to a scalar register)
-    asm("v_writelane_b32 %0, %1, %2" : "+v"(x) : "s"(sv), "n"(LANE));
-    return x;
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)v, 0xE4, 1 << (G / 4), 1 << (G % 4), false);
 }
 
 __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32_t count, int64_t t_start, int64_t x,
@@ -142,12 +143,12 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
     if (__builtin_expect(((uint64_t)(count >> 16) | (ut >> 40) | (ux >> 16) | (uint64_t)(kind >> 8)) != 0, 0))
         return fnv_record_wide(h, kind, count, ut, ux);
     uint32_t lo = (uint32_t)h, hi = (uint32_t)(h >> 32);
+    asm("" : "+v"(lo));            // the chain stays in vector registers
     uint32_t vv = 0;
     constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP3 = (uint32_t)fnv_pow(3), kP4 = (uint32_t)fnv_pow(4),
                        kP7 = (uint32_t)fnv_pow(7), kP24 = (uint32_t)fnv_pow(24);
     const uint32_t tl = (uint32_t)ut, th = (uint32_t)(ut >> 32);
-    // v is wave-uniform (a scalar), so lane ST takes it with one lane write: no lane mask, no select
-#define MMBP_STEP(ST, B, PL) do { const uint32_t v_ = lo ^ (B); vv = put_lane<ST>(vv, v_); lo = v_ * (PL); } while (0)
+#define MMBP_STEP(ST, B, PL) do { const uint32_t v_ = lo ^ (B); vv = keep_in_group<ST>(vv, v_); lo = v_ * (PL); } while (0)
     MMBP_STEP(0, kind, kP4);
     MMBP_STEP(1, count & 0xffu, kP1);
     MMBP_STEP(2, count >> 8, kP3);
@@ -160,11 +161,11 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
     MMBP_STEP(9, (uint32_t)ux >> 8, kP7);
 #undef MMBP_STEP
     uint32_t e = (vv * c.ph + __umulhi(vv, c.pl)) * c.w;
-    e += dpp_u32<0x111, 0xf>(0u, e);           // sum over the first row of 16 lanes
-    e += dpp_u32<0x112, 0xf>(0u, e);
-    e += dpp_u32<0x114, 0xf>(0u, e);
-    e += dpp_u32<0x118, 0xf>(0u, e);
-    hi = hi * kP24 + (uint32_t)__builtin_amdgcn_readlane((int)e, 15);
+    e += dpp_u32<0x114, 0xf>(0u, e);           // lanes 3, 7, 11, 15 of a row hold its terms: row_shr 4 and 8 sum them
+    e += dpp_u32<0x118, 0xf>(0u, e);           // into lane 15, the two row broadcasts carry the rows into lane 63
+    e += dpp_u32<0x142, 0xa>(0u, e);
+    e += dpp_u32<0x143, 0xc>(0u, e);
+    hi = hi * kP24 + (uint32_t)__builtin_amdgcn_readlane((int)e, 63);
     return ((uint64_t)hi << 32) | lo;
 }
 
