@@ -94,7 +94,12 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
         const int free_slots = cap - nR;
         int nA = 0, nArr = 0;                  // admissible requests; arrived requests among the free_slots next ones
         int64_t P = 0;
-        if (free_slots > 0 && head_arr <= t) {
+        if (free_slots == 1 && head_arr <= t) {
+            // one free slot (the usual case under load): the head request, which has arrived, is the admissible set
+            nA = 1;
+            nArr = 1;
+            P = uniform_i64((int64_t)win_in[w][next & (2 * kWin - 1)]);
+        } else if (free_slots > 0 && head_arr <= t) {
             // admissible set A: FCFS prefix of the arrived requests that fits the free slots and the
             // token capacity (an oversized head request is still admitted alone)
             int64_t tok[Q];
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(kBlock) void online_sim_kernel(
                 nA += __popcll(__ballot(arrived[q]));
             }
             nArr = nA;
-            if (maxtok > 0) {
+            if (maxtok > 0 && nArr > 1) {        // (one arrived request is admitted whatever its length)
                 int n2 = 0;
                 int64_t carry = 0;
 #pragma unroll
