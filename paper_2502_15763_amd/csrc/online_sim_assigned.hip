@@ -259,6 +259,7 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
         int idx[Q];
         int64_t tok[Q], len[Q];
         uint32_t first = 0xFFFFFFFFu;          // the first client that picks
+        int npick = 0;
 #pragma unroll
         for (int q = Q - 1; q >= 0; q--) {
             pick[q] = pick_pos[q] >= 0;
@@ -267,10 +268,17 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
             len[q] = pick[q] ? (int64_t)qlen[pick_pos[q]] : 0;
             const unsigned long long pm = __ballot(pick[q]);
             if (pm) first = (uint32_t)(q * kWave + __builtin_ctzll(pm));
+            npick += __popcll(pm);
         }
         int nA = 0;
         int64_t P = 0;
-        if (first != 0xFFFFFFFFu) {
+        if (npick == 1) {                      // one pick (the usual case under load): it is the prefill
+            int tok32[Q];
+#pragma unroll
+            for (int q = 0; q < Q; q++) tok32[q] = (int)tok[q];
+            nA = 1;
+            P = (int64_t)lane_value<Q>(tok32, (int)(first >> 6), (int)(first & 63u));
+        } else if (first != 0xFFFFFFFFu) {
             if (p.policy == MMBP_POLICY_PREFILL_FIRST_SINGLE) {
 #pragma unroll
                 for (int q = 0; q < Q; q++) pick[q] = pick[q] && (uint32_t)(q * kWave + lane) == first;
