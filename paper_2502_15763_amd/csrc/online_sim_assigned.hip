@@ -154,6 +154,11 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
     }
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
+    // While every client's remain_token is below 2^24, (remain_token, lowest client) is one 32-bit key and a
+    // steal needs one wave reduction instead of three (remain_token only goes down).
+    bool small_keys = true;
+#pragma unroll
+    for (int q = 0; q < Q; q++) small_keys = small_keys && !__any(remain[q] >= (1ll << 24));
     const bool wide_in = __any(wide);          // some N^p_i does not fit 16 bits: picks read in_len from memory
     if (!wide_in)
         for (int pos = lane; pos < N; pos += kWave) qin[pos] = (uint16_t)in_len[order[pos]];
@@ -216,7 +221,18 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                         m &= m - 1;
                         int src = -1;
                         if (__builtin_amdgcn_readlane(th[jq], jl) < __builtin_amdgcn_readlane(qend[jq], jl)) src = jq * kWave + jl;
-                        else {
+                        else if (small_keys) {
+                            uint32_t key = 0;                             // (remain_token, 255 - client): the maximum is the steal's source
+#pragma unroll
+                            for (int q = 0; q < Q; q++)
+                                key = max(key, ((uint32_t)trm[q] << 8) | (uint32_t)(255 - (q * kWave + lane)));
+                            const uint32_t mx = wave_max_u32(key);
+                            if (mx >> 8) src = 255 - (int)(mx & 255u);
+                            else {
+                                closed = true;           // every queue is empty by now (lengths are positive), also for
+                                m = 0;                   // the clients still to come: nobody else picks anything
+                            }
+                        } else {
                             int64_t bm = trm[0];                          // the largest remain_token, lowest client among equals
 #pragma unroll
                             for (int q = 1; q < Q; q++) bm = max(bm, trm[q]);
@@ -229,8 +245,8 @@ __global__ __launch_bounds__(kWave) void online_sim_assigned_kernel(
                                 for (int q = Q - 1; q >= 0; q--) c = trm[q] == mx ? (uint32_t)(q * kWave + lane) : c;
                                 src = (int)wave_min_u32(c);
                             } else {
-                                closed = true;           // every queue is empty by now (lengths are positive), also for
-                                m = 0;                   // the clients still to come: nobody else picks anything
+                                closed = true;
+                                m = 0;
                             }
                         }
                         if (src < 0) continue;

@@ -820,6 +820,25 @@ def test_sim_assigned_maximum_size(oracle, cap):
     compare_sim(g, o, label=f"assigned maximum size cap={cap}")
 
 
+@pytest.mark.parametrize("cap,N", [(6, 48), (70, 210)])
+def test_sim_assigned_large_remain_token(oracle, cap, N):
+    """Queues whose remain_token exceeds 24 bits: a steal then compares the 64-bit sums themselves (the
+    kernel packs sum and client into one 32-bit key only while every sum is small), and the decode runs are
+    longer than 16 bits of count, so their records take the byte-by-byte hash."""
+    S = 3
+    rng = np.random.default_rng(1234 + cap)
+    in_len = rng.integers(1, 3000, size=(S, N)).astype(np.int32)
+    out_len = rng.integers(1 << 20, 1 << 22, size=(S, N)).astype(np.int32)
+    out_len[2, ::2] = rng.integers(1, 50, size=len(out_len[2, ::2]))       # a scenario that mixes short and long
+    assign = rng.integers(0, max(cap // 3, 1), size=(S, N)).astype(np.int32)    # most clients start idle: stealing
+    assign[1] = rng.integers(0, cap, size=N)
+    p = dict(cap=cap, a_prefill=130, b_decode=210, c_prefill=25000, c_decode=29000, max_prefill_tokens=4096, policy=0)
+    say(f"sim assigned large remain_token cap={cap} N={N}")
+    o = oracle.online_iter_sim_assigned(in_len, out_len, assign, p, S, 6 * N + 8)
+    g = gpu_online_sim_assigned(in_len, out_len, assign, p, S, 6 * N + 8)
+    compare_sim(g, o, label=f"assigned large remain_token cap={cap}")
+
+
 @pytest.mark.parametrize("b_decode", [0, 1, 7])
 def test_sim_prefill_waits_many_iterations(oracle, b_decode):
     """A small decode slope against a large prefill constant: C_d needs hundreds of decode iterations
