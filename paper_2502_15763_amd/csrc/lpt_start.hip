@@ -117,6 +117,9 @@ __global__ __launch_bounds__(kBlock) void lpt_start_kernel(const CostT *__restri
     int cn[kClientsPerLane];
 #pragma unroll
     for (int r = 0; r < kClientsPerLane; r++) { ld[r] = 0; cn[r] = 0; }
+    // While no load can reach 2^24 (the largest load so far plus the largest cost stays below it), (load, client)
+    // is one 32-bit key and a placement needs one wave reduction instead of three.
+    unsigned long long top = 0;                          // the largest load so far
     for (int q0 = 0; q0 < N; q0 += kWave) {
         const int nb = min(kWave, N - q0);
         // this batch's requests, one per lane
@@ -131,6 +134,23 @@ __global__ __launch_bounds__(kBlock) void lpt_start_kernel(const CostT *__restri
             const uint32_t clo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)bc, k);
             const uint32_t chi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(bc >> 32), k);
             const unsigned long long ci = ((unsigned long long)chi << 32) | clo;
+            if (top + cmax < (1ull << 24)) {                 // (clients are below 256: MMBP_MAX_M)
+                uint32_t bk = 0xFFFFFFFFu;               // smallest (load, client) among this lane's clients with room
+#pragma unroll
+                for (int r = 0; r < kClientsPerLane; r++) {
+                    const int j = lane + r * kWave;
+                    if (j < M && cn[r] < cap) bk = min(bk, ((uint32_t)ld[r] << 8) | (uint32_t)j);
+                }
+                const uint32_t wk = wave_min_u32(bk);
+                if (wk == 0xFFFFFFFFu) continue;         // cannot happen: N <= M * cap leaves room somewhere
+                const uint32_t wj = wk & 255u;
+#pragma unroll
+                for (int r = 0; r < kClientsPerLane; r++)
+                    if ((uint32_t)(lane + r * kWave) == wj) { ld[r] += ci; cn[r] += 1; }
+                top = max(top, (unsigned long long)(wk >> 8) + ci);
+                if (lane == 0 && i >= 0 && i < N) asg[i] = (int32_t)wj;
+                continue;
+            }
             // this lane's best client: smallest (load, client) among its clients with room
             unsigned long long bl = ~0ull;
             uint32_t bj = 0xFFFFFFFFu;
@@ -148,6 +168,7 @@ __global__ __launch_bounds__(kBlock) void lpt_start_kernel(const CostT *__restri
 #pragma unroll
             for (int r = 0; r < kClientsPerLane; r++)
                 if ((uint32_t)(lane + r * kWave) == wj) { ld[r] += ci; cn[r] += 1; }
+            top = max(top, (((unsigned long long)mh << 32) | ml) + ci);
             if (lane == 0 && i >= 0 && i < N) asg[i] = (int32_t)wj;
         }
     }
