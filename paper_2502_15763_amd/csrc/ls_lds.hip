@@ -277,6 +277,9 @@ __device__ void sort_groups(const Lds &l, int P, int M)
         }
 }
 
+constexpr int kPruneRows = 2;              // row segments per lane in that tile
+constexpr int kPruneTileCols = 40;         // the pruned scan takes the tile arithmetic, not the binary search, up to this many columns
+
 // min over the n sorted entries cu[sb .. sb+n) of |cu - x|: the nearest at or above x, the nearest below
 __device__ __forceinline__ uint32_t nearest_sorted(const uint32_t *cu, int sb, int n, uint32_t x)
 {
@@ -549,7 +552,50 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
             const int sb = min(max(uni(l.gstart[astar]), 0), P), sn = min(max(uni(l.cnt[astar]), 0), P - sb);
             const int s1 = min(max(uni(l.gstart[astar + 1]), 0), P);
             const uint32_t lstar = wload(astar);
-            if (sn > 0)
+            if (sn > 0 && sn <= kPruneTileCols) {
+                // Few columns: the tile arithmetic against all of them (two vector instructions per candidate, the
+                // columns read as broadcasts that do not depend on the rows) is shorter than a binary search per
+                // row, which is a chain of dependent LDS reads; two row segments per lane share the column reads
+                // (four would spill under the pruned kernels' register limit).
+                const int n4 = (sn + 3) >> 2;                  // (the positions after the last column are empty ones: no candidates)
+                for (int base = wave; base < nseg; base += kPruneRows * kWaves) {
+                    uint32_t x[kPruneRows], cx[kPruneRows], lsum[kPruneRows], oth[kPruneRows], key[kPruneRows];
+#pragma unroll
+                    for (int q = 0; q < kPruneRows; q++) {
+                        const int seg = base + q * kWaves;
+                        const bool on = seg < nseg && (seg < sega || seg >= segb);
+                        const int g = on ? min((int)l.seg_grp[seg], M - 1) : 0;
+                        const uint32_t lg = load32(g);
+                        cx[q] = on ? l.cu[seg * 64 + lane] : kPad;
+                        x[q] = cx[q] - (lg - lstar);
+                        lsum[q] = lg + lstar;
+                        oth[q] = others_max(top, g, astar);
+                    }
+                    {
+                        RowAcc acc[kPruneRows];
+#pragma unroll
+                        for (int q = 0; q < kPruneRows; q++) { acc[q].up = kInf; acc[q].mx = 0u; }
+                        const uint4 *col = reinterpret_cast<const uint4 *>(l.cu + sb);
+                        for (int k = 0; k < n4; k++) {
+                            const uint4 c4 = col[k];
+#pragma unroll
+                            for (int q = 0; q < kPruneRows; q++) nearest_x4(acc[q], x[q], c4);
+                        }
+#pragma unroll
+                        for (int q = 0; q < kPruneRows; q++) key[q] = nearest_key(acc[q]);
+                    }
+#pragma unroll
+                    for (int q = 0; q < kPruneRows; q++) {
+                        const int pp = (base + q * kWaves) * 64 + lane;
+                        const uint32_t v = cx[q] != kPad ? swap_value(key[q], lsum[q], oth[q]) : kInf;
+                        sbest = min(sbest, v);
+                        if (v != kInf) {
+                            l.rowkey[pp] = v;
+                            kbest = min(kbest, ((unsigned long long)v << 32) | ((unsigned long long)l.job[pp] << 16) | (unsigned long long)pp);
+                        }
+                    }
+                }
+            } else if (sn > 0)
                 for (int p = tid; p < P; p += BLOCK) {
                     if (p >= sb && p < s1) continue;
                     const uint32_t cx = l.cu[p];
