@@ -368,10 +368,14 @@ def main():
             hin, hout = il[:Sh].contiguous(), ol[:Sh].contiguous()
             hcost = torch.from_numpy(W.job_cost(w.in_len[:Sh], w.out_len[:Sh], np.int32)).cuda()
             rr = torch.from_numpy(np.tile((np.arange(w.N) % cap).astype(np.int32), (Sh, 1))).cuda()
-            t0 = time.perf_counter()
-            hls = api.run_local_search(hcost, rr, cap, w.N, 1024, pruned=True)
-            torch.cuda.synchronize()
-            ls_dt = time.perf_counter() - t0
+            def second_call(f):                           # the first call loads the kernel and allocates: the second is timed
+                f()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                r = f()
+                torch.cuda.synchronize()
+                return r, time.perf_counter() - t0
+            hls, ls_dt = second_call(lambda: api.run_local_search(hcost, rr, cap, w.N, 1024, pruned=True))
             ha = api.run_online_sim_assigned(hin, hout, hls["assign"], w.params)      # warm-up, allocates outputs
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -403,19 +407,16 @@ def main():
         pcost = torch.from_numpy(W.job_cost(pin, pout, np.int32)).cuda()
         zero_arr = torch.zeros((Sp, Np), dtype=torch.int64, device=dev)
         pp = dict(W.PAPER_PARAMS)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        lpt = api.run_lpt_start(pcost, Mp, capp)
-        torch.cuda.synchronize()
-        lpt_dt = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        pls = api.run_local_search(pcost, lpt["assign"], Mp, capp, 1024, pruned=True)
-        torch.cuda.synchronize()
-        pls_dt = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        pa = api.run_online_sim_assigned(din, dout, pls["assign"], pp)
-        torch.cuda.synchronize()
-        pa_dt = time.perf_counter() - t0
+        def second_call(f):                               # the first call loads the kernel and allocates: the second is timed
+            f()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            r = f()
+            torch.cuda.synchronize()
+            return r, time.perf_counter() - t0
+        lpt, lpt_dt = second_call(lambda: api.run_lpt_start(pcost, Mp, capp))
+        pls, pls_dt = second_call(lambda: api.run_local_search(pcost, lpt["assign"], Mp, capp, 1024, pruned=True))
+        pa, pa_dt = second_call(lambda: api.run_online_sim_assigned(din, dout, pls["assign"], pp))
         pb = api.run_online_sim(zero_arr, din, dout, dict(pp, policy=api.POLICY_PREFILL_FIRST_SINGLE))
         pr_ = api.run_online_sim(zero_arr, din, dout, pp)
         plb = api.run_lower_bound_ex(pcost, Mp, cap=[capp] * Mp)
