@@ -734,6 +734,64 @@ def test_hybrid_pipeline_offline_search_then_assigned_sim(oracle):
     compare_sim(g, o, label="hybrid")
 
 
+_HYB = {}
+
+
+def _hybrid_on_gpu():
+    """The hybrid leg as the benchmark runs it, computed once: 2048 scenarios x 2048 requests on 64 clients, pruned
+    search from round-robin (limit 1024 passes) in ONE call, then the assigned simulator on its result."""
+    if not _HYB:
+        w = W.config5()
+        S, N, cap = 2048, w.N, w.params["cap"]
+        in_len, out_len = w.in_len[:S], w.out_len[:S]
+        cost = W.job_cost(in_len, out_len, np.int32)
+        assign0 = np.tile((np.arange(N) % cap).astype(np.int32), (S, 1))
+        say("hybrid at the benchmark size: pruned search and assigned simulator on GPU")
+        g = gpu_local_search(cost, assign0, cap, N, 1024, pruned=True)
+        p = dict(w.params, cap=cap)
+        _HYB.update(in_len=in_len, out_len=out_len, cost=cost, assign0=assign0, cap=cap, N=N, p=p, g=g,
+                    sim=gpu_online_sim_assigned(in_len, out_len, g["assign"], p))
+    return _HYB
+
+
+@pytest.mark.parametrize("part", range(4))
+def test_hybrid_pipeline_at_the_benchmark_size(oracle, part):
+    """Every output of both steps against the oracle (scenarios are independent: four slices of 512)."""
+    h = _hybrid_on_gpu()
+    sl = slice(512 * part, 512 * (part + 1))
+    say(f"hybrid at the benchmark size: oracle on scenarios {sl.start}..{sl.stop - 1}")
+    o = oracle.local_search(h["cost"][sl], h["assign0"][sl], h["cap"], h["N"], 1024, want_log=True)
+    compare_ls({k: (v[sl] if isinstance(v, np.ndarray) else v) for k, v in h["g"].items()}, o, label=f"hybrid pruned search, slice {part}")
+    osim = oracle.online_iter_sim_assigned(h["in_len"][sl], h["out_len"][sl], o["assign"], h["p"], 0, 0)
+    compare_sim({k: (v[sl] if isinstance(v, np.ndarray) else v) for k, v in h["sim"].items()}, osim, label=f"hybrid assigned simulator, slice {part}")
+
+
+def test_paper_shaped_pipeline_at_the_benchmark_size(oracle):
+    """The paper-shaped leg as the benchmark runs it: 1024 scenarios x 1319 requests on 200 clients of at most 7,
+    LPT start, pruned search, assigned simulator, and the FCFS simulator under the rule and the baseline."""
+    in_len, out_len = W.paper_shaped(S=1024)
+    S, N = in_len.shape
+    p = dict(W.PAPER_PARAMS)
+    M = p["cap"]
+    cap = -(-N // M)
+    cost = W.job_cost(in_len, out_len, np.int32)
+    say("paper-shaped at the benchmark size: LPT start")
+    lg, lo = gpu_lpt_start(cost, M, cap), oracle.lpt_start(cost, M, cap)
+    _same_lpt(lg, lo, "paper-shaped LPT, benchmark size")
+    say("paper-shaped at the benchmark size: pruned search")
+    g = gpu_local_search(cost, lg["assign"], M, cap, 1024, pruned=True)
+    o = oracle.local_search(cost, lo["assign"].astype(np.int32), M, cap, 1024, want_log=True)
+    compare_ls(g, o, label="paper-shaped pruned search, benchmark size")
+    say("paper-shaped at the benchmark size: simulators")
+    compare_sim(gpu_online_sim_assigned(in_len, out_len, g["assign"], p), oracle.online_iter_sim_assigned(in_len, out_len, o["assign"], p, 0, 0),
+                label="paper-shaped assigned simulator, benchmark size")
+    arr = np.zeros((S, N), np.int64)
+    for pol in (0, 2):
+        pp = dict(p, policy=pol)
+        compare_sim(gpu_online_sim(arr, in_len, out_len, pp), oracle.online_iter_sim(arr, in_len, out_len, pp, 0, 0),
+                    label=f"paper-shaped FCFS policy {pol}, benchmark size")
+
+
 # ------------------------------------------------------------------ more clients than one wave has lanes
 @pytest.mark.parametrize("policy", [0, 1, 2])
 def test_sim_many_clients(oracle, policy):
