@@ -37,15 +37,19 @@
 // job) of those.  Wave 0 then knows the best value V and k0 = the lowest-index non-critical job of a
 // best swap; only critical jobs with a lower index than k0 ("early") can carry a lower id: they are
 // taken in index order, four at a time, against the flagged jobs (rowkey == V); k0's own partners
-// are scanned; the packed minimum (i, k, pos_i, pos_k) is applied.  Moves are value-only in phase A
-// and rescanned for the id when a move wins.
+// are scanned; the packed minimum (i, k, pos_i, pos_k) is applied.  In the full scan moves are
+// value-only in phase A and rescanned for the id when a move wins.
 //
 // Pruned scan (PRUNE): only the candidates that involve the critical client are looked at (the others
 // cannot lower max_j t_j).  The positions of every client are then kept in ascending order of cu
-// (a bitonic network after each regrouping; a swap removes one entry and inserts the other in place),
+// (sorted after each regrouping: one wave per 64-slot segment where no client has more, a bitonic
+// network over the layout otherwise; a swap or a move removes one entry and inserts the other in place),
 // and a row's best partner in the critical client is found by binary search: the nearest column at or
 // above x and the nearest below it, i.e. the same key min |y - x| the tile computes, in O(log n)
-// per row instead of one subtraction per column.  Selection, tie-break and apply are shared.
+// per row instead of one subtraction per column; where that client holds at most kPruneTileCols jobs
+// the rows run the tile arithmetic against all of them instead (no chain of dependent LDS reads).
+// The moves off the critical client are evaluated with their ids by all waves (a slice of the target
+// clients each), so a winning move needs no second look.  Selection, tie-break and apply are shared.
 //
 // Exactness: all loads stay at or below the initial makespan T0; with T0 + 2*max T_i < 2^29 every
 // quantity above is exact in 32 bits: x lies in (2^29, 3*2^29), a real |y - x| is below 2^29, a

@@ -19,7 +19,7 @@ constexpr int kBlock = 256;
 // clients), so slot c lives in lane c % 64, register c / 64.
 // FAST = the host saw that no trace records are wanted and that a_prefill and b_decode fit 31 bits: the
 // trace-store code is absent and the products of the time model take 32 x 64-bit multiplies.  The kernel
-// is bound by scalar instruction issue, so both count.
+// is bound by instruction issue, the scalar and the vector unit about equally loaded, so both count.
 template <int Q, bool FAST>
 __global__ __launch_bounds__(kBlock) void online_sim_kernel(
     const int64_t *__restrict__ arrival_all, const int32_t *__restrict__ in_all, const int32_t *__restrict__ out_all,
