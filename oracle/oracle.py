@@ -4,7 +4,6 @@ can compute reference results on the CPU."""
 from __future__ import annotations
 
 import ctypes as C
-import os
 import numpy as np
 
 from . import build as _build

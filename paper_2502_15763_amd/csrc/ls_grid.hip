@@ -241,7 +241,7 @@ __device__ void g_finish(const GWs &w, const OutPtrs &o, int s, int M)
 
 // Opens a pass: accounting, top-3, reset of the row minima, task table.  Returns false (after
 // writing the outputs) when the scenario stops here.
-__device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int N, int M, int max_passes, bool last_launch,
+__device__ bool g_prep_pass(const GWs &w, const OutPtrs &o, int s, int M, int max_passes, bool last_launch,
                             bool toggle, int *s_ntask)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_stage_kernel(const CostT *__re
         uint4 *rk4 = (uint4 *)(w.rowkey < w.rowkey_other ? w.rowkey : w.rowkey_other);   // both buffers
         for (int q = tid; q < (w.pstride >> 1); q += kSelBlock) rk4[q] = make_uint4(kInf, kInf, kInf, kInf);
     }
-    g_prep_pass(w, o, s, N, M, max_passes, false, false, &s_ntask);
+    g_prep_pass(w, o, s, M, max_passes, false, false, &s_ntask);
 }
 
 // ---- kernel 1: evaluation of all candidates of a pass ----
@@ -997,7 +997,7 @@ __global__ __launch_bounds__(kSelBlock) void grid_select_kernel(const CostT *__r
         }
     }
     __syncthreads();
-    g_prep_pass(w, o, s, N, M, max_passes, last_launch != 0, true, &s_ntask);
+    g_prep_pass(w, o, s, M, max_passes, last_launch != 0, true, &s_ntask);
 }
 
 }  // namespace

@@ -137,7 +137,7 @@ __device__ __forceinline__ uint32_t keep_in_group(uint32_t x, uint32_t v)
 }
 
 __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32_t count, int64_t t_start, int64_t x,
-                                               const HashLane &c, int lane)
+                                               const HashLane &c)
 {
     const uint64_t ut = (uint64_t)t_start, ux = (uint64_t)x;
     if (__builtin_expect(((uint64_t)(count >> 16) | (ut >> 40) | (ux >> 16) | (uint64_t)(kind >> 8)) != 0, 0))
@@ -182,7 +182,7 @@ struct Trace {
 
     __device__ __forceinline__ void emit(uint32_t kind, uint32_t count, int64_t t_start, int64_t x, int lane)
     {
-        h = fnv_record(h, kind, count, t_start, x, hc, lane);
+        h = fnv_record(h, kind, count, t_start, x, hc);
         if constexpr (TRACED) {
             if (buf && len < cap && lane == 0) {
                 mmbp_trace_rec r;
