@@ -112,19 +112,20 @@ constexpr int kStepBytes[kHashSteps] = {4, 1, 3, 1, 1, 1, 1, 4, 1, 7};   // kind
 constexpr int step_after(int s) { int n = 24; for (int i = 0; i <= s; i++) n -= kStepBytes[i]; return n; }
 
 struct HashLane {          // per-lane constants of the record hash (lane 16 (s / 4) + 4 (s % 4) + 3 = step s; zero elsewhere)
-    uint32_t pl, ph, w;
+    uint32_t pl, ph, w, w24;   // w24 = w * prime^24: the weight of a step when one more record follows in the same sum
 };
 
 __device__ __forceinline__ HashLane hash_lane_init(int lane)
 {
     HashLane c;
-    c.pl = 0; c.ph = 0; c.w = 0;
+    c.pl = 0; c.ph = 0; c.w = 0; c.w24 = 0;
 #pragma unroll
     for (int st = 0; st < kHashSteps; st++)
         if (lane == 16 * (st / 4) + 4 * (st % 4) + 3) {
             c.pl = (uint32_t)fnv_pow(kStepBytes[st]);
             c.ph = (uint32_t)(fnv_pow(kStepBytes[st]) >> 32);
             c.w = (uint32_t)fnv_pow(step_after(st));
+            c.w24 = (uint32_t)fnv_pow(step_after(st) + 24);
         }
     return c;
 }
@@ -169,6 +170,47 @@ __device__ __forceinline__ uint64_t fnv_record(uint64_t h, uint32_t kind, uint32
     return ((uint64_t)hi << 32) | lo;
 }
 
+// Two records in a row (a decode run and the prefill after it, the usual pair): the lo chain runs through both,
+// and their hi terms meet in one wave sum.
+__device__ __forceinline__ uint64_t fnv_record_pair(uint64_t h, uint32_t kind1, uint32_t count1, int64_t t1, int64_t x1,
+                                                    uint32_t kind2, uint32_t count2, int64_t t2, int64_t x2, const HashLane &c)
+{
+    const uint64_t ut1 = (uint64_t)t1, ux1 = (uint64_t)x1, ut2 = (uint64_t)t2, ux2 = (uint64_t)x2;
+    if (__builtin_expect(((uint64_t)(count1 >> 16) | (ut1 >> 40) | (ux1 >> 16) | (uint64_t)(kind1 >> 8) |
+                          (uint64_t)(count2 >> 16) | (ut2 >> 40) | (ux2 >> 16) | (uint64_t)(kind2 >> 8)) != 0, 0))
+        return fnv_record(fnv_record(h, kind1, count1, t1, x1, c), kind2, count2, t2, x2, c);
+    uint32_t lo = (uint32_t)h, hi = (uint32_t)(h >> 32);
+    asm("" : "+v"(lo));
+    uint32_t va = 0, vb = 0;
+    constexpr uint32_t kP1 = (uint32_t)fnv_pow(1), kP3 = (uint32_t)fnv_pow(3), kP4 = (uint32_t)fnv_pow(4),
+                       kP7 = (uint32_t)fnv_pow(7), kP48 = (uint32_t)fnv_pow(48);
+#define MMBP_STEP(VV, ST, B, PL) do { const uint32_t v_ = lo ^ (B); VV = keep_in_group<ST>(VV, v_); lo = v_ * (PL); } while (0)
+#define MMBP_RECORD(VV, KIND, COUNT, UT, UX) do { \
+        const uint32_t tl_ = (uint32_t)(UT), th_ = (uint32_t)((UT) >> 32); \
+        MMBP_STEP(VV, 0, KIND, kP4); \
+        MMBP_STEP(VV, 1, (COUNT) & 0xffu, kP1); \
+        MMBP_STEP(VV, 2, (COUNT) >> 8, kP3); \
+        MMBP_STEP(VV, 3, tl_ & 0xffu, kP1); \
+        MMBP_STEP(VV, 4, (tl_ >> 8) & 0xffu, kP1); \
+        MMBP_STEP(VV, 5, (tl_ >> 16) & 0xffu, kP1); \
+        MMBP_STEP(VV, 6, tl_ >> 24, kP1); \
+        MMBP_STEP(VV, 7, th_, kP4); \
+        MMBP_STEP(VV, 8, (uint32_t)(UX) & 0xffu, kP1); \
+        MMBP_STEP(VV, 9, (uint32_t)(UX) >> 8, kP7); \
+    } while (0)
+    MMBP_RECORD(va, kind1, count1, ut1, ux1);
+    MMBP_RECORD(vb, kind2, count2, ut2, ux2);
+#undef MMBP_RECORD
+#undef MMBP_STEP
+    uint32_t e = (va * c.ph + __umulhi(va, c.pl)) * c.w24 + (vb * c.ph + __umulhi(vb, c.pl)) * c.w;
+    e += dpp_u32<0x114, 0xf>(0u, e);
+    e += dpp_u32<0x118, 0xf>(0u, e);
+    e += dpp_u32<0x142, 0xa>(0u, e);
+    e += dpp_u32<0x143, 0xc>(0u, e);
+    hi = hi * kP48 + (uint32_t)__builtin_amdgcn_readlane((int)e, 63);
+    return ((uint64_t)hi << 32) | lo;
+}
+
 // TRACED = false: the caller asked for no trace records, so none of the code that would store them exists.
 template <bool TRACED = true>
 struct Trace {
@@ -206,6 +248,14 @@ struct Trace {
     }
     __device__ __forceinline__ void other(uint32_t kind, uint32_t count, int64_t t, int64_t x, int lane)
     {
+        if constexpr (!TRACED) {
+            if (run_open) {                      // the open decode run and this record in one go
+                h = fnv_record_pair(h, 0u, run_count, run_t, run_D, kind, count, t, x, hc);
+                run_open = 0;
+                { int two = 2; asm("" : "+v"(two)); len += two; }
+                return;
+            }
+        }
         flush(lane);
         emit(kind, count, t, x, lane);
     }
