@@ -297,13 +297,59 @@ __device__ __forceinline__ uint32_t nearest_sorted(const uint32_t *cu, int sb, i
     return min(up, dn);
 }
 
+// The pruned layout's starts (no tile tables): a prefix sum of the clients' slot counts, 64 clients per step of
+// one wave (a serial walk over the clients is a chain of dependent LDS accesses: with 200 clients it was most
+// of the staging of a small scenario).  Out of line: it runs once per regrouping, and inlined it raised the
+// register pressure of the pass loop.
+__device__ __attribute__((noinline)) void sorted_layout_starts(const Lds &l, int N, int M, int cap, int plimit, int lane)
+{
+    int running = 0, nf = 0;
+    unsigned long long sq = 0;
+    for (int j0 = 0; j0 < M; j0 += kWave) {
+        const int j = j0 + lane;
+        const int n = j < M ? min(max(l.cnt[j], 0), N) : 0;
+        const int slots = ((n + 63) >> 6) * 64;
+        int incl = slots;
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl, off);
+            if (lane >= off) incl += up;
+        }
+        const int start = min(running + incl - slots, plimit);
+        const int end = min(start + slots, plimit);
+        if (j < M) {
+            l.gstart[j] = start;
+            l.chpre[j] = 0; l.upre[j] = 0;
+            for (int q = start >> 6; q < (end >> 6); q++) l.seg_grp[q] = (uint8_t)j;
+        }
+        running += __builtin_amdgcn_readlane(incl, kWave - 1);
+        const bool ok = j < M && n < cap;         // move targets, ascending
+        const unsigned long long m = __ballot(ok);
+        if (ok) l.feas[nf + __popcll(m & ((1ull << lane) - 1ull))] = j;
+        nf += __popcll(m);
+        sq += (unsigned long long)n * (unsigned long long)n;
+    }
+    for (int off = 32; off >= 1; off >>= 1) sq += __shfl_xor(sq, off);
+    if (lane == 0) {
+        const int pos = min(running, plimit);
+        l.gstart[M] = pos;
+        l.chpre[M] = 0; l.upre[M] = 0;
+        l.ctrl->P = pos;
+        l.ctrl->nfeas = nf;
+        l.ctrl->nchunk = 0;
+        l.ctrl->ntask = 0;
+        l.ctrl->pairs_per_scan = ((unsigned long long)N * (unsigned long long)N - sq) / 2ull;
+    }
+}
+
 // Groups the jobs by client and builds the chunk and task tables (all threads; barriers inside).
 template <typename CostT, int BLOCK>
 __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const int32_t *asg, int N, int M, int cap, bool sorted)
 {
     const int tid = threadIdx.x;
     const LdsDims d = lds_dims(N, M, sorted);            // (sorted = the pruned scan: its tables have no entries)
-    if (tid == 0) {
+    if (sorted) {
+        if (tid < kWave) sorted_layout_starts(l, N, M, cap, (int)d.P, tid);
+    } else if (tid == 0) {
         int pos = 0, nf = 0, nch = 0, nu = 0;
         unsigned long long sq = 0;
         for (int g = 0; g < M; g++) {
