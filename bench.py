@@ -92,7 +92,7 @@ def main():
     ap.add_argument("--no-sim", action="store_true", help="skip the simulator and hybrid-pipeline legs")
     ap.add_argument("--no-pruned", action="store_true", help="skip the pruned-scan leg")
     ap.add_argument("--no-large", action="store_true", help="skip the one-large-scenario (multi-workgroup path) leg")
-    ap.add_argument("--only", choices=["headline", "secondary", "sim", "probe"], default=None,
+    ap.add_argument("--only", choices=["headline", "secondary", "sim", "pipeline", "probe"], default=None,
                     help="run one leg only (for profiling a single kernel)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 256 MiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
@@ -109,7 +109,7 @@ def main():
         args.no_cpu_baseline = True
         args.no_pruned = args.no_large = True
         args.no_secondary = args.only != "secondary"
-        args.no_sim = args.only != "sim"
+        args.no_sim = args.only not in ("sim", "pipeline")
 
     import numpy as np
     import torch
@@ -312,55 +312,56 @@ def main():
         arr = torch.from_numpy(w.arrival_us).cuda()
         il = torch.from_numpy(w.in_len).cuda()
         ol = torch.from_numpy(w.out_len).cuda()
-        r = api.run_online_sim(arr, il, ol, w.params)            # warm-up, allocates outputs
-        torch.cuda.synchronize()
-        reps = 5
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        t0 = time.perf_counter()
-        for k in range(reps):
-            evs[k][0].record()
-            api.online_iter_sim(arr, il, ol, w.params, r["finish_us"], r["total_us"], r["busy_slot_us"],
-                                r["n_prefill_iter"], r["n_decode_iter"], r["trace_hash"], r["status"])
-            evs[k][1].record()
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / reps
-        k_s = sum(a.elapsed_time(b) for a, b in evs) / reps / 1e3
-        iters = int(r["n_prefill_iter"].sum().item() + r["n_decode_iter"].sum().item())
-
-        def utilisation():
-            busy = r["busy_slot_us"].double()
-            return float((busy / (w.params["cap"] * r["total_us"].double())).mean().item())
-
-        d = current_facts(facts, "online_sim_kernel", "c5")
-        insts = (d["valu_insts"] + d["salu_insts"]) if d and "valu_insts" in d and "salu_insts" in d else None
-        out["online_sim"] = {"metric": "online sim scenarios/sec", "value": w.S / dt, "unit": "scenarios/s",
-                             "ms_per_call": dt * 1e3, "iterations_per_s": iters / dt,
-                             "workload": "configs[4]: 8192 scenarios x 2048 requests, cap 64",
-                             "dtype": "int64 times, int32 lengths",
-                             "roofline": {"bound": "alu",
-                                          "unit": "T wave-instructions/s (vector + scalar issue; peak = 256 CUs x (1 vector + 1 scalar) "
-                                                  "per clock x 2.4 GHz; one dependent chain per wave, so latency-bound below it)",
-                                          "achieved": (insts / k_s / 1e12) if insts else None,
-                                          "peak": ISSUE_PEAK_WAVE_INSTS / 1e12,
-                                          "frac": (insts / k_s / ISSUE_PEAK_WAVE_INSTS) if insts else None,
-                                          "wave_insts_per_launch": insts,
-                                          "wave_insts_per_simulated_iteration": (insts / iters) if insts else None,
-                                          "traffic": hbm_traffic(d), "traffic_source": d["file"] if d else None,
-                                          "algorithmic_bytes": w.S * w.N * (16 + 8),
-                                          "hbm_gb_per_s_algorithmic": w.S * w.N * 24 / k_s / 1e9,
-                                          "kernel": "online_sim_kernel", "kernel_ms": k_s * 1e3},
-                             "slot_utilisation": {"rule": utilisation()}}
-        # the paper's baseline (prefill first, with / without batched prefill) on the same scenarios
-        for name, pol in (("prefill_first", api.POLICY_PREFILL_FIRST), ("prefill_first_single", api.POLICY_PREFILL_FIRST_SINGLE)):
-            pp = dict(w.params, policy=pol)
-            t0 = time.perf_counter()
-            api.online_iter_sim(arr, il, ol, pp, r["finish_us"], r["total_us"], r["busy_slot_us"],
-                                r["n_prefill_iter"], r["n_decode_iter"], r["trace_hash"], r["status"])
+        if args.only != "pipeline":
+            r = api.run_online_sim(arr, il, ol, w.params)            # warm-up, allocates outputs
             torch.cuda.synchronize()
-            out["online_sim"]["slot_utilisation"][name] = utilisation()
-            out["online_sim"].setdefault("baseline_ms_per_call", {})[name] = (time.perf_counter() - t0) * 1e3
+            reps = 5
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            t0 = time.perf_counter()
+            for k in range(reps):
+                evs[k][0].record()
+                api.online_iter_sim(arr, il, ol, w.params, r["finish_us"], r["total_us"], r["busy_slot_us"],
+                                    r["n_prefill_iter"], r["n_decode_iter"], r["trace_hash"], r["status"])
+                evs[k][1].record()
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            k_s = sum(a.elapsed_time(b) for a, b in evs) / reps / 1e3
+            iters = int(r["n_prefill_iter"].sum().item() + r["n_decode_iter"].sum().item())
 
-        if args.only is None:
+            def utilisation():
+                busy = r["busy_slot_us"].double()
+                return float((busy / (w.params["cap"] * r["total_us"].double())).mean().item())
+
+            d = current_facts(facts, "online_sim_kernel", "c5")
+            insts = (d["valu_insts"] + d["salu_insts"]) if d and "valu_insts" in d and "salu_insts" in d else None
+            out["online_sim"] = {"metric": "online sim scenarios/sec", "value": w.S / dt, "unit": "scenarios/s",
+                                 "ms_per_call": dt * 1e3, "iterations_per_s": iters / dt,
+                                 "workload": "configs[4]: 8192 scenarios x 2048 requests, cap 64",
+                                 "dtype": "int64 times, int32 lengths",
+                                 "roofline": {"bound": "alu",
+                                              "unit": "T wave-instructions/s (vector + scalar issue; peak = 256 CUs x (1 vector + 1 scalar) "
+                                                      "per clock x 2.4 GHz; one dependent chain per wave, so latency-bound below it)",
+                                              "achieved": (insts / k_s / 1e12) if insts else None,
+                                              "peak": ISSUE_PEAK_WAVE_INSTS / 1e12,
+                                              "frac": (insts / k_s / ISSUE_PEAK_WAVE_INSTS) if insts else None,
+                                              "wave_insts_per_launch": insts,
+                                              "wave_insts_per_simulated_iteration": (insts / iters) if insts else None,
+                                              "traffic": hbm_traffic(d), "traffic_source": d["file"] if d else None,
+                                              "algorithmic_bytes": w.S * w.N * (16 + 8),
+                                              "hbm_gb_per_s_algorithmic": w.S * w.N * 24 / k_s / 1e9,
+                                              "kernel": "online_sim_kernel", "kernel_ms": k_s * 1e3},
+                                 "slot_utilisation": {"rule": utilisation()}}
+            # the paper's baseline (prefill first, with / without batched prefill) on the same scenarios
+            for name, pol in (("prefill_first", api.POLICY_PREFILL_FIRST), ("prefill_first_single", api.POLICY_PREFILL_FIRST_SINGLE)):
+                pp = dict(w.params, policy=pol)
+                t0 = time.perf_counter()
+                api.online_iter_sim(arr, il, ol, pp, r["finish_us"], r["total_us"], r["busy_slot_us"],
+                                    r["n_prefill_iter"], r["n_decode_iter"], r["trace_hash"], r["status"])
+                torch.cuda.synchronize()
+                out["online_sim"]["slot_utilisation"][name] = utilisation()
+                out["online_sim"].setdefault("baseline_ms_per_call", {})[name] = (time.perf_counter() - t0) * 1e3
+
+        if args.only in (None, "pipeline"):
             # the paper's offline + online combination on the same lengths, all requests known at t = 0:
             # local search over M = cap clients, then the simulator that runs the assignment as sorted
             # per-client queues with stealing; against it the FCFS simulator on the same requests
@@ -396,7 +397,7 @@ def main():
                 "mean_total_s": {"offline_assignment_then_queues_with_stealing": float(ha["total_us"].double().mean().item()) / 1e6,
                                  "fcfs": float(hf["total_us"].double().mean().item()) / 1e6}}
 
-    if not args.no_sim and args.only is None:
+    if not args.no_sim and args.only in (None, "pipeline"):
         # the paper's own shape (Table "Experiment Settings": 1319 requests, 200 clients, its time model), lengths
         # drawn from the printed means and deviations: baseline policy against offline assignment + online rule
         Sp = 1024
