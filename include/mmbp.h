@@ -193,7 +193,8 @@ int mmbp_local_search(const void *cost, int dtype, int S, int N, int M, int cap,
  * enumerated (the same numbers mmbp_local_search reports), not the smaller number evaluated here.
  * Arguments, workspace and error behaviour as for mmbp_local_search; a scenario that fits one
  * workgroup's LDS is always searched there (each client's costs are kept sorted and the best partner of
- * a request is found by binary search), and more shapes fit than for the full scan, which needs tables
+ * a request is found by binary search, or against all of them where they are few), and more shapes fit
+ * than for the full scan, which needs tables
  * for its tiles: for those the workspace may be NULL although mmbp_workspace_bytes() is not 0.
  */
 int mmbp_local_search_pruned(const void *cost, int dtype, int S, int N, int M, int cap, int max_passes,
