@@ -99,6 +99,8 @@ struct Ctrl {
 
 struct Lds {
     uint32_t *cu, *rowkey;        // rowkey[p]: best swap makespan of the job at p against the critical client
+    uint16_t *rowkey16;           // the pruned scan keeps the low 16 bits of it (same memory, half of it): a filter for the
+                                  // rows that may attain the best value; every use re-checks the value exactly
     uint16_t *job;
     unsigned long long *tasks;    // row unit record | chunk record << 32
     uint32_t *chunks;             // c0/64 | columns (jobs of the client in the chunk) << 10 | b << 19
@@ -130,7 +132,7 @@ __host__ __device__ inline size_t lds_bytes(int N, int M, bool prune)
     const LdsDims d = lds_dims(N, M, prune);
     size_t b = 0;
     b += 4 * d.P;                     // cu
-    b += 4 * d.P;                     // rowkey
+    b += (prune ? 2 : 4) * d.P;       // rowkey (16 bits per row in the pruned scan)
     b += 2 * d.P;                     // job
     b = align_up(b, 16);
     b += 8 * d.T;                     // tasks
@@ -151,7 +153,7 @@ __device__ inline Lds carve(unsigned char *base, int N, int M, bool prune)
     Lds l;
     size_t o = 0;
     l.cu = (uint32_t *)(base + o); o += 4 * d.P;
-    l.rowkey = (uint32_t *)(base + o); o += 4 * d.P;
+    l.rowkey = (uint32_t *)(base + o); l.rowkey16 = (uint16_t *)(base + o); o += (prune ? 2 : 4) * d.P;
     l.job = (uint16_t *)(base + o); o += 2 * d.P;
     o = align_up(o, 16);
     l.tasks = (unsigned long long *)(base + o); o += 8 * d.T;
@@ -377,7 +379,10 @@ __device__ void build_layout(const Lds &l, const CostT *__restrict__ c, const in
     for (int j = tid; j < M; j += BLOCK) l.fillc[j] = 0;
     __syncthreads();
     const int P = l.ctrl->P;
-    for (int p = tid; p < P; p += BLOCK) { l.cu[p] = kPad; l.job[p] = kNoJob; l.rowkey[p] = kInf; }
+    for (int p = tid; p < P; p += BLOCK) {
+        l.cu[p] = kPad; l.job[p] = kNoJob;
+        if (sorted) l.rowkey16[p] = 0xFFFFu; else l.rowkey[p] = kInf;
+    }
     // chunk records: one thread per client
     for (int g = tid; g < M; g += BLOCK) {
         const int n = l.cnt[g];
@@ -520,7 +525,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
         if (reset_rows) {
             const int P = min(ctrl->P, Pmax) & ~63;
             uint4 *rk = reinterpret_cast<uint4 *>(l.rowkey);
-            for (int q = lane; q < (P >> 2); q += kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
+            for (int q = lane; q < (P >> (PRUNE ? 3 : 2)); q += kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
         }
     };
     if (wave == 0) open_pass(SMALLM ? (lane < M ? load32(lane) : 0u) : 0u, true);   // (build_layout ended with a barrier)
@@ -640,7 +645,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                         const uint32_t v = cx[q] != kPad ? swap_value(key[q], lsum[q], oth[q]) : kInf;
                         sbest = min(sbest, v);
                         if (v != kInf) {
-                            l.rowkey[pp] = v;
+                            l.rowkey16[pp] = (uint16_t)v;
                             kbest = min(kbest, ((unsigned long long)v << 32) | ((unsigned long long)l.job[pp] << 16) | (unsigned long long)pp);
                         }
                     }
@@ -655,7 +660,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                     const uint32_t v = swap_value(nearest_sorted(l.cu, sb, sn, cx - (lg - lstar)), lg + lstar, others_max(top, g, astar));
                     sbest = min(sbest, v);
                     if (v != kInf) {
-                        l.rowkey[p] = v;                 // one thread per row: nothing to combine
+                        l.rowkey16[p] = (uint16_t)v;     // one thread per row: nothing to combine
                         kbest = min(kbest, ((unsigned long long)v << 32) | ((unsigned long long)l.job[p] << 16) | (unsigned long long)p);
                     }
                 }
@@ -828,6 +833,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                         __builtin_amdgcn_wave_barrier();
                         const uint4 *cu4 = reinterpret_cast<const uint4 *>(l.cu);
                         const uint4 *rk4 = reinterpret_cast<const uint4 *>(l.rowkey);
+                        const uint2 *rk2 = reinterpret_cast<const uint2 *>(l.rowkey16);
                         const uint2 *job2 = reinterpret_cast<const uint2 *>(l.job);
                         // The early jobs are taken in increasing index order, four at a time, each batch against
                         // every flagged job; the first batch with a partner holds the lowest id (a partner f of an
@@ -860,7 +866,17 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                                 const bool in = q < (P >> 2);
                                 const int g = in ? min((int)l.seg_grp[q >> 4], M - 1) : 0;
                                 const uint4 cc = in ? cu4[q] : make_uint4(kPad, kPad, kPad, kPad);
-                                const uint4 rr = in ? rk4[q] : make_uint4(kInf, kInf, kInf, kInf);
+                                uint4 rr = make_uint4(kInf, kInf, kInf, kInf);
+                                if constexpr (PRUNE) {
+                                    // 16 bits per row: a row whose low bits match is re-checked by the key test below
+                                    // (a candidate of value V passes it, nothing else does), so a chance match costs
+                                    // nothing but its place in the count of flagged rows
+                                    if (in) {
+                                        const uint2 r2 = rk2[q];
+                                        const uint32_t hiV = V & 0xFFFF0000u;
+                                        rr = make_uint4(hiV | (r2.x & 0xFFFFu), hiV | (r2.x >> 16), hiV | (r2.y & 0xFFFFu), hiV | (r2.y >> 16));
+                                    }
+                                } else if (in) rr = rk4[q];
                                 const uint2 jj = in ? job2[q] : uint2{0u, 0u};
                                 const uint32_t dl = l.tdl[g], r1 = l.tr1[g];
                                 const uint32_t pq = (uint32_t)q << 2;
@@ -962,7 +978,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
         __syncthreads();                                 // B2: the scan is complete
         if (wave != 0) {                                 // the waves that now wait put the row minima back to "none"
             uint4 *rk = reinterpret_cast<uint4 *>(l.rowkey);
-            for (int q = tid - kWave; q < (P >> 2); q += BLOCK - kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
+            for (int q = tid - kWave; q < (P >> (PRUNE ? 3 : 2)); q += BLOCK - kWave) rk[q] = make_uint4(kInf, kInf, kInf, kInf);
             continue;
         }
 

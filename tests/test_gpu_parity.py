@@ -94,6 +94,23 @@ def test_ls_bad_scenarios_do_not_disturb_others(oracle):
     compare_ls(g, o, label="bad scenarios")
 
 
+def test_ls_pruned_best_values_ending_in_sixteen_ones(oracle):
+    """The pruned scan keeps 16 bits of every row's best value as a filter for the rows that may attain the best
+    value of the pass; rows it never wrote hold 0xFFFF.  Loads are placed so that many passes have a best value
+    whose low 16 bits are all ones: every such row then passes the filter and must fail the exact test."""
+    rng = np.random.default_rng(5)
+    for (S, M, n, target, slack) in [(600, 3, 9, 65535, 2), (300, 5, 70, 131071, 0), (300, 4, 40, 65535 + 65536 * 3, 1)]:
+        N = M * n
+        cost = rng.integers(0, 25, size=(S, N)).astype(np.int32)
+        assign = np.tile((np.arange(N) % M).astype(np.int32), (S, 1))
+        for j in range(M):                                # job j is on client j: one big job each puts the loads near the target
+            cost[:, j] = target - rng.integers(12 * n - 50, 12 * n + 50, size=S)
+        say(f"ls pruned, best values near {target}: S={S} M={M} n={n}")
+        o = oracle.local_search(cost, assign, M, n + slack, 60, want_log=True)
+        compare_ls(gpu_local_search(cost, assign, M, n + slack, 60, pruned=True), o, label=f"pruned, values near {target}")
+        compare_ls(gpu_local_search(cost, assign, M, n + slack, 60), o, label=f"full scan, values near {target}")
+
+
 def test_ls_large_costs_need_64_bit(oracle):
     """Loads far above 2^31: the exact 64-bit path."""
     rng = np.random.default_rng(8)
