@@ -42,8 +42,10 @@
 //
 // Pruned scan (PRUNE): only the candidates that involve the critical client are looked at (the others
 // cannot lower max_j t_j).  The positions of every client are then kept in ascending order of cu
-// (sorted after each regrouping: one wave per 64-slot segment where no client has more, a bitonic
-// network over the layout otherwise; a swap or a move removes one entry and inserts the other in place),
+// (sorted after each regrouping: one wave per client where no range exceeds 64 positions, a bitonic
+// network over the layout otherwise; a swap or a move removes one entry and inserts the other in place).
+// Its ranges are multiples of 16 positions, not 64, with a few free positions for moves to enter in place, so
+// several small clients share a 64-position segment and the rows' client and load are per lane,
 // and a row's best partner in the critical client is found by binary search: the nearest column at or
 // above x and the nearest below it, i.e. the same key min |y - x| the tile computes, in O(log n)
 // per row instead of one subtraction per column; where that client holds at most kPruneTileCols jobs
@@ -114,13 +116,20 @@ struct Lds {
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr int kPruneGranShift = 4, kPruneGran = 1 << kPruneGranShift;   // positions a client's range is a multiple of (pruned layout)
+constexpr int kPruneSlack = 4;                                          // free positions every client gets when the jobs are regrouped
+
 struct LdsDims {
     size_t P, U, C, T;            // padded positions, row units, column chunks, tasks (upper bounds)
 };
 __host__ __device__ inline LdsDims lds_dims(int N, int M, bool prune)
 {
     LdsDims d;
-    d.P = ((size_t)N + 63u) / 64u * 64u + 64u * (size_t)M;   // multiple of 64: keeps every array 16-byte aligned
+    // multiple of 64: keeps every array 16-byte aligned.  The full scan's clients own whole 64-position segments (a
+    // tile's rows are one client's); the pruned scan's own multiples of kPruneGran positions with at least
+    // kPruneSlack of them free after a regrouping (moves then enter in place), so small clients share a segment.
+    d.P = prune ? ((size_t)N + (size_t)(kPruneSlack + kPruneGran - 1) * (size_t)M + 63u) / 64u * 64u
+                : ((size_t)N + 63u) / 64u * 64u + 64u * (size_t)M;
     d.U = prune ? 0 : d.P / (64u * kRMax) + (size_t)M;       // the pruned scan searches sorted columns: no tile tables
     d.C = prune ? 0 : (size_t)N / kChunk + (size_t)M;
     d.T = d.U * d.C;
@@ -141,7 +150,7 @@ __host__ __device__ inline size_t lds_bytes(int N, int M, bool prune)
     b = align_up(b, 16);
     b += 8 * (size_t)M;               // load
     b += 4 * (size_t)(M + 1) * 8;     // cnt, gstart, fillc, feas, chpre, upre, tdl, tr1
-    b += align_up(d.P / 64 + 1, 16);  // seg_grp
+    b += align_up(d.P / kPruneGran + 1, 16);  // seg_grp (one entry per 64 positions in the full scan, per kPruneGran in the pruned scan)
     b = align_up(b, 16);
     b += sizeof(Ctrl);
     return b;
@@ -169,7 +178,7 @@ __device__ inline Lds carve(unsigned char *base, int N, int M, bool prune)
     l.upre = (int *)(base + o); o += 4 * (size_t)(M + 1);
     l.tdl = (uint32_t *)(base + o); o += 4 * (size_t)(M + 1);
     l.tr1 = (uint32_t *)(base + o); o += 4 * (size_t)(M + 1);
-    l.seg_grp = (uint8_t *)(base + o); o += align_up(d.P / 64 + 1, 16);
+    l.seg_grp = (uint8_t *)(base + o); o += align_up(d.P / kPruneGran + 1, 16);
     o = align_up(o, 16);
     l.ctrl = (Ctrl *)(base + o);
     return l;
@@ -239,14 +248,16 @@ __device__ void sort_groups(const Lds &l, int P, int M)
     const int tid = threadIdx.x;
     int maxcnt = 0;                                      // jobs of the largest client (every thread reads all counts: broadcasts)
     for (int g = 0; g < M; g++) maxcnt = max(maxcnt, l.cnt[g]);
-    if (maxcnt <= kWave) {
-        // No client has more jobs than a wave has lanes, so every client is one segment: a wave sorts a
-        // segment in its registers (21 compare-exchange steps across the lanes) instead of all threads
-        // running the network over the whole layout (about a hundred steps with a barrier each, most of
-        // them over empty positions when clients are many and small).
+    if (maxcnt + kPruneSlack <= kWave) {                 // (a range is its jobs plus at most the slack, rounded up: at most 64 positions)
+        // No client's range has more positions than a wave has lanes: a wave sorts a client's range in
+        // its registers (21 compare-exchange steps across the lanes) instead of all threads running the network
+        // over the whole layout (about a hundred steps with a barrier each, most of them over empty positions
+        // when clients are many and small).
         const int lane = tid & 63;
-        for (int seg = tid >> 6; seg < (P >> 6); seg += BLOCK / kWave) {
-            uint32_t x = l.cu[seg * 64 + lane], jb = l.job[seg * 64 + lane];
+        for (int g = tid >> 6; g < M; g += BLOCK / kWave) {
+            const int base = min(max(l.gstart[g], 0), P), slots = min(max(l.gstart[g + 1], base), P) - base;
+            const bool in = lane < slots;
+            uint32_t x = in ? l.cu[base + lane] : kPad, jb = in ? (uint32_t)l.job[base + lane] : (uint32_t)kNoJob;
             for (int k = 2; k <= kWave; k <<= 1)
                 for (int j = k >> 1; j > 0; j >>= 1) {
                     const uint32_t px = (uint32_t)__shfl_xor((int)x, j), pj = (uint32_t)__shfl_xor((int)jb, j);
@@ -255,8 +266,7 @@ __device__ void sort_groups(const Lds &l, int P, int M)
                     x = sw ? px : x;
                     jb = sw ? pj : jb;
                 }
-            l.cu[seg * 64 + lane] = x;
-            l.job[seg * 64 + lane] = (uint16_t)jb;
+            if (in) { l.cu[base + lane] = x; l.job[base + lane] = (uint16_t)jb; }     // (empty positions sort last: they stay where they were)
         }
         __syncthreads();
         return;
@@ -270,7 +280,7 @@ __device__ void sort_groups(const Lds &l, int P, int M)
                 int i, q;
                 if (j == (k >> 1)) { i = blk * k + off; q = blk * k + (k - 1 - off); }
                 else { i = blk * 2 * j + off; q = i + j; }
-                if (q < P && l.seg_grp[i >> 6] == l.seg_grp[q >> 6]) {
+                if (q < P && l.seg_grp[i >> kPruneGranShift] == l.seg_grp[q >> kPruneGranShift]) {
                     const uint32_t a = l.cu[i], b = l.cu[q];
                     if (a > b) {
                         l.cu[i] = b; l.cu[q] = a;
@@ -310,7 +320,8 @@ __device__ __attribute__((noinline)) void sorted_layout_starts(const Lds &l, int
     for (int j0 = 0; j0 < M; j0 += kWave) {
         const int j = j0 + lane;
         const int n = j < M ? min(max(l.cnt[j], 0), N) : 0;
-        const int slots = ((n + 63) >> 6) * 64;
+        const int room = j < M ? min(max(cap - n, 0), kPruneSlack) : 0;      // (a client never holds more than cap jobs)
+        const int slots = ((n + room + kPruneGran - 1) >> kPruneGranShift) * kPruneGran;
         int incl = slots;
         for (int off = 1; off < kWave; off <<= 1) {
             const int up = __shfl_up(incl, off);
@@ -321,7 +332,7 @@ __device__ __attribute__((noinline)) void sorted_layout_starts(const Lds &l, int
         if (j < M) {
             l.gstart[j] = start;
             l.chpre[j] = 0; l.upre[j] = 0;
-            for (int q = start >> 6; q < (end >> 6); q++) l.seg_grp[q] = (uint8_t)j;
+            for (int q = start >> kPruneGranShift; q < (end >> kPruneGranShift); q++) l.seg_grp[q] = (uint8_t)j;
         }
         running += __builtin_amdgcn_readlane(incl, kWave - 1);
         const bool ok = j < M && n < cap;         // move targets, ascending
@@ -335,7 +346,9 @@ __device__ __attribute__((noinline)) void sorted_layout_starts(const Lds &l, int
         const int pos = min(running, plimit);
         l.gstart[M] = pos;
         l.chpre[M] = 0; l.upre[M] = 0;
-        l.ctrl->P = pos;
+        const int pend = min((pos + 63) & ~63, plimit);  // the layout ends on a whole segment: empty positions after the last client
+        for (int q = pos >> kPruneGranShift; q < (pend >> kPruneGranShift); q++) l.seg_grp[q] = 0;
+        l.ctrl->P = pend;
         l.ctrl->nfeas = nf;
         l.ctrl->nchunk = 0;
         l.ctrl->ntask = 0;
@@ -431,6 +444,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
     int32_t *asg = assign_all + (size_t)s * N;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     constexpr int kWaves = BLOCK / kWave;
+    constexpr int kGrpShift = PRUNE ? kPruneGranShift : 6;   // positions per entry of seg_grp
 
     // ---------------- stage: validation, counts, loads ----------------
     for (int j = tid; j < M; j += BLOCK) { l.load[j] = 0; l.cnt[j] = 0; }
@@ -611,17 +625,18 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                 // Few columns: the tile arithmetic against all of them (two vector instructions per candidate, the
                 // columns read as broadcasts that do not depend on the rows) is shorter than a binary search per
                 // row, which is a chain of dependent LDS reads; two row segments per lane share the column reads
-                // (four would spill under the pruned kernels' register limit).
+                // (four would spill under the pruned kernels' register limit).  A segment may hold several small
+                // clients, so the client and its load are per lane.
                 const int n4 = (sn + 3) >> 2;                  // (the positions after the last column are empty ones: no candidates)
                 for (int base = wave; base < nseg; base += kPruneRows * kWaves) {
                     uint32_t x[kPruneRows], cx[kPruneRows], lsum[kPruneRows], oth[kPruneRows], key[kPruneRows];
 #pragma unroll
                     for (int q = 0; q < kPruneRows; q++) {
-                        const int seg = base + q * kWaves;
-                        const bool on = seg < nseg && (seg < sega || seg >= segb);
-                        const int g = on ? min((int)l.seg_grp[seg], M - 1) : 0;
+                        const int seg = base + q * kWaves, pp = seg * 64 + lane;
+                        const bool on = seg < nseg && (pp < sb || pp >= s1);      // (not the critical client's own positions)
+                        const int g = on ? min((int)l.seg_grp[pp >> kPruneGranShift], M - 1) : 0;
                         const uint32_t lg = load32(g);
-                        cx[q] = on ? l.cu[seg * 64 + lane] : kPad;
+                        cx[q] = on ? l.cu[pp] : kPad;
                         x[q] = cx[q] - (lg - lstar);
                         lsum[q] = lg + lstar;
                         oth[q] = others_max(top, g, astar);
@@ -655,7 +670,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                     if (p >= sb && p < s1) continue;
                     const uint32_t cx = l.cu[p];
                     if (cx == kPad) continue;
-                    const int g = min((int)l.seg_grp[p >> 6], M - 1);
+                    const int g = min((int)l.seg_grp[p >> kPruneGranShift], M - 1);
                     const uint32_t lg = load32(g);
                     const uint32_t v = swap_value(nearest_sorted(l.cu, sb, sn, cx - (lg - lstar)), lg + lstar, others_max(top, g, astar));
                     sbest = min(sbest, v);
@@ -686,9 +701,11 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
             // Moves off the critical client, with their ids (a move that wins is then known without a second
             // look): every wave takes every segment of the client and a slice of the target clients, which
             // keeps all waves busy where clients are many and small.
+            const int mb = min(max(uni(l.gstart[astar]), 0), P), me = min(max(uni(l.gstart[astar + 1]), mb), P);
             if (nfeas > 0)
-                for (int seg = sega; seg < segb; seg++) {
-                    const uint32_t x = l.cu[seg * 64 + lane], jb = l.job[seg * 64 + lane];
+                for (int p0 = mb; p0 < me; p0 += kWave) {                    // (the client's range may end inside a segment)
+                    const bool in = p0 + lane < me;
+                    const uint32_t x = in ? l.cu[p0 + lane] : kPad, jb = in ? (uint32_t)l.job[p0 + lane] : 0u;
                     if (wave == 0) w_cnt += (uint32_t)__popcll(__ballot(x != kPad)) * (uint32_t)(M - 1);
                     const uint32_t ci = (x - kBias) >> 1;
                     const uint32_t la = load32(astar);
@@ -754,10 +771,11 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                     const unsigned long long km = ctrl->kmove;
                     const uint32_t id = uniu((uint32_t)km);
                     const uint32_t ji = id / (uint32_t)M;
+                    const int mb = min(max(uni(l.gstart[astar]), 0), P), me = min(max(uni(l.gstart[astar + 1]), mb), P);
                     if ((uint32_t)(km >> 32) == V)
-                        for (int seg = sega; seg < segb; seg++) {
-                            const int p = seg * 64 + lane;
-                            if (l.cu[p] != kPad && (uint32_t)l.job[p] == ji) best = ((unsigned long long)id << 32) | (unsigned long long)p;
+                        for (int p0 = mb; p0 < me; p0 += kWave) {
+                            const int p = p0 + lane;
+                            if (p < me && l.cu[p] != kPad && (uint32_t)l.job[p] == ji) best = ((unsigned long long)id << 32) | (unsigned long long)p;
                         }
                 } else {
                     // ---- a move wins (move ids are below swap ids): lowest id among moves of value V.  V is
@@ -798,7 +816,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
 
                     // all critical jobs against the flagged job at pf (uniform): every swap of value V
                     auto pair_with = [&](int pf) {
-                        const int g = uni(l.seg_grp[pf >> 6]);
+                        const int g = uni(l.seg_grp[pf >> kGrpShift]);
                         const uint32_t lg = wload(g), jf = uniu(l.job[pf]);
                         const uint32_t xf = uniu(l.cu[pf]) - (lg - lstar);
                         const uint32_t oth = others_max(top, g, astar);
@@ -864,7 +882,7 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
                             for (int q0 = 0; q0 < (P >> 2); q0 += kWave) {
                                 const int q = q0 + lane;                            // positions 4q .. 4q+3 (P % 256 == 0 is not given)
                                 const bool in = q < (P >> 2);
-                                const int g = in ? min((int)l.seg_grp[q >> 4], M - 1) : 0;
+                                const int g = in ? min((int)l.seg_grp[q >> (kGrpShift - 2)], M - 1) : 0;
                                 const uint4 cc = in ? cu4[q] : make_uint4(kPad, kPad, kPad, kPad);
                                 uint4 rr = make_uint4(kInf, kInf, kInf, kInf);
                                 if constexpr (PRUNE) {
@@ -938,13 +956,13 @@ __global__ __launch_bounds__(BLOCK, PRUNE ? 6 : MMBP_LDS_WPE) void ls_lds_kernel
             const int p = (int)(uint32_t)win;
             ap_j0 = (int)(id / (uint32_t)M); ap_g1 = (int)(id % (uint32_t)M);
             if (win == ~0ull || ap_j0 >= N || p >= P) act = kActError;       // cannot happen: the best move was found above
-            else { ap_g0 = uni(l.seg_grp[p >> 6]); ap_x0 = (uniu(l.cu[p]) - kBias) >> 1; }
+            else { ap_g0 = uni(l.seg_grp[p >> kGrpShift]); ap_x0 = (uniu(l.cu[p]) - kBias) >> 1; }
         } else if (act == kActSwap) {
             ap_j0 = (int)(uint32_t)(win >> 48); ap_j1 = (int)((uint32_t)(win >> 32) & 0xFFFFu);                  // j0 < j1
             const int pi = (int)((win >> 16) & 0xFFFFu), pk = (int)(win & 0xFFFFu);
             if (win == ~0ull || ap_j0 >= N || ap_j1 >= N || pi >= P || pk >= P) act = kActError;               // cannot happen
             else {
-                ap_g0 = uni(l.seg_grp[pi >> 6]); ap_g1 = uni(l.seg_grp[pk >> 6]);
+                ap_g0 = uni(l.seg_grp[pi >> kGrpShift]); ap_g1 = uni(l.seg_grp[pk >> kGrpShift]);
                 ap_x0 = uniu(l.cu[pi]); ap_x1 = uniu(l.cu[pk]);
             }
         }
