@@ -45,8 +45,8 @@
 // (sorted after each regrouping: one wave per client where no range exceeds 64 positions, a bitonic
 // network over the layout otherwise; a swap or a move removes one entry and inserts the other in place).
 // Its ranges are multiples of 16 positions, not 64, with a few free positions for moves to enter in place, so
-// several small clients share a 64-position segment and the rows' client and load are per lane,
-// and a row's best partner in the critical client is found by binary search: the nearest column at or
+// several small clients share a 64-position segment and the rows' client and load are per lane.
+// A row's best partner in the critical client is found by binary search: the nearest column at or
 // above x and the nearest below it, i.e. the same key min |y - x| the tile computes, in O(log n)
 // per row instead of one subtraction per column; where that client holds at most kPruneTileCols jobs
 // the rows run the tile arithmetic against all of them instead (no chain of dependent LDS reads).
