@@ -96,6 +96,8 @@ def main():
                     help="run one leg only (for profiling a single kernel)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also launch one plain 256 MiB device copy (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
+    ap.add_argument("--tail-study", action="store_true",
+                    help="with the secondary leg: time its longest scenarios alone and in company (per-scan latency)")
     ap.add_argument("--kernel-hash", action="store_true", help="print the source hashes the profile summaries record, and exit")
     args = ap.parse_args()
     if args.kernel_hash:
@@ -262,6 +264,24 @@ def main():
             "value": sec["value"], "unit": "candidates/s", "ms_per_step": sec["ms_per_step"],
             "mean_passes": sec["mean_passes"], "max_passes_seen": sec["max_passes_seen"],
             "candidates_per_step": sec["total_evals"], "roofline": sec["roofline"]}
+        if args.tail_study:
+            # where this batch loses time: its scenarios with the most passes, alone and in company (one launch each)
+            import dataclasses
+            order = np.argsort(-sec["passes"], kind="stable")
+            study = []
+            for kk in (1, 64, 256, 512, 1024):
+                idx = np.sort(order[:kk])
+                sub = dataclasses.replace(c2, S=kk, cost=c2.cost[idx], assign0=c2.assign0[idx], in_len=c2.in_len[idx],
+                                          out_len=c2.out_len[idx])
+                r = offline_leg(sub, "c2-subset", 5, 1)
+                scans = int(r["passes"].max()) + 1
+                study.append({"scenarios": kk, "kernel_ms": r["roofline"]["kernel_ms"], "scans_of_the_longest": scans,
+                              "us_per_scan_of_the_longest": r["roofline"]["kernel_ms"] * 1e3 / scans,
+                              "scans_total": int(r["passes"].sum()) + kk, "frac": r["roofline"]["frac"]})
+            out["secondary"]["tail_study"] = {
+                "what": "the K scenarios of configs[1] with the most passes, one launch per K (K = 1: the longest scenario "
+                        "alone on the chip; 256: one workgroup per CU; 512: two per CU, all resident; 1024: the whole batch)",
+                "runs": study}
 
     # the same search with the pruned scan (identical results): reported on its own, never mixed
     # into `value` or the roofline, which count evaluated candidates only
